@@ -1,0 +1,160 @@
+/*
+ * marius_hip.h -- C ABI of the MI355X (gfx950) graph-embedding training step.
+ *
+ * One call of mar_train_batch is one iteration of the paper's synchronous training
+ * loop (Alg. 1) with every table resident in device memory: form the batch from edge
+ * ids, evaluate the contrastive loss of Eq. 1 with sampled negatives (Sec. 2.1),
+ * differentiate it, and apply Adagrad (Sec. 5.1, "Hyperparameters") to the touched
+ * node and relation rows.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory owned by the caller; the library never
+ *     allocates or frees device memory and keeps no pointer except the four tables and
+ *     the workspace handed to mar_init_tables.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t cast to void*, NULL = the
+ *     default stream); they do not synchronise.  Scalar results land in device memory.
+ *   - Return value: MAR_OK (0) or a negative MAR_E* code.  Nothing is enqueued when an
+ *     argument check fails.  mar_last_error gives a text for the last failure of the
+ *     calling thread.
+ *   - Node and relation ids are NOT range-checked on the device: ids outside
+ *     [0, num_nodes) / [0, num_rels) are undefined behaviour.
+ *   - Calls on one context must not overlap (one stream at a time): they share the
+ *     workspace.
+ */
+#ifndef MARIUS_HIP_H
+#define MARIUS_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MAR_OK        0
+#define MAR_EINVAL   -1   /* null / misaligned pointer, unknown model, bad count          */
+#define MAR_ERANGE   -2   /* a size is outside what the kernels support                   */
+#define MAR_ENOMEM   -3   /* workspace too small                                          */
+#define MAR_EHIP     -4   /* a HIP runtime call or kernel launch failed                   */
+
+/* Score functions f(theta_s, theta_r, theta_d) (Sec. 2.1). */
+#define MAR_MODEL_DISTMULT 0   /* theta_s^T diag(theta_r) theta_d, as printed in Sec. 2.1             */
+#define MAR_MODEL_COMPLEX  1   /* Re sum_k s_k r_k conj(d_k); row = [re(0..dim/2) | im(0..dim/2)]      */
+#define MAR_MODEL_TRANSE   2   /* -|| s + r - d ||_2                                                   */
+
+#define MAR_MAX_DIM 400        /* largest supported row width in floats                              */
+
+/* Problem statement (Sec. 2.1; hyperparameters of Table 1). */
+typedef struct mar_config {
+  int64_t  num_nodes;           /* |V|; num_nodes + num_rels must be < 2^31                          */
+  int32_t  num_rels;            /* |R| >= 1                                                          */
+  int32_t  dim;                 /* d: floats per row, 1..MAR_MAX_DIM (even for ComplEx)              */
+  int32_t  model;               /* MAR_MODEL_*                                                       */
+  int32_t  batch_size;          /* b: most edges one mar_train_batch call may carry                  */
+  int32_t  num_chunks;          /* the batch is cut into this many contiguous chunks;                */
+                                /* batch_size must be a multiple of num_chunks                       */
+  int32_t  negs_per_chunk;      /* n_t: negatives per chunk and corrupted side, shared by the chunk  */
+  int32_t  deg_negs_per_chunk;  /* round(alpha_nt * n_t): how many of them are drawn by degree       */
+  float    lr;                  /* Adagrad learning rate                                             */
+  float    eps;                 /* Adagrad epsilon, added outside the square root                    */
+  float    init_std;            /* standard deviation of the N(0, std^2) initialisation              */
+  uint64_t seed;                /* key of the counter-based generator                                */
+} mar_config;
+
+typedef struct mar_ctx mar_ctx;  /* opaque: host-side metadata only */
+
+/* Optional per-step outputs for checking a step against a reference.  Every member
+ * is a device pointer and may be NULL.  Capacities: uniq_* and grad_rows hold up to
+ * min(num_nodes + num_rels, 3*batch_size + 2*num_chunks*negs_per_chunk) rows. */
+typedef struct mar_debug_out {
+  int32_t* num_uniq;    /* [2]: number of unique touched nodes, unique touched relations            */
+  int32_t* uniq_nodes;  /* ascending unique node ids                                                */
+  int32_t* uniq_rels;   /* ascending unique relation ids                                            */
+  float*   pos;         /* [n_edges] positive scores f(e)                                           */
+  float*   lse_dst;     /* [n_edges] log sum_j exp f(s, r, n_j)  (destination corrupted)            */
+  float*   lse_src;     /* [n_edges] log sum_j exp f(m_j, r, d)  (source corrupted)                 */
+  float*   grad_rows;   /* [(num_uniq[0] + num_uniq[1]) * dim] summed gradient of the batch loss    */
+                        /* per unique row: nodes in uniq_nodes order, then relations                */
+} mar_debug_out;
+
+/* Bytes of device workspace a context for `cfg` needs.  Host only. */
+int mar_workspace_bytes(const mar_config* cfg, size_t* out_bytes);
+
+/*
+ * Creates a context over caller-owned tables (Sec. 2.1: d(|V| + |R|) parameters; Sec. 5.1:
+ * Adagrad keeps one accumulator per parameter).
+ *   node_emb, node_state : device, [num_nodes * dim] floats, row-major, 16-byte aligned
+ *   rel_emb,  rel_state  : device, [num_rels  * dim] floats
+ *   workspace            : device, >= mar_workspace_bytes, 256-byte aligned; owned by the
+ *                          caller, used by every later call until mar_destroy
+ *   fill                 : 1 = embeddings ~ N(0, init_std^2) from the counter-based
+ *                          generator (key = seed), accumulators = 0; 0 = adopt contents
+ * The context is returned in *out.
+ */
+int mar_init_tables(const mar_config* cfg, float* node_emb, float* node_state,
+                    float* rel_emb, float* rel_state, void* workspace, size_t workspace_bytes,
+                    int fill, void* hip_stream, mar_ctx** out);
+
+/*
+ * Draws the negative node ids of training step `step` (Sec. 2.1: negative sampling; Table 1:
+ * alpha_nt): for each chunk c and each side, negs_per_chunk ids; the first
+ * deg_negs_per_chunk are the matching endpoint of a uniformly drawn edge of the given edge
+ * list (degree-proportional), the rest uniform over [0, num_nodes).  Ids depend only on
+ * (seed, step, side, chunk, slot) through Philox4x32-10 and a 64-bit multiply-high.
+ *   edge_src, edge_dst : device, [num_edges] int32 (may be NULL when deg_negs_per_chunk = 0)
+ *   neg_src, neg_dst   : device, out, [num_chunks * negs_per_chunk] int32: ids that replace
+ *                        the source / the destination
+ */
+int mar_sample_negatives(mar_ctx* ctx, uint64_t step, const int32_t* edge_src, const int32_t* edge_dst,
+                         int64_t num_edges, int32_t* neg_src, int32_t* neg_dst, void* hip_stream);
+
+/*
+ * One training step on edges (src[i], rel[i], dst[i]), i < n_edges <= batch_size (Alg. 1 body;
+ * loss: Eq. 1 with the log term over the sampled negatives of the edge's chunk, once per
+ * corrupted side; optimiser: Adagrad, one update per touched row with the gradient summed
+ * over all of the row's occurrences).  Chunk c covers edges [c*S, (c+1)*S), S =
+ * batch_size / num_chunks; a short batch uses the first ceil(n_edges / S) chunks.
+ *   src, rel, dst    : device, [n_edges] int32
+ *   neg_src, neg_dst : device, [num_chunks * negs_per_chunk] int32
+ *   loss_sum_out     : device, 1 float: the loss summed over the batch (may be NULL)
+ *   dbg              : host pointer to a struct of device pointers, or NULL
+ */
+int mar_train_batch(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const int32_t* dst,
+                    int32_t n_edges, const int32_t* neg_src, const int32_t* neg_dst,
+                    float* loss_sum_out, const mar_debug_out* dbg, void* hip_stream);
+
+/*
+ * Link-prediction scores (Sec. 5.1, "Evaluation Task and Metrics"): the positive score of
+ * each edge and its rank among the chunk's negatives per corrupted side, rank = 1 + number
+ * of negatives scoring strictly higher.  Tables are not modified.
+ *   pos_scores : device, out, [n_edges] float (may be NULL)
+ *   rank_dst, rank_src : device, out, [n_edges] int32
+ */
+int mar_eval_scores(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const int32_t* dst,
+                    int32_t n_edges, const int32_t* neg_src, const int32_t* neg_dst,
+                    float* pos_scores, int32_t* rank_dst, int32_t* rank_src, void* hip_stream);
+
+/*
+ * Per-phase device timing of mar_train_batch with HIP events on the call's stream.
+ * Phases: 0 index build (unique set, occurrence order), 1 row gather and operand build,
+ * 2 score + softmax + gradient w.r.t. the edge side (MFMA), 3 gradient w.r.t. the
+ * negatives (MFMA), 4 chain rule, 5 per-row reduce + Adagrad scatter.
+ * mar_profile_enable(ctx, max_steps) starts recording (max_steps <= 4096; 0 stops);
+ * mar_profile_read synchronises with the recorded events, adds each phase's elapsed
+ * milliseconds over the recorded steps into ms[MAR_NUM_PHASES], reports how many steps
+ * were recorded, and resets the recording.
+ */
+#define MAR_NUM_PHASES 6
+int mar_profile_enable(mar_ctx* ctx, int32_t max_steps);
+int mar_profile_read(mar_ctx* ctx, double* ms, int32_t* steps);
+
+/* Releases the host-side context (device memory stays with the caller). */
+int mar_destroy(mar_ctx* ctx);
+
+/* Text of the calling thread's most recent failure ("" if none).  ctx may be NULL. */
+const char* mar_last_error(const mar_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MARIUS_HIP_H */

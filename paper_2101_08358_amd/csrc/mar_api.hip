@@ -1,0 +1,278 @@
+// C ABI of the training-step library: argument checks, workspace carve-up, launch order.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <new>
+
+#include "mar_common.h"
+
+static thread_local char g_err[512] = "";
+
+void mar_set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+extern "C" const char* mar_last_error(const mar_ctx*) { return g_err; }
+
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static int hip_fail(hipError_t e, const char* what) {
+  return fail(MAR_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ------------------------------------------------------------------ configuration -----
+static int check_config(const mar_config* cfg, MarDims* d) {
+  if (!cfg) return fail(MAR_EINVAL, "config is NULL");
+  if (cfg->num_nodes < 1 || cfg->num_rels < 1) return fail(MAR_EINVAL, "num_nodes and num_rels must be >= 1");
+  if (cfg->num_nodes + (int64_t)cfg->num_rels >= ((int64_t)1 << 31))
+    return fail(MAR_ERANGE, "num_nodes + num_rels must be below 2^31");
+  if (cfg->model < MAR_MODEL_DISTMULT || cfg->model > MAR_MODEL_TRANSE) return fail(MAR_EINVAL, "unknown model %d", cfg->model);
+  if (cfg->dim < 1 || cfg->dim > MAR_MAX_DIM) return fail(MAR_ERANGE, "dim %d outside 1..%d", cfg->dim, MAR_MAX_DIM);
+  if (cfg->model == MAR_MODEL_COMPLEX && (cfg->dim & 1)) return fail(MAR_EINVAL, "ComplEx needs an even dim");
+  if (cfg->batch_size < 1 || cfg->num_chunks < 1 || cfg->negs_per_chunk < 1)
+    return fail(MAR_EINVAL, "batch_size, num_chunks and negs_per_chunk must be >= 1");
+  if (cfg->batch_size % cfg->num_chunks) return fail(MAR_ERANGE, "batch_size must be a multiple of num_chunks");
+  if (cfg->deg_negs_per_chunk < 0 || cfg->deg_negs_per_chunk > cfg->negs_per_chunk)
+    return fail(MAR_EINVAL, "deg_negs_per_chunk outside 0..negs_per_chunk");
+  if (!(cfg->lr > 0.f) || !(cfg->eps >= 0.f)) return fail(MAR_EINVAL, "lr must be > 0 and eps >= 0");
+  const int64_t cn = (int64_t)cfg->num_chunks * cfg->negs_per_chunk;
+  const int64_t n_occ = 3 * (int64_t)cfg->batch_size + 2 * cn;
+  if (n_occ >= ((int64_t)1 << 30)) return fail(MAR_ERANGE, "batch too large: 3*batch_size + 2*chunks*negatives must be below 2^30");
+  d->dim = cfg->dim;
+  d->dk = (cfg->dim + 3) & ~3;
+  d->B = cfg->batch_size; d->C = cfg->num_chunks; d->S = cfg->batch_size / cfg->num_chunks;
+  d->N = cfg->negs_per_chunk; d->Ndeg = cfg->deg_negs_per_chunk;
+  d->num_nodes = cfg->num_nodes; d->num_rels = cfg->num_rels;
+  d->n_occ_max = n_occ;
+  const int64_t ids = cfg->num_nodes + cfg->num_rels;
+  d->u_max = ids < n_occ ? ids : n_occ;
+  d->nwords = (ids + 31) / 32;
+  if (!mar_flash_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the contraction kernels", d->dk);
+  return MAR_OK;
+}
+
+// Carves the workspace; with base == NULL only measures.
+static size_t carve(const MarDims& d, char* base, MarLayout* L) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> void* {
+    void* p = base ? base + off : nullptr;
+    off += (bytes + 255) & ~(size_t)255;
+    return p;
+  };
+  const size_t n_occ = (size_t)d.n_occ_max, u1 = (size_t)d.u_max + 1;
+  const size_t B = d.B, CN = (size_t)d.C * d.N, dk = d.dk;
+  const size_t scan_elems = (size_t)d.nwords > u1 ? (size_t)d.nwords : u1;
+  const size_t tasks = (n_occ + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
+  MarLayout l;
+  l.scalars = (int32_t*)take(16 * 4);
+  l.bitmap = (uint32_t*)take((size_t)d.nwords * 4);
+  l.word_prefix = (uint32_t*)take((size_t)d.nwords * 4);
+  l.bsum = (uint32_t*)take((scan_elems / 4096 + 2) * 4);
+  l.uniq = (int32_t*)take(u1 * 4);
+  l.count = (uint32_t*)take(u1 * 4);
+  l.seg_off = (uint32_t*)take((u1 + 1) * 4);
+  l.inv = (int32_t*)take(n_occ * 4);
+  l.slot = (int32_t*)take(n_occ * 4);
+  l.occ_pos = (int32_t*)take(n_occ * 4);
+  l.rank_sorted = (int32_t*)take(n_occ * 4);
+  l.Q = (float*)take(2 * B * dk * 4);
+  l.Km = (float*)take(2 * CN * dk * 4);
+  l.qq = (float*)take(2 * B * 4);
+  l.kk = (float*)take(2 * CN * 4);
+  l.pos = (float*)take(B * 4);
+  l.lse = (float*)take(2 * B * 4);
+  l.gQ = (float*)take(2 * B * dk * 4);
+  l.G = (float*)take(n_occ * dk * 4);
+  l.carry = (float*)take(tasks * 2 * dk * 4);
+  l.loss_part = (float*)take((B / 4 + 2) * 4);
+  l.rank_tmp = (int32_t*)take(2 * B * 4);
+  if (L) *L = l;
+  return off;
+}
+
+extern "C" int mar_workspace_bytes(const mar_config* cfg, size_t* out_bytes) {
+  MarDims d;
+  const int rc = check_config(cfg, &d);
+  if (rc) return rc;
+  if (!out_bytes) return fail(MAR_EINVAL, "out_bytes is NULL");
+  *out_bytes = carve(d, nullptr, nullptr);
+  return MAR_OK;
+}
+
+extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* node_state, float* rel_emb,
+                               float* rel_state, void* workspace, size_t workspace_bytes, int fill,
+                               void* hip_stream, mar_ctx** out) {
+  MarDims d;
+  const int rc = check_config(cfg, &d);
+  if (rc) return rc;
+  if (!out) return fail(MAR_EINVAL, "out is NULL");
+  if (!node_emb || !node_state || !rel_emb || !rel_state) return fail(MAR_EINVAL, "a table pointer is NULL");
+  if (((uintptr_t)node_emb | (uintptr_t)node_state | (uintptr_t)rel_emb | (uintptr_t)rel_state) & 15)
+    return fail(MAR_EINVAL, "table pointers must be 16-byte aligned");
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(MAR_EINVAL, "workspace must be non-NULL and 256-byte aligned");
+  const size_t need = carve(d, nullptr, nullptr);
+  if (workspace_bytes < need) return fail(MAR_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  mar_ctx* c = new (std::nothrow) mar_ctx();
+  if (!c) return fail(MAR_ENOMEM, "out of host memory");
+  c->cfg = *cfg; c->dm = d;
+  c->node_emb = node_emb; c->node_state = node_state; c->rel_emb = rel_emb; c->rel_state = rel_state;
+  c->workspace = workspace; c->workspace_bytes = workspace_bytes;
+  carve(d, (char*)workspace, &c->L);
+  c->bitmap_dirty = 0; c->prof_max = 0; c->prof_steps = 0; c->prof_events = nullptr;
+  const hipError_t e = mar_launch_init(c, fill, (hipStream_t)hip_stream);
+  if (e != hipSuccess) { delete c; return hip_fail(e, "init kernels"); }
+  *out = c;
+  return MAR_OK;
+}
+
+extern "C" int mar_destroy(mar_ctx* c) {
+  if (!c) return MAR_OK;
+  if (c->prof_events) {
+    for (int i = 0; i < c->prof_max * (MAR_NUM_PHASES + 1); ++i) (void)hipEventDestroy(c->prof_events[i]);
+    free(c->prof_events);
+  }
+  delete c;
+  return MAR_OK;
+}
+
+extern "C" int mar_sample_negatives(mar_ctx* c, uint64_t step, const int32_t* edge_src, const int32_t* edge_dst,
+                                    int64_t num_edges, int32_t* neg_src, int32_t* neg_dst, void* hip_stream) {
+  if (!c) return fail(MAR_EINVAL, "context is NULL");
+  if (!neg_src || !neg_dst) return fail(MAR_EINVAL, "an output pointer is NULL");
+  if (step >> 63) return fail(MAR_ERANGE, "step must be below 2^63");
+  if (c->dm.Ndeg > 0) {
+    if (!edge_src || !edge_dst) return fail(MAR_EINVAL, "degree-based negatives need the edge list");
+    if (num_edges < 1) return fail(MAR_EINVAL, "degree-based negatives need num_edges >= 1");
+  }
+  if (num_edges < 0) return fail(MAR_EINVAL, "num_edges is negative");
+  const hipError_t e = mar_launch_sample(c, step, edge_src, edge_dst, num_edges, neg_src, neg_dst, (hipStream_t)hip_stream);
+  return e == hipSuccess ? MAR_OK : hip_fail(e, "sampling kernel");
+}
+
+static int make_batch(const mar_ctx* c, const int32_t* src, const int32_t* rel, const int32_t* dst, int32_t n,
+                      const int32_t* neg_src, const int32_t* neg_dst, MarBatch* b) {
+  if (!c) return fail(MAR_EINVAL, "context is NULL");
+  if (n < 0 || n > c->dm.B) return fail(MAR_ERANGE, "n_edges %d outside 0..batch_size %d", n, c->dm.B);
+  if (n > 0 && (!src || !rel || !dst || !neg_src || !neg_dst)) return fail(MAR_EINVAL, "an id array is NULL");
+  b->src = src; b->rel = rel; b->dst = dst; b->neg_src = neg_src; b->neg_dst = neg_dst;
+  b->n = n;
+  b->nchunks = (n + c->dm.S - 1) / c->dm.S;
+  b->cn = b->nchunks * c->dm.N;
+  b->n_occ = 3 * (int64_t)n + 2 * (int64_t)b->cn;
+  return MAR_OK;
+}
+
+#define HIP_TRY(expr, what) do { const hipError_t e_ = (expr); if (e_ != hipSuccess) { c->bitmap_dirty = 1; return hip_fail(e_, what); } } while (0)
+
+extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* rel, const int32_t* dst, int32_t n_edges,
+                               const int32_t* neg_src, const int32_t* neg_dst, float* loss_sum_out,
+                               const mar_debug_out* dbg, void* hip_stream) {
+  MarBatch b;
+  const int rc = make_batch(c, src, rel, dst, n_edges, neg_src, neg_dst, &b);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (n_edges == 0) {
+    if (loss_sum_out) HIP_TRY(mar_launch_fill_u32((uint32_t*)loss_sum_out, 1, 0u, st), "loss reset");
+    if (dbg && dbg->num_uniq) HIP_TRY(mar_launch_fill_u32((uint32_t*)dbg->num_uniq, 2, 0u, st), "debug reset");
+    return MAR_OK;
+  }
+  if (c->bitmap_dirty) {
+    HIP_TRY(mar_launch_clear_bitmap(c, st), "bitmap reset");
+    c->bitmap_dirty = 0;
+  }
+  hipEvent_t* ev = nullptr;
+  if (c->prof_events && c->prof_steps < c->prof_max) ev = c->prof_events + (size_t)c->prof_steps * (MAR_NUM_PHASES + 1);
+  int evi = 0;
+#define MARK() do { if (ev) HIP_TRY(hipEventRecord(ev[evi++], st), "event record"); } while (0)
+  MARK();
+  HIP_TRY(mar_launch_index(c, b, st), "index kernels");
+  if (dbg) HIP_TRY(mar_launch_debug_copy(c, b, dbg, st), "debug copy");
+  MARK();
+  HIP_TRY(mar_launch_prep(c, b, 1, dbg ? dbg->pos : nullptr, st), "gather kernel");
+  MARK();
+  HIP_TRY(mar_launch_flash(c, b, 1, nullptr, nullptr, st), "score/softmax kernel");
+  MARK();
+  HIP_TRY(mar_launch_flash(c, b, 2, nullptr, nullptr, st), "negative-gradient kernel");
+  MARK();
+  HIP_TRY(mar_launch_chain(c, b, st), "chain-rule kernel");
+  MARK();
+  HIP_TRY(mar_launch_reduce(c, b, loss_sum_out, dbg ? dbg->grad_rows : nullptr, st), "reduce/Adagrad kernels");
+  MARK();
+#undef MARK
+  if (ev) c->prof_steps++;
+  if (dbg) {
+    const size_t nb = (size_t)n_edges * sizeof(float);
+    if (dbg->lse_dst) HIP_TRY(hipMemcpyAsync(dbg->lse_dst, c->L.lse + (size_t)MAR_SIDE_DST * c->dm.B, nb, hipMemcpyDeviceToDevice, st), "debug copy");
+    if (dbg->lse_src) HIP_TRY(hipMemcpyAsync(dbg->lse_src, c->L.lse + (size_t)MAR_SIDE_SRC * c->dm.B, nb, hipMemcpyDeviceToDevice, st), "debug copy");
+  }
+  return MAR_OK;
+}
+
+extern "C" int mar_eval_scores(mar_ctx* c, const int32_t* src, const int32_t* rel, const int32_t* dst, int32_t n_edges,
+                               const int32_t* neg_src, const int32_t* neg_dst, float* pos_scores, int32_t* rank_dst,
+                               int32_t* rank_src, void* hip_stream) {
+  MarBatch b;
+  const int rc = make_batch(c, src, rel, dst, n_edges, neg_src, neg_dst, &b);
+  if (rc) return rc;
+  if (!rank_dst || !rank_src) return fail(MAR_EINVAL, "a rank output pointer is NULL");
+  if (n_edges == 0) return MAR_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  HIP_TRY(mar_launch_prep(c, b, 0, pos_scores, st), "gather kernel");
+  HIP_TRY(mar_launch_flash(c, b, 3, rank_dst, rank_src, st), "rank kernel");
+  return MAR_OK;
+}
+
+// ----------------------------------------------------------------------- profiling -----
+extern "C" int mar_profile_enable(mar_ctx* c, int32_t max_steps) {
+  if (!c) return fail(MAR_EINVAL, "context is NULL");
+  if (max_steps < 0 || max_steps > MAR_MAX_PROFILE_STEPS) return fail(MAR_ERANGE, "max_steps outside 0..%d", MAR_MAX_PROFILE_STEPS);
+  if (c->prof_events) {
+    for (int i = 0; i < c->prof_max * (MAR_NUM_PHASES + 1); ++i) (void)hipEventDestroy(c->prof_events[i]);
+    free(c->prof_events);
+    c->prof_events = nullptr;
+  }
+  c->prof_max = 0; c->prof_steps = 0;
+  if (max_steps == 0) return MAR_OK;
+  const size_t ne = (size_t)max_steps * (MAR_NUM_PHASES + 1);
+  c->prof_events = (hipEvent_t*)calloc(ne, sizeof(hipEvent_t));
+  if (!c->prof_events) return fail(MAR_ENOMEM, "out of host memory");
+  for (size_t i = 0; i < ne; ++i) {
+    const hipError_t e = hipEventCreate(&c->prof_events[i]);
+    if (e != hipSuccess) {
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(c->prof_events[j]);
+      free(c->prof_events); c->prof_events = nullptr;
+      return hip_fail(e, "event create");
+    }
+  }
+  c->prof_max = max_steps;
+  return MAR_OK;
+}
+
+extern "C" int mar_profile_read(mar_ctx* c, double* ms, int32_t* steps) {
+  if (!c || !ms || !steps) return fail(MAR_EINVAL, "an argument is NULL");
+  for (int p = 0; p < MAR_NUM_PHASES; ++p) ms[p] = 0.0;
+  *steps = c->prof_steps;
+  for (int s = 0; s < c->prof_steps; ++s) {
+    hipEvent_t* ev = c->prof_events + (size_t)s * (MAR_NUM_PHASES + 1);
+    hipError_t e = hipEventSynchronize(ev[MAR_NUM_PHASES]);
+    if (e != hipSuccess) return hip_fail(e, "event synchronize");
+    for (int p = 0; p < MAR_NUM_PHASES; ++p) {
+      float t = 0.f;
+      e = hipEventElapsedTime(&t, ev[p], ev[p + 1]);
+      if (e != hipSuccess) return hip_fail(e, "event elapsed time");
+      ms[p] += t;
+    }
+  }
+  c->prof_steps = 0;
+  return MAR_OK;
+}

@@ -1,0 +1,89 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/marius_hip.h"
+
+// Side index of a corrupted endpoint; also the generator's "side" counter bit.
+#define MAR_SIDE_SRC 0   // negatives replace the source
+#define MAR_SIDE_DST 1   // negatives replace the destination
+
+// Workspace carve-up (device pointers).
+struct MarLayout {
+  int32_t*  scalars;      // [16]: 0 = unique rows (nodes + relations), 1 = unique nodes
+  uint32_t* bitmap;       // one bit per unified id (node id, or num_nodes + relation id)
+  uint32_t* word_prefix;  // set bits before each bitmap word
+  uint32_t* bsum;         // scan scratch (block sums)
+  int32_t*  uniq;         // ascending unified ids of the touched rows
+  uint32_t* count;        // occurrences per unique row (u_max + 1, last stays 0)
+  uint32_t* seg_off;      // exclusive scan of count: start of each row's segment
+  int32_t*  inv;          // occurrence -> rank of its row among the unique rows
+  int32_t*  slot;         // occurrence -> index inside its row's segment
+  int32_t*  occ_pos;      // occurrence -> position in row-sorted order
+  int32_t*  rank_sorted;  // position -> rank
+  float*    Q;            // [2][batch][dk] edge-side operands (side-major)
+  float*    Km;           // [2][chunks][N][dk] gathered negative rows
+  float*    qq;           // [2][batch] squared norms of Q rows (TransE)
+  float*    kk;           // [2][chunks*N] squared norms of Km rows (TransE)
+  float*    pos;          // [batch] positive scores
+  float*    lse;          // [2][batch] log-sum-exp per edge and side
+  float*    gQ;           // [2][batch][dk] gradient w.r.t. Q rows
+  float*    G;            // [n_occ][dk] one gradient row per occurrence, in row-sorted order
+  float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders
+  float*    loss_part;    // per-block partial loss sums
+  int32_t*  rank_tmp;     // [2][batch] scratch ranks when the caller passes none
+};
+
+struct MarDims {
+  int32_t dim, dk;                 // row width and its multiple-of-4 padding
+  int32_t B, C, S, N, Ndeg;
+  int64_t num_nodes; int32_t num_rels;
+  int64_t n_occ_max;               // 3B + 2CN
+  int64_t u_max;                   // min(num_nodes + num_rels, n_occ_max)
+  int64_t nwords;                  // bitmap words
+};
+
+#define MAR_MAX_PROFILE_STEPS 4096
+
+struct mar_ctx {
+  mar_config cfg;
+  MarDims dm;
+  float *node_emb, *node_state, *rel_emb, *rel_state;
+  void* workspace; size_t workspace_bytes;
+  MarLayout L;
+  int bitmap_dirty;                // a failed step may leave bits set
+  // profiling
+  int32_t prof_max, prof_steps;
+  hipEvent_t* prof_events;         // (MAR_NUM_PHASES + 1) per step
+};
+
+void mar_set_error(const char* fmt, ...);
+
+// Sizes of the reduce kernel's work split.
+#define MAR_TASK_ROWS 64           // occurrence rows per wave task
+
+// ---- launchers (each returns a hipError_t from the launch) --------------------------
+hipError_t mar_launch_init(const mar_ctx* c, int fill, hipStream_t st);
+hipError_t mar_launch_sample(const mar_ctx* c, uint64_t step, const int32_t* es, const int32_t* ed,
+                             int64_t num_edges, int32_t* neg_src, int32_t* neg_dst, hipStream_t st);
+hipError_t mar_launch_clear_bitmap(const mar_ctx* c, hipStream_t st);
+hipError_t mar_launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
+
+struct MarBatch {
+  const int32_t *src, *rel, *dst, *neg_src, *neg_dst;
+  int32_t n;        // edges
+  int32_t nchunks;  // ceil(n / S)
+  int32_t cn;       // nchunks * N
+  int64_t n_occ;    // 3n + 2cn
+};
+
+hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st);
+hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, int train, float* pos_out, hipStream_t st);
+hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32_t* rank_dst, int32_t* rank_src,
+                            hipStream_t st);
+hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st);
+hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st);
+hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
+int mar_flash_supported(int dk);

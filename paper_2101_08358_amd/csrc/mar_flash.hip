@@ -1,0 +1,287 @@
+// Score block, softmax and its two gradient contractions on the matrix cores (gfx950).
+//
+// For one chunk and one corrupted side the positives' operands Q (n_e x d) meet the chunk's
+// shared negatives K (N x d): scores A = Q K^T (Sec. 2.1: every edge against the sampled
+// negatives), log-sum-exp per edge (Eq. 1's log term), and with P = softmax rows
+//     gQ = P K   (gradient w.r.t. the edge-side operand)        -- pass 1, online softmax
+//     gK = P^T Q (gradient w.r.t. the negatives' rows)          -- pass 2, needs the final lse
+// The score block is never written to memory.  Both passes are the same loop: a wave owns 16
+// "stationary" rows x (Q rows in pass 1, K rows in pass 2) whose fragments stay in registers,
+// and streams tiles of the other matrix Y through LDS:
+//     T[y][x]   = sum_k Y[y][k] X[x][k]              v_mfma_f32_16x16x4_f32, lane <-> x
+//     W[y][x]   = exp(T - max) or exp(T - lse[y])    in the accumulator registers
+//     O^T[c][x] += sum_y Y[y][c] W[y][x]             the accumulator layout of T is exactly the
+//                                                    B-operand layout the second product needs
+// so every per-x quantity (running max, running sum, rescale factor) is per lane.
+// Pass 3 (evaluation) only counts negatives scoring above the positive.
+// TransE uses |q - n|^2 = |q|^2 + |n|^2 - 2 q.n for the scores and W = P / distance.
+#include "mar_common.h"
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct FlashArgs {
+  const float* X;      // stationary matrix, rows of dk floats
+  const float* Y;      // streamed matrix
+  const float* xx;     // squared row norms (TransE)
+  const float* yy;
+  float* lse;          // [2][B]: written by pass 1, read by pass 2
+  const float* pos;    // [B] positive scores (pass 3)
+  float* out;          // pass 1: gQ rows [2][B][dk]; pass 2: gradient rows G
+  const int32_t* rowmap;  // pass 2: occ_pos of the negatives' occurrences
+  int32_t* rank_dst; int32_t* rank_src;   // pass 3
+  int32_t n, B, C, N, S, cn, nchunks, dk, nstripes;
+};
+
+__device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+template <int NK>
+struct FlashGeom {
+  static constexpr int KW = 4 * NK;                                  // tile width in floats
+  static constexpr int PITCH = (KW % 8 == 4) ? KW : KW + 4;          // LDS row pitch: 4 mod 8
+  static constexpr int N16 = NK / 4;                                  // k groups of 16 (b128 reads)
+  static constexpr int NT = NK % 4;                                   // remaining k groups of 4
+};
+
+// PASS: 1 online softmax + gQ, 2 gK with given lse, 3 rank counts.  L2: TransE scores.
+template <int NK, int NC, int TY, int PASS, int L2>
+__global__ void __launch_bounds__(256)
+k_flash(FlashArgs a) {
+  typedef FlashGeom<NK> GM;
+  constexpr int PITCH = GM::PITCH;
+  constexpr int NU = (TY * NK + 255) / 256;              // float4 units staged per thread
+  __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
+  __shared__ float aux[TY];                               // per streamed row: lse (pass 2)
+  __shared__ float auy[TY];                               // per streamed row: squared norm (TransE)
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, m = lane & 15;
+
+  // workgroup -> (chunk-side, stripe); consecutive workgroup ids rotate over the 8 XCDs, so all
+  // stripes of one chunk-side are given ids with the same residue and share one L2.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int cs = (slot / a.nstripes) * 8 + xcd;
+  const int stripe = slot % a.nstripes;
+  if (cs >= 2 * a.nchunks) return;
+  const int side = cs & 1, c = cs >> 1;
+  const int ne = min(a.S, a.n - c * a.S);                 // edges in this chunk
+  const int n_x = PASS == 2 ? a.N : ne;
+  const int n_y = PASS == 2 ? ne : a.N;
+  if (stripe * 64 >= n_x) return;
+  const size_t q_base = (size_t)side * a.B + (size_t)c * a.S;       // first Q row of the chunk
+  const size_t k_base = (size_t)side * a.C * a.N + (size_t)c * a.N; // first K row of the chunk
+  const size_t x_base = PASS == 2 ? k_base : q_base;
+  const size_t y_base = PASS == 2 ? q_base : k_base;
+  const int dk = a.dk;
+
+  // ---- stationary fragments: xf[4s+i] = X[x][16s + 4g + i], tail xf[4*N16+j] = X[x][16*N16 + 4j + g]
+  const int x = stripe * 64 + wave * 16 + m;
+  const bool xv = x < n_x;
+  const float* xrow = a.X + (x_base + (xv ? x : 0)) * dk;
+  float xf[NK];
+#pragma unroll
+  for (int s = 0; s < GM::N16; ++s) {
+    const int col = 16 * s + 4 * g;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (xv && col < dk) v = *reinterpret_cast<const float4*>(xrow + col);
+    xf[4 * s + 0] = v.x; xf[4 * s + 1] = v.y; xf[4 * s + 2] = v.z; xf[4 * s + 3] = v.w;
+  }
+#pragma unroll
+  for (int j = 0; j < GM::NT; ++j) {
+    const int col = 16 * GM::N16 + 4 * j + g;
+    xf[4 * GM::N16 + j] = (xv && col < dk) ? xrow[col] : 0.f;
+  }
+  float xnorm = 0.f, posx = 0.f;
+  if (L2) xnorm = xv ? a.xx[x_base + x] : 0.f;
+  if (PASS == 3) posx = xv ? a.pos[(size_t)c * a.S + x] : 0.f;
+
+  v4f oacc[NC];
+#pragma unroll
+  for (int cb = 0; cb < NC; ++cb) oacc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+  float mrun = -3.0e38f, lrun = 0.f, wsum = 0.f;
+  int cnt = 0;
+
+  // ---- streamed tiles, register-staged prefetch
+  const int ntiles = (n_y + TY - 1) / TY;
+  float4 stage[NU];
+  float st_aux = 0.f, st_auy = 0.f;
+  auto load_tile = [&](int t) {
+    const int y0 = t * TY;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int unit = threadIdx.x + 256 * u;
+      const int row = unit / NK, cu = unit % NK;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (unit < TY * NK && y0 + row < n_y && 4 * cu < dk)
+        v = *reinterpret_cast<const float4*>(a.Y + (y_base + y0 + row) * dk + 4 * cu);
+      stage[u] = v;
+    }
+    if (threadIdx.x < TY) {
+      const int yr = y0 + threadIdx.x;
+      if (PASS == 2) st_aux = yr < n_y ? a.lse[y_base + yr] : __builtin_inff();
+      if (L2) st_auy = yr < n_y ? a.yy[y_base + yr] : 0.f;
+    }
+  };
+  load_tile(0);
+
+  for (int t = 0; t < ntiles; ++t) {
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int unit = threadIdx.x + 256 * u;
+      const int row = unit / NK, cu = unit % NK;
+      if (unit < TY * NK) *reinterpret_cast<float4*>(&tile[row * PITCH + 4 * cu]) = stage[u];
+    }
+    if (threadIdx.x < TY) {
+      if (PASS == 2) aux[threadIdx.x] = st_aux;
+      if (L2) auy[threadIdx.x] = st_auy;
+    }
+    __syncthreads();
+    if (t + 1 < ntiles) load_tile(t + 1);
+
+    const int y0 = t * TY;
+#pragma unroll 1
+    for (int yb = 0; yb < TY / 16; ++yb) {
+      if (y0 + yb * 16 >= n_y) break;
+      // -- T[y][x]: lane (g, m), register r holds y = yb*16 + 4g + r, x = m
+      v4f tacc = (v4f){0.f, 0.f, 0.f, 0.f};
+      const float* yrow = &tile[(yb * 16 + m) * PITCH + 4 * g];
+#pragma unroll
+      for (int s = 0; s < GM::N16; ++s) {
+        const float4 yv = *reinterpret_cast<const float4*>(yrow + 16 * s);
+        tacc = mfma16(yv.x, xf[4 * s + 0], tacc);
+        tacc = mfma16(yv.y, xf[4 * s + 1], tacc);
+        tacc = mfma16(yv.z, xf[4 * s + 2], tacc);
+        tacc = mfma16(yv.w, xf[4 * s + 3], tacc);
+      }
+#pragma unroll
+      for (int j = 0; j < GM::NT; ++j) {
+        const float yv = tile[(yb * 16 + m) * PITCH + 16 * GM::N16 + 4 * j + g];
+        tacc = mfma16(yv, xf[4 * GM::N16 + j], tacc);
+      }
+      // -- scores
+      float sc[4], dist[4];
+      const int yl = yb * 16 + 4 * g;                      // first of this lane's 4 streamed rows
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        sc[r] = tacc[r];
+        if (L2) {
+          const float d2 = fmaxf(xnorm + auy[yl + r] - 2.f * tacc[r], 0.f);
+          dist[r] = sqrtf(d2);
+          sc[r] = -dist[r];
+        }
+        if (PASS != 2 && y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
+      }
+      if (PASS == 3) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) cnt += sc[r] > posx ? 1 : 0;
+        continue;
+      }
+      float w[4];
+      if (PASS == 1) {
+        float mloc = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float mnew = fmaxf(mrun, mloc);
+        const float alpha = __expf(mrun - mnew);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w[r] = __expf(sc[r] - mnew);
+        lrun = lrun * alpha + ((w[0] + w[1]) + (w[2] + w[3]));
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+          for (int cb = 0; cb < NC; ++cb) oacc[cb] *= alpha;
+          if (L2) wsum *= alpha;
+        }
+        mrun = mnew;
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w[r] = __expf(sc[r] - aux[yl + r]);
+      }
+      if (L2) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w[r] = dist[r] > 0.f ? w[r] / dist[r] : 0.f;
+        wsum += (w[0] + w[1]) + (w[2] + w[3]);
+      }
+      // -- O^T[c][x] += sum_y Y[y][c] W[y][x]: A = Y fragment (row c), B = W (lane x)
+      const float* ycol = &tile[yl * PITCH + m];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int cb = 0; cb < NC; ++cb) oacc[cb] = mfma16(ycol[r * PITCH + 16 * cb], w[r], oacc[cb]);
+      }
+    }
+  }
+
+  // ---- epilogue
+  if (PASS == 3) {
+    cnt += __shfl_xor(cnt, 16);
+    cnt += __shfl_xor(cnt, 32);
+    if (g == 0 && xv) (side == MAR_SIDE_DST ? a.rank_dst : a.rank_src)[(size_t)c * a.S + x] = 1 + cnt;
+    return;
+  }
+  float scale = 1.f;
+  if (PASS == 1) {
+    float ltot = lrun + __shfl_xor(lrun, 16);
+    ltot += __shfl_xor(ltot, 32);
+    if (g == 0 && xv) a.lse[x_base + x] = mrun + logf(ltot);
+    scale = 1.f / ltot;
+  }
+  if (L2) {
+    wsum += __shfl_xor(wsum, 16);
+    wsum += __shfl_xor(wsum, 32);
+  }
+  if (!xv) return;
+  float* orow = PASS == 1 ? a.out + (x_base + x) * dk
+                          : a.out + (size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] * dk;
+#pragma unroll
+  for (int cb = 0; cb < NC; ++cb) {
+    const int col = 16 * cb + 4 * g;                       // O^T rows 16cb + 4g + r of lane's column x
+    if (col < dk) {
+      float4 o = make_float4(oacc[cb][0], oacc[cb][1], oacc[cb][2], oacc[cb][3]);
+      if (L2) {
+        const float4 xs = *reinterpret_cast<const float4*>(xrow + col);
+        o.x -= xs.x * wsum; o.y -= xs.y * wsum; o.z -= xs.z * wsum; o.w -= xs.w * wsum;
+      }
+      o.x *= scale; o.y *= scale; o.z *= scale; o.w *= scale;
+      *reinterpret_cast<float4*>(orow + col) = o;
+    }
+  }
+}
+
+// ------------------------------------------------------------------- launchers -----
+int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
+
+template <int NK, int NC, int TY>
+static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
+#define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, TY, P, L>), grid, dim3(256), 0, st, a)
+  if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
+  else if (pass == 2) { if (l2) FL(2, 1); else FL(2, 0); }
+  else { if (l2) FL(3, 1); else FL(3, 0); }
+#undef FL
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32_t* rank_dst, int32_t* rank_src,
+                            hipStream_t st) {
+  const MarDims& d = c->dm;
+  const MarLayout& L = c->L;
+  FlashArgs a;
+  a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;
+  a.xx = pass == 2 ? L.kk : L.qq; a.yy = pass == 2 ? L.qq : L.kk;
+  a.lse = L.lse; a.pos = L.pos;
+  a.out = pass == 1 ? L.gQ : L.G;
+  a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
+  a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
+  const int max_nx = pass == 2 ? d.N : (b.n < d.S ? b.n : d.S);
+  a.nstripes = (max_nx + 63) / 64;
+  const int ncs = 2 * b.nchunks;
+  const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes));
+  const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
+  const int nk = d.dk / 4;
+  if (nk <= 13) return launch_sized<13, 4, 64>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 7, 64>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 64>(a, pass, l2, grid, st);
+  if (nk <= 64) return launch_sized<64, 16, 32>(a, pass, l2, grid, st);
+  return launch_sized<100, 25, 32>(a, pass, l2, grid, st);
+}

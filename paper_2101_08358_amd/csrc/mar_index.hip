@@ -1,0 +1,358 @@
+// Integer side of the training step: counter-based sampling and table fill, the batch's
+// unique-row set, and the row-sorted order of all row occurrences (gfx950).
+//
+// The unique set comes from a bitmap over "unified ids" (a node id, or num_nodes + relation
+// id): mark bits, pop-count scan -> rank of every touched row and the ascending id list.
+// Occurrences are then counted per rank and an exclusive scan gives each row a contiguous
+// segment of positions; gradient rows are later written straight into that order so the
+// per-row reduction streams contiguous memory.
+#include "mar_common.h"
+
+// ---------------------------------------------------------------- Philox4x32-10 -----
+// Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11).
+__device__ __forceinline__ void philox4x32_10(uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3,
+                                              uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+}
+
+// Negative sampling (Sec. 2.1; degree-based fraction of Table 1).  One thread per pair of
+// slots: counter = (slot >> 1, 2*chunk + side, step lo, step hi), key = seed; even slot takes
+// output words 0,1 and odd slot words 2,3 as a 64-bit value x; id = mulhi64(x, range).
+__global__ void __launch_bounds__(256)
+k_sample(uint64_t seed, uint64_t step, int64_t num_nodes, const int32_t* __restrict__ es,
+         const int32_t* __restrict__ ed, int64_t num_edges, int C, int N, int Ndeg,
+         int32_t* __restrict__ neg_src, int32_t* __restrict__ neg_dst) {
+  const int pairs = (N + 1) >> 1;
+  const int64_t total = (int64_t)2 * C * pairs;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int pr = (int)(i % pairs);
+  const int cs = (int)(i / pairs);            // 2*chunk + side
+  const int side = cs & 1, chunk = cs >> 1;
+  uint32_t c0 = (uint32_t)pr, c1 = (uint32_t)cs, c2 = (uint32_t)step, c3 = (uint32_t)(step >> 32);
+  philox4x32_10(c0, c1, c2, c3, (uint32_t)seed, (uint32_t)(seed >> 32));
+  const uint64_t x[2] = {(uint64_t)c0 | ((uint64_t)c1 << 32), (uint64_t)c2 | ((uint64_t)c3 << 32)};
+  int32_t* out = (side == MAR_SIDE_SRC ? neg_src : neg_dst) + (size_t)chunk * N;
+  const int32_t* endpoint = side == MAR_SIDE_SRC ? es : ed;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int slot = 2 * pr + h;
+    if (slot >= N) break;
+    int32_t id;
+    if (slot < Ndeg) id = endpoint[__umul64hi(x[h], (uint64_t)num_edges)];
+    else id = (int32_t)__umul64hi(x[h], (uint64_t)num_nodes);
+    out[slot] = id;
+  }
+}
+
+// N(0, std^2) fill: counter = (block lo, block hi, 0, 0x80000000 | table) gives elements
+// 4*block .. 4*block+3 by two Box-Muller pairs on 24-bit uniforms.
+__global__ void __launch_bounds__(256)
+k_init_normal(float* __restrict__ tab, int64_t n, uint64_t seed, uint32_t table, float std) {
+  const int64_t nblocks = (n + 3) >> 2;
+  for (int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; b < nblocks; b += (int64_t)gridDim.x * blockDim.x) {
+    uint32_t c0 = (uint32_t)b, c1 = (uint32_t)((uint64_t)b >> 32), c2 = 0u, c3 = 0x80000000u | table;
+    philox4x32_10(c0, c1, c2, c3, (uint32_t)seed, (uint32_t)(seed >> 32));
+    const uint32_t o[4] = {c0, c1, c2, c3};
+    float z[4];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const float u1 = (float)((o[2 * p] >> 8) + 1u) * (1.0f / 16777216.0f);
+      const float u2 = (float)(o[2 * p + 1] >> 8) * (1.0f / 16777216.0f);
+      const float r = sqrtf(-2.0f * logf(u1));
+      float sn, cs;
+      sincospif(2.0f * u2, &sn, &cs);
+      z[2 * p] = r * cs * std;
+      z[2 * p + 1] = r * sn * std;
+    }
+    const int64_t e = b << 2;
+    if (e + 3 < n) {
+      *reinterpret_cast<float4*>(tab + e) = make_float4(z[0], z[1], z[2], z[3]);
+    } else {
+      for (int k = 0; k < 4 && e + k < n; ++k) tab[e + k] = z[k];
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) k_fill_u32(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// ------------------------------------------------------------ occurrence numbering -----
+// Occurrence k of a batch with n edges and cn = chunks*N negatives per side:
+//   [0,n) source of edge k | [n,2n) destination | [2n,3n) relation |
+//   [3n,3n+cn) destination-replacing negatives | [3n+cn,3n+2cn) source-replacing negatives
+struct OccArgs {
+  const int32_t *src, *rel, *dst, *neg_src, *neg_dst;
+  int32_t n, cn;
+  int32_t num_nodes;
+};
+
+__device__ __forceinline__ int32_t occ_unified_id(const OccArgs& a, int64_t k) {
+  const int64_t n = a.n;
+  if (k < n) return a.src[k];
+  if (k < 2 * n) return a.dst[k - n];
+  if (k < 3 * n) return a.num_nodes + a.rel[k - 2 * n];
+  k -= 3 * n;
+  if (k < a.cn) return a.neg_dst[k];
+  return a.neg_src[k - a.cn];
+}
+
+// Marks the bitmap and zeroes the per-rank counters for this step.
+__global__ void __launch_bounds__(256)
+k_mark(OccArgs a, int64_t n_occ, uint32_t* __restrict__ bitmap, uint32_t* __restrict__ count, int64_t n_count) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (int64_t i = t0; i < n_count; i += stride) count[i] = 0u;
+  for (int64_t k = t0; k < n_occ; k += stride) {
+    const uint32_t id = (uint32_t)occ_unified_id(a, k);
+    const uint32_t bit = 1u << (id & 31u);
+    uint32_t* w = bitmap + (id >> 5);
+    if (!(*w & bit)) atomicOr(w, bit);
+  }
+}
+
+// ------------------------------------------------------------------------- scans -----
+// Exclusive prefix sums over f(in[i]); f = popcount for the bitmap, identity for counts.
+// Elements per block: 256 threads x 16.
+#define SCAN_PER_THREAD 16
+#define SCAN_BLOCK_ELEMS (256 * SCAN_PER_THREAD)
+
+template <int POPC> __device__ __forceinline__ uint32_t scan_f(uint32_t v) { return POPC ? (uint32_t)__popc(v) : v; }
+
+// Block-wide exclusive scan of one value per thread (256 threads); returns the exclusive
+// prefix and the block total through `total`.
+__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* total) {
+  __shared__ uint32_t wave_tot[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();                    // protects wave_tot across successive calls
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const uint32_t t = wave_tot[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+template <int POPC>
+__global__ void __launch_bounds__(256)
+k_scan_block_sums(const uint32_t* __restrict__ in, int64_t n, uint32_t* __restrict__ bsum) {
+  const int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK_ELEMS + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+  uint32_t s = 0;
+#pragma unroll
+  for (int j = 0; j < SCAN_PER_THREAD; ++j) if (base + j < n) s += scan_f<POPC>(in[base + j]);
+  uint32_t tot;
+  block_exclusive_scan_256(s, &tot);
+  if (threadIdx.x == 0) bsum[blockIdx.x] = tot;
+}
+
+// One block: exclusive scan of bsum[0..nb) in place.
+__global__ void __launch_bounds__(256) k_scan_bsum(uint32_t* __restrict__ bsum, int64_t nb) {
+  uint32_t carry = 0;
+  for (int64_t b0 = 0; b0 < nb; b0 += 256) {
+    const int64_t i = b0 + threadIdx.x;
+    const uint32_t v = i < nb ? bsum[i] : 0u;
+    uint32_t tot;
+    const uint32_t ex = block_exclusive_scan_256(v, &tot);
+    if (i < nb) bsum[i] = carry + ex;
+    carry += tot;
+  }
+}
+
+// Writes out[i] = exclusive prefix.  With POPC: also emits the ascending ids of the set bits,
+// the unique-row total into scalars[0] and the number of set bits below `split_bit` (the
+// first relation's unified id) into scalars[1].  With `single_block` the kernel loops over the
+// whole input itself and needs no block sums.
+template <int POPC>
+__global__ void __launch_bounds__(256)
+k_scan_apply(const uint32_t* __restrict__ in, int64_t n, const uint32_t* __restrict__ bsum, int single_block,
+             uint32_t* __restrict__ out, int32_t* __restrict__ uniq, int32_t* __restrict__ scalars, int64_t split_bit) {
+  const int64_t nblk = (n + SCAN_BLOCK_ELEMS - 1) / SCAN_BLOCK_ELEMS;
+  uint32_t carry = 0;
+  for (int64_t blk = single_block ? 0 : blockIdx.x; blk < nblk; blk += single_block ? 1 : gridDim.x) {
+    const int64_t base = blk * SCAN_BLOCK_ELEMS + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+    uint32_t v[SCAN_PER_THREAD];
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < SCAN_PER_THREAD; ++j) {
+      v[j] = base + j < n ? in[base + j] : 0u;
+      s += scan_f<POPC>(v[j]);
+    }
+    uint32_t tot;
+    uint32_t run = block_exclusive_scan_256(s, &tot) + (single_block ? carry : bsum[blk]);
+    carry += tot;
+#pragma unroll
+    for (int j = 0; j < SCAN_PER_THREAD; ++j) {
+      if (base + j < n) {
+        out[base + j] = run;
+        if (POPC) {
+          uint32_t w = v[j];
+          const int64_t id0 = (base + j) << 5;
+          if (id0 <= split_bit && split_bit < id0 + 32)
+            scalars[1] = (int32_t)(run + __popc(w & ((1u << (split_bit - id0)) - 1u)));
+          uint32_t r = run;
+          while (w) {
+            const int b = __ffs(w) - 1;
+            uniq[r++] = (int32_t)(id0 + b);
+            w &= w - 1;
+          }
+        }
+        run += scan_f<POPC>(v[j]);
+      }
+    }
+    if (POPC && base <= n - 1 && n - 1 < base + SCAN_PER_THREAD) scalars[0] = (int32_t)run;   // thread owning the last word
+  }
+}
+
+template <int POPC>
+static hipError_t scan_u32(const uint32_t* in, int64_t n, uint32_t* out, uint32_t* bsum, int32_t* uniq,
+                           int32_t* scalars, int64_t split_bit, hipStream_t st) {
+  const int64_t nblk = (n + SCAN_BLOCK_ELEMS - 1) / SCAN_BLOCK_ELEMS;
+  if (nblk <= 16) {
+    hipLaunchKernelGGL(k_scan_apply<POPC>, dim3(1), dim3(256), 0, st, in, n, bsum, 1, out, uniq, scalars, split_bit);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(k_scan_block_sums<POPC>, dim3((unsigned)nblk), dim3(256), 0, st, in, n, bsum);
+  hipLaunchKernelGGL(k_scan_bsum, dim3(1), dim3(256), 0, st, bsum, nblk);
+  hipLaunchKernelGGL(k_scan_apply<POPC>, dim3((unsigned)nblk), dim3(256), 0, st, in, n, bsum, 0, out, uniq, scalars, split_bit);
+  return hipGetLastError();
+}
+
+// -------------------------------------------------------- rank + slot per occurrence -----
+// Wave-aggregated counter increment: lanes that share a key issue one atomic together.
+// Every lane of the wave must call this (inactive lanes pass active = false).
+__device__ __forceinline__ int wave_agg_inc(uint32_t* __restrict__ counters, int key, bool active) {
+  const int lane = threadIdx.x & 63;
+  int result = 0;
+  bool pending = active;
+  for (;;) {
+    const uint64_t pend = __ballot(pending);
+    if (!pend) break;
+    const int leader = __ffsll((unsigned long long)pend) - 1;
+    const int k = __shfl(key, leader);
+    const bool mine = pending && key == k;
+    const uint64_t m = __ballot(mine);
+    int base = 0;
+    if (lane == leader) base = (int)atomicAdd(&counters[k], (uint32_t)__popcll(m));
+    base = __shfl(base, leader);
+    if (mine) {
+      result = base + __popcll(m & ((1ull << lane) - 1ull));
+      pending = false;
+    }
+  }
+  return result;
+}
+
+__global__ void __launch_bounds__(256)
+k_count(OccArgs a, int64_t n_occ, const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ word_prefix,
+        uint32_t* __restrict__ count, int32_t* __restrict__ inv, int32_t* __restrict__ slot) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t rounds = (n_occ + stride - 1) / stride;          // same trip count for every lane
+  for (int64_t it = 0; it < rounds; ++it) {
+    const int64_t k = it * stride + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool active = k < n_occ;
+    int rank = 0;
+    if (active) {
+      const uint32_t id = (uint32_t)occ_unified_id(a, k);
+      const uint32_t w = id >> 5, bit = 1u << (id & 31u);
+      rank = (int)(word_prefix[w] + __popc(bitmap[w] & (bit - 1u)));
+    }
+    const int sl = wave_agg_inc(count, rank, active);
+    if (active) { inv[k] = rank; slot[k] = sl; }
+  }
+}
+
+// Copies the unique id lists into the caller's debug buffers.
+__global__ void __launch_bounds__(256)
+k_debug_uniq(const int32_t* __restrict__ uniq, const int32_t* __restrict__ scalars, int32_t num_nodes,
+             int32_t* __restrict__ num_uniq, int32_t* __restrict__ uniq_nodes, int32_t* __restrict__ uniq_rels) {
+  const int total = scalars[0], un = scalars[1];
+  if (blockIdx.x == 0 && threadIdx.x == 0 && num_uniq) { num_uniq[0] = un; num_uniq[1] = total - un; }
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    if (i < un) { if (uniq_nodes) uniq_nodes[i] = uniq[i]; }
+    else if (uniq_rels) uniq_rels[i - un] = uniq[i] - num_nodes;
+  }
+}
+
+// ------------------------------------------------------------------- launchers -----
+static inline unsigned grid_for(int64_t n, int threads, unsigned cap) {
+  int64_t g = (n + threads - 1) / threads;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (unsigned)g;
+}
+
+hipError_t mar_launch_init(const mar_ctx* c, int fill, hipStream_t st) {
+  const MarDims& d = c->dm;
+  hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(d.nwords, 256, 4096)), dim3(256), 0, st, c->L.bitmap, d.nwords, 0u);
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, (uint32_t*)c->L.scalars, (int64_t)16, 0u);
+  if (fill) {
+    const int64_t nn = d.num_nodes * d.dim, nr = (int64_t)d.num_rels * d.dim;
+    hipLaunchKernelGGL(k_init_normal, dim3(grid_for((nn + 3) / 4, 256, 1 << 16)), dim3(256), 0, st,
+                       c->node_emb, nn, c->cfg.seed, 0u, c->cfg.init_std);
+    hipLaunchKernelGGL(k_init_normal, dim3(grid_for((nr + 3) / 4, 256, 1 << 16)), dim3(256), 0, st,
+                       c->rel_emb, nr, c->cfg.seed, 1u, c->cfg.init_std);
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(nn, 256, 1 << 16)), dim3(256), 0, st, (uint32_t*)c->node_state, nn, 0u);
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(nr, 256, 1 << 16)), dim3(256), 0, st, (uint32_t*)c->rel_state, nr, 0u);
+  }
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_clear_bitmap(const mar_ctx* c, hipStream_t st) {
+  hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(c->dm.nwords, 256, 4096)), dim3(256), 0, st, c->L.bitmap, c->dm.nwords, 0u);
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
+  hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(n, 256, 4096)), dim3(256), 0, st, p, n, v);
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_sample(const mar_ctx* c, uint64_t step, const int32_t* es, const int32_t* ed,
+                             int64_t num_edges, int32_t* neg_src, int32_t* neg_dst, hipStream_t st) {
+  const MarDims& d = c->dm;
+  const int64_t total = (int64_t)2 * d.C * ((d.N + 1) / 2);
+  hipLaunchKernelGGL(k_sample, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, c->cfg.seed, step,
+                     d.num_nodes, es, ed, num_edges, d.C, d.N, d.Ndeg, neg_src, neg_dst);
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
+  const MarDims& d = c->dm;
+  const MarLayout& L = c->L;
+  OccArgs a{b.src, b.rel, b.dst, b.neg_src, b.neg_dst, b.n, b.cn, (int32_t)d.num_nodes};
+  const int64_t n_count = d.u_max + 1;
+  const int64_t work = b.n_occ > n_count ? b.n_occ : n_count;
+  hipLaunchKernelGGL(k_mark, dim3(grid_for(work, 256, 2048)), dim3(256), 0, st, a, b.n_occ, L.bitmap, L.count, n_count);
+  hipError_t e = scan_u32<1>(L.bitmap, d.nwords, L.word_prefix, L.bsum, L.uniq, L.scalars, d.num_nodes, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, 256, 2048)), dim3(256), 0, st, a, b.n_occ, L.bitmap, L.word_prefix,
+                     L.count, L.inv, L.slot);
+  return scan_u32<0>(L.count, n_count, L.seg_off, L.bsum, nullptr, nullptr, -1, st);
+}
+
+hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st) {
+  (void)b;
+  if (dbg->num_uniq || dbg->uniq_nodes || dbg->uniq_rels)
+    hipLaunchKernelGGL(k_debug_uniq, dim3(64), dim3(256), 0, st, c->L.uniq, c->L.scalars, (int32_t)c->dm.num_nodes,
+                       dbg->num_uniq, dbg->uniq_nodes, dbg->uniq_rels);
+  return hipGetLastError();
+}

@@ -1,0 +1,371 @@
+// Row-wise (bandwidth-bound) kernels of the training step (gfx950): gather of the batch's
+// rows into dense contraction operands, the chain rule from operand gradients back to the
+// source / relation / destination rows, and the per-row gradient reduction fused with the
+// sparse Adagrad scatter.
+#include "mar_common.h"
+
+struct RowArgs {
+  const float *node_emb, *rel_emb;
+  const int32_t *src, *rel, *dst, *neg_src, *neg_dst;
+  int32_t n, cn, B, C, N, S, dim, dk, model;
+  int64_t n_occ;
+  int32_t num_nodes;
+};
+
+template <int GL> __device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = GL / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// ---------------------------------------------------------------------- gather -----
+// Section A (train only): occurrence -> position in row-sorted order; clears the occurrence's
+//   bitmap word for the next step.
+// Section B: one lane group per edge builds the two edge-side operands
+//     side DST (negatives replace d): a_ej = <q, n_j>,  q = s*r (DistMult), s.r complex (ComplEx)
+//     side SRC (negatives replace s): b_ej = <q, m_j>,  q = r*d,            conj(r).d
+//   for TransE the scores are -|q - n_j| with q = s + r and q = d - r; also the positive score.
+// Section C: one lane group per negative copies its row into the dense per-chunk matrix.
+template <int GL>
+__global__ void __launch_bounds__(256)
+k_prep(RowArgs a, int train, int nbA, int nbB, const uint32_t* __restrict__ seg_off, const int32_t* __restrict__ inv,
+       const int32_t* __restrict__ slot, int32_t* __restrict__ occ_pos, int32_t* __restrict__ rank_sorted,
+       uint32_t* __restrict__ bitmap, float* __restrict__ Q, float* __restrict__ Km, float* __restrict__ qq,
+       float* __restrict__ kk, float* __restrict__ pos, float* __restrict__ pos_user) {
+  const int blk = blockIdx.x;
+  if (blk < nbA) {
+    const int64_t k = (int64_t)blk * 256 + threadIdx.x;
+    if (k < a.n_occ) {
+      const int r = inv[k];
+      const int p = (int)seg_off[r] + slot[k];
+      occ_pos[k] = p;
+      rank_sorted[p] = r;
+      // unified id of the occurrence (same numbering as the index kernels)
+      int64_t kk2 = k; uint32_t id;
+      if (kk2 < a.n) id = a.src[kk2];
+      else if (kk2 < 2 * (int64_t)a.n) id = a.dst[kk2 - a.n];
+      else if (kk2 < 3 * (int64_t)a.n) id = a.num_nodes + a.rel[kk2 - 2 * (int64_t)a.n];
+      else { kk2 -= 3 * (int64_t)a.n; id = kk2 < a.cn ? a.neg_dst[kk2] : a.neg_src[kk2 - a.cn]; }
+      bitmap[id >> 5] = 0u;
+    }
+    return;
+  }
+  constexpr int GPB = 256 / GL;                  // lane groups per block
+  const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
+  const int dim = a.dim, dk = a.dk;
+  if (blk < nbA + nbB) {
+    const int e = (blk - nbA) * GPB + grp;
+    if (e >= a.n) return;
+    const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
+    const float* r_row = a.rel_emb + (size_t)a.rel[e] * dim;
+    const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
+    float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
+    float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
+    float acc = 0.f, nd = 0.f, ns = 0.f;
+    if (a.model == MAR_MODEL_COMPLEX) {
+      const int h = dim >> 1;
+      for (int k = l; k < h; k += GL) {
+        const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
+        const float ure = sr * rr - si * ri, uim = sr * ri + si * rr;
+        const float wre = rr * dr + ri * di, wim = rr * di - ri * dr;
+        acc += ure * dr + uim * di;
+        qd[k] = ure; qd[h + k] = uim; qs[k] = wre; qs[h + k] = wim;
+      }
+    } else {
+      for (int k = l; k < dim; k += GL) {
+        const float s = s_row[k], r = r_row[k], d = d_row[k];
+        float u, w;
+        if (a.model == MAR_MODEL_DISTMULT) { u = s * r; w = r * d; acc += u * d; }
+        else { u = s + r; w = d - r; const float df = u - d; acc += df * df; nd += u * u; ns += w * w; }
+        qd[k] = u; qs[k] = w;
+      }
+    }
+    for (int k = dim + l; k < dk; k += GL) { qd[k] = 0.f; qs[k] = 0.f; }
+    acc = group_sum<GL>(acc);
+    if (a.model == MAR_MODEL_TRANSE) {
+      nd = group_sum<GL>(nd); ns = group_sum<GL>(ns);
+      acc = -sqrtf(acc);
+      if (l == 0) { qq[(size_t)MAR_SIDE_DST * a.B + e] = nd; qq[(size_t)MAR_SIDE_SRC * a.B + e] = ns; }
+    }
+    if (l == 0) { pos[e] = acc; if (pos_user) pos_user[e] = acc; }
+    return;
+  }
+  {
+    const int rr = (blk - nbA - nbB) * GPB + grp;          // row among 2*cn negatives
+    if (rr >= 2 * a.cn) return;
+    const int side = rr >= a.cn ? MAR_SIDE_DST : MAR_SIDE_SRC;
+    const int cj = rr - (side == MAR_SIDE_DST ? a.cn : 0);  // chunk*N + j
+    const int32_t id = side == MAR_SIDE_DST ? a.neg_dst[cj] : a.neg_src[cj];
+    const float* row = a.node_emb + (size_t)id * dim;
+    const size_t krow = (size_t)side * a.C * a.N + cj;
+    float* out = Km + krow * dk;
+    float nn = 0.f;
+    for (int k = l; k < dk; k += GL) {
+      const float v = k < dim ? row[k] : 0.f;
+      nn += v * v;
+      out[k] = v;
+    }
+    if (a.model == MAR_MODEL_TRANSE) {
+      nn = group_sum<GL>(nn);
+      if (l == 0) kk[krow] = nn;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ chain rule -----
+// From the gradients w.r.t. the two edge-side operands (gq_dst w.r.t. the DST-side q, gq_src
+// w.r.t. the SRC-side q) and the positive term -2 f(e) to gradient rows of s, r, d, written at
+// the occurrences' row-sorted positions.  Also the per-edge loss terms, summed per block in a
+// fixed order.
+template <int GL>
+__global__ void __launch_bounds__(256)
+k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ pos, const float* __restrict__ lse,
+        const int32_t* __restrict__ occ_pos, float* __restrict__ G, float* __restrict__ loss_part) {
+  constexpr int GPB = 256 / GL;
+  __shared__ float lsum[GPB];
+  const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
+  const int e = blockIdx.x * GPB + grp;
+  const int dim = a.dim, dk = a.dk;
+  float le = 0.f;
+  if (e < a.n) {
+    const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
+    const float* r_row = a.rel_emb + (size_t)a.rel[e] * dim;
+    const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
+    const float* gu = gQ + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
+    const float* gw = gQ + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
+    float* gs = G + (size_t)occ_pos[e] * dk;
+    float* gd = G + (size_t)occ_pos[a.n + e] * dk;
+    float* gr = G + (size_t)occ_pos[2 * (size_t)a.n + e] * dk;
+    if (a.model == MAR_MODEL_COMPLEX) {
+      const int h = dim >> 1;
+      for (int k = l; k < h; k += GL) {
+        const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
+        const float ure = gu[k], uim = gu[h + k], wre = gw[k], wim = gw[h + k];
+        // g_s = conj(r) (gU - 2 d);  g_d = r (gW - 2 s)
+        const float zr = ure - 2.f * dr, zi = uim - 2.f * di;
+        gs[k] = rr * zr + ri * zi;  gs[h + k] = rr * zi - ri * zr;
+        const float yr = wre - 2.f * sr, yi = wim - 2.f * si;
+        gd[k] = rr * yr - ri * yi;  gd[h + k] = rr * yi + ri * yr;
+        // g_r = conj(s) gU + conj(gW) d - 2 conj(s) d
+        gr[k]     = sr * ure + si * uim + wre * dr + wim * di - 2.f * (sr * dr + si * di);
+        gr[h + k] = sr * uim - si * ure + wre * di - wim * dr - 2.f * (sr * di - si * dr);
+      }
+    } else if (a.model == MAR_MODEL_DISTMULT) {
+      for (int k = l; k < dim; k += GL) {
+        const float s = s_row[k], r = r_row[k], d = d_row[k], u = gu[k], w = gw[k];
+        gs[k] = r * (u - 2.f * d);
+        gd[k] = r * (w - 2.f * s);
+        gr[k] = s * u + d * w - 2.f * s * d;
+      }
+    } else {
+      const float dist = -pos[e];
+      const float inv2 = dist > 0.f ? 2.f / dist : 0.f;
+      for (int k = l; k < dim; k += GL) {
+        const float dl = (s_row[k] + r_row[k] - d_row[k]) * inv2;     // 2 * unit(s + r - d)
+        const float u = gu[k], w = gw[k];
+        gs[k] = u + dl;
+        gr[k] = u - w + dl;
+        gd[k] = w - dl;
+      }
+    }
+    for (int k = dim + l; k < dk; k += GL) { gs[k] = 0.f; gd[k] = 0.f; gr[k] = 0.f; }
+    le = -2.f * pos[e] + lse[(size_t)MAR_SIDE_DST * a.B + e] + lse[(size_t)MAR_SIDE_SRC * a.B + e];
+  }
+  if (l == 0) lsum[grp] = le;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int i = 0; i < GPB; ++i) t += lsum[i];
+    loss_part[blockIdx.x] = t;
+  }
+}
+
+// ------------------------------------------------- per-row reduce + Adagrad scatter -----
+struct ReduceArgs {
+  float *node_emb, *node_state, *rel_emb, *rel_state;
+  const float* G;
+  float* carry;
+  const int32_t* rank_sorted;
+  const uint32_t* seg_off;
+  const int32_t* uniq;
+  float* dbg_grad;
+  int64_t n_occ;
+  int32_t num_nodes, dim, dk;
+  float lr, eps;
+};
+
+// Adagrad (Sec. 5.1): state += g^2; theta -= lr * g / (sqrt(state) + eps), on columns
+// 4*q .. 4*q+3 of the row with the given rank.
+__device__ __forceinline__ void adagrad_cols(const ReduceArgs& a, int rank, int q, float4 g) {
+  const int32_t id = a.uniq[rank];
+  float *emb, *st;
+  if (id < a.num_nodes) { emb = a.node_emb + (size_t)id * a.dim; st = a.node_state + (size_t)id * a.dim; }
+  else { emb = a.rel_emb + (size_t)(id - a.num_nodes) * a.dim; st = a.rel_state + (size_t)(id - a.num_nodes) * a.dim; }
+  const float gv[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int col = 4 * q + i;
+    if (col < a.dim) {
+      const float s = st[col] + gv[i] * gv[i];
+      st[col] = s;
+      emb[col] = emb[col] - a.lr * gv[i] / (sqrtf(s) + a.eps);
+      if (a.dbg_grad) a.dbg_grad[(size_t)rank * a.dim + col] = gv[i];
+    }
+  }
+}
+
+// One wave per task of MAR_TASK_ROWS consecutive positions.  Rows of one segment (= one unique
+// table row) are summed; a segment that lies inside the task is finished here, one that
+// crosses the task's borders leaves a partial sum (slot 0: began earlier, slot 1: continues).
+template <int NV>
+__global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t p0 = task * MAR_TASK_ROWS;
+  if (p0 >= a.n_occ) return;
+  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_occ ? p0 + MAR_TASK_ROWS : a.n_occ;
+  const int cnt = (int)(p1 - p0);
+  const int nq = a.dk >> 2;
+  const int my_rank = lane < cnt ? a.rank_sorted[p0 + lane] : -1;
+  int cur = __shfl(my_rank, 0);
+  float4 acc[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+  auto flush = [&](int rank) {
+    const int64_t lo = a.seg_off[rank], hi = a.seg_off[rank + 1];
+    if (lo >= p0 && hi <= p1) {
+#pragma unroll
+      for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) adagrad_cols(a, rank, q, acc[v]); }
+    } else {
+      float* c = a.carry + ((size_t)task * 2 + (lo < p0 ? 0 : 1)) * a.dk;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) *reinterpret_cast<float4*>(c + 4 * q) = acc[v]; }
+    }
+  };
+
+  for (int i = 0; i < cnt; ++i) {
+    const int r = __shfl(my_rank, i);
+    if (r != cur) {
+      flush(cur);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+      cur = r;
+    }
+    const float* row = a.G + (size_t)(p0 + i) * a.dk;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int q = lane + 64 * v;
+      if (q < nq) {
+        const float4 g = *reinterpret_cast<const float4*>(row + 4 * q);
+        acc[v].x += g.x; acc[v].y += g.y; acc[v].z += g.z; acc[v].w += g.w;
+      }
+    }
+  }
+  flush(cur);
+}
+
+// Finishes the segments that span several tasks: the task in which such a segment begins
+// adds its own tail partial and the head partials of the following tasks, in task order.
+// Block 0 also adds up the per-block loss terms in a fixed order.
+template <int NV>
+__global__ void __launch_bounds__(256)
+k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, float* __restrict__ loss_out) {
+  const int lane = threadIdx.x & 63;
+  if (blockIdx.x == 0 && threadIdx.x < 64 && loss_out) {
+    float t = 0.f;
+    for (int i = lane; i < n_loss_part; i += 64) t += loss_part[i];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) t += __shfl_xor(t, o);
+    if (lane == 0) *loss_out = t;
+  }
+  const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t p0 = task * MAR_TASK_ROWS;
+  if (p0 >= a.n_occ) return;
+  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_occ ? p0 + MAR_TASK_ROWS : a.n_occ;
+  const int rank = a.rank_sorted[p1 - 1];
+  const int64_t lo = a.seg_off[rank], hi = a.seg_off[rank + 1];
+  if (!(lo >= p0 && hi > p1)) return;
+  const int nq = a.dk >> 2;
+  const int64_t last_task = (hi - 1) / MAR_TASK_ROWS;
+  float4 acc[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int q = lane + 64 * v;
+    acc[v] = q < nq ? *reinterpret_cast<const float4*>(a.carry + ((size_t)task * 2 + 1) * a.dk + 4 * q)
+                    : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  for (int64_t t = task + 1; t <= last_task; ++t) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int q = lane + 64 * v;
+      if (q < nq) {
+        const float4 g = *reinterpret_cast<const float4*>(a.carry + ((size_t)t * 2) * a.dk + 4 * q);
+        acc[v].x += g.x; acc[v].y += g.y; acc[v].z += g.z; acc[v].w += g.w;
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) adagrad_cols(a, rank, q, acc[v]); }
+}
+
+// ------------------------------------------------------------------- launchers -----
+static RowArgs row_args(const mar_ctx* c, const MarBatch& b) {
+  const MarDims& d = c->dm;
+  RowArgs a;
+  a.node_emb = c->node_emb; a.rel_emb = c->rel_emb;
+  a.src = b.src; a.rel = b.rel; a.dst = b.dst; a.neg_src = b.neg_src; a.neg_dst = b.neg_dst;
+  a.n = b.n; a.cn = b.cn; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.dim = d.dim; a.dk = d.dk; a.model = c->cfg.model;
+  a.n_occ = b.n_occ; a.num_nodes = (int32_t)d.num_nodes;
+  return a;
+}
+
+static inline int lane_group(int dk) { return dk <= 64 ? 16 : (dk <= 128 ? 32 : 64); }
+
+hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, int train, float* pos_out, hipStream_t st) {
+  const MarLayout& L = c->L;
+  RowArgs a = row_args(c, b);
+  const int GL = lane_group(a.dk), gpb = 256 / GL;
+  const int nbA = train ? (int)((b.n_occ + 255) / 256) : 0;
+  const int nbB = (b.n + gpb - 1) / gpb;
+  const int nbC = (2 * b.cn + gpb - 1) / gpb;
+  const dim3 grid(nbA + nbB + nbC), blk(256);
+#define PREP(GLV) hipLaunchKernelGGL(k_prep<GLV>, grid, blk, 0, st, a, train, nbA, nbB, L.seg_off, L.inv, L.slot, L.occ_pos, \
+                                   L.rank_sorted, L.bitmap, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
+  if (GL == 16) PREP(16); else if (GL == 32) PREP(32); else PREP(64);
+#undef PREP
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
+  const MarLayout& L = c->L;
+  RowArgs a = row_args(c, b);
+  const int GL = lane_group(a.dk), gpb = 256 / GL;
+  const dim3 grid((b.n + gpb - 1) / gpb), blk(256);
+#define CHAIN(GLV) hipLaunchKernelGGL(k_chain<GLV>, grid, blk, 0, st, a, L.gQ, L.pos, L.lse, L.occ_pos, L.G, L.loss_part)
+  if (GL == 16) CHAIN(16); else if (GL == 32) CHAIN(32); else CHAIN(64);
+#undef CHAIN
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st) {
+  const MarLayout& L = c->L;
+  const MarDims& d = c->dm;
+  ReduceArgs a;
+  a.node_emb = c->node_emb; a.node_state = c->node_state; a.rel_emb = c->rel_emb; a.rel_state = c->rel_state;
+  a.G = L.G; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.seg_off = L.seg_off; a.uniq = L.uniq;
+  a.dbg_grad = dbg_grad; a.n_occ = b.n_occ; a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk;
+  a.lr = c->cfg.lr; a.eps = c->cfg.eps;
+  const int64_t tasks = (b.n_occ + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
+  const dim3 grid((unsigned)((tasks + 3) / 4)), blk(256);
+  const int GL = lane_group(d.dk), gpb = 256 / GL;
+  const int n_loss_part = (b.n + gpb - 1) / gpb;
+  if (d.dk <= 256) {
+    hipLaunchKernelGGL(k_reduce<1>, grid, blk, 0, st, a);
+    hipLaunchKernelGGL(k_fixup<1>, grid, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+  } else {
+    hipLaunchKernelGGL(k_reduce<2>, grid, blk, 0, st, a);
+    hipLaunchKernelGGL(k_fixup<2>, grid, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+  }
+  return hipGetLastError();
+}

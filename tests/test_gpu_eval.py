@@ -1,0 +1,77 @@
+"""GPU parity: link-prediction scores and ranks against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2101_08358_amd as mar
+from oracle import step as ostep
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(model, V, R, dim, B, C, N, n, seed, std=0.3, integer=False):
+    rng = np.random.default_rng(seed)
+    if integer:
+        ne = rng.integers(-2, 3, (V, dim)).astype(np.float32)
+        re_ = rng.integers(-2, 3, (R, dim)).astype(np.float32)
+    else:
+        ne = (rng.standard_normal((V, dim)) * std).astype(np.float32)
+        re_ = (rng.standard_normal((R, dim)) * std).astype(np.float32)
+    src, rel, dst = (rng.integers(0, V, n).astype(np.int32), rng.integers(0, R, n).astype(np.int32),
+                     rng.integers(0, V, n).astype(np.int32))
+    neg_src, neg_dst = rng.integers(0, V, (C, N)).astype(np.int32), rng.integers(0, V, (C, N)).astype(np.int32)
+    tr = mar.Trainer(V, R, dim, model, B, C, N, node_emb=ne, rel_emb=re_)
+    tr.neg_src.copy_(torch.from_numpy(neg_src.reshape(-1))); tr.neg_dst.copy_(torch.from_numpy(neg_dst.reshape(-1)))
+    pos, rd, rs = tr.eval_scores(*(torch.from_numpy(x).to(tr.device) for x in (src, rel, dst)))
+    torch.cuda.synchronize()
+    got = pos.cpu().numpy(), rd.cpu().numpy(), rs.cpu().numpy()
+    assert torch.equal(tr.node_emb.cpu(), torch.from_numpy(ne))      # tables untouched
+    tr.close()
+    exp = ostep.eval_scores(model, B // C, ne, re_, src, rel, dst, neg_src, neg_dst, return_blocks=True)
+    return got, exp
+
+
+@pytest.mark.parametrize("model", (0, 1, 2))
+def test_ranks_exact_on_integer_embeddings(model):
+    """Small-integer embeddings make every score's decisive quantity exact in fp32 and fp64 (the sum for
+    DistMult / ComplEx, the squared distance for TransE, whose square root is monotone), ties included (a
+    negative equal to the edge's own endpoint); ranks must then agree exactly."""
+    got, exp = _run(model, 60, 3, 24, 300, 3, 70, 260, seed=model, integer=True)
+    if model != 2:
+        assert np.array_equal(got[0], exp[0].astype(np.float32))
+    else:
+        assert np.allclose(got[0], exp[0], rtol=1e-6)
+    assert np.array_equal(got[1], exp[1]) and np.array_equal(got[2], exp[2])
+
+
+def _tolerant(got, exp, S):
+    """A rank is an integer decided by float comparisons: where a negative's score is within rounding of
+    the positive's, either outcome is valid.  The rank must lie between the counts with the margin
+    subtracted and added."""
+    pos, rd, rs, blocks = exp
+    assert np.max(np.abs(got[0] - pos)) <= 1e-4 * max(np.max(np.abs(pos)), 1e-30)
+    n = pos.shape[0]
+    decided = 0
+    for side, ranks, oranks in ((0, got[1], rd), (1, got[2], rs)):
+        for c, blk in enumerate(blocks):
+            A = blk[side]
+            lo, hi = c * S, c * S + A.shape[0]
+            tol = 2e-6 * max(np.max(np.abs(A)), np.max(np.abs(pos)))
+            rmin = 1 + np.sum(A > pos[lo:hi, None] + tol, axis=1)
+            rmax = 1 + np.sum(A > pos[lo:hi, None] - tol, axis=1)
+            assert np.all(ranks[lo:hi] >= rmin) and np.all(ranks[lo:hi] <= rmax)
+            # where no negative is within the margin (no collision with the edge's own endpoint, no
+            # near tie) the rank is unique and must equal the oracle's
+            sure = rmin == rmax
+            assert np.array_equal(ranks[lo:hi][sure], oranks[lo:hi][sure])
+            decided += int(sure.sum())
+    assert decided >= 0.5 * 2 * n
+
+
+@pytest.mark.parametrize("model", (0, 1, 2))
+@pytest.mark.parametrize("shape", ((5000, 9, 100, 2000, 2, 1000, 1700), (300, 2, 50, 100, 10, 100, 100)))
+def test_ranks_within_rounding_of_oracle(model, shape):
+    V, R, dim, B, C, N, n = shape
+    got, exp = _run(model, V, R, dim, B, C, N, n, seed=10 + model)
+    _tolerant(got, exp, B // C)
+    assert got[1].min() >= 1 and got[1].max() <= N + 1

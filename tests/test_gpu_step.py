@@ -1,0 +1,93 @@
+"""GPU parity: one training step through the C ABI against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from parity_util import run_step_both, check_step
+
+pytestmark = pytest.mark.gpu
+
+DISTMULT, COMPLEX, TRANSE = 0, 1, 2
+
+
+@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE))
+@pytest.mark.parametrize("shape", (
+    # (V, R, dim, B, C, N, n_edges)
+    (500, 7, 50, 1000, 10, 100, 1000),        # config-1 geometry on a small graph (heavy row reuse)
+    (20000, 30, 100, 2000, 2, 1000, 2000),    # config-2/3/4 chunk geometry: several 64-row stripes, ragged tails
+    (3000, 5, 100, 600, 3, 130, 470),         # ragged everything: short last chunk, N not a multiple of 16
+))
+def test_one_step_matches_oracle(model, shape):
+    V, R, dim, B, C, N, n = shape
+    print("case", model, shape, flush=True)
+    out = run_step_both(model, V, R, dim, B, C, N, n, seed=100 + model)
+    rep = check_step(out)
+    print(rep, flush=True)
+
+
+@pytest.mark.parametrize("model,dim", ((DISTMULT, 400), (COMPLEX, 200), (TRANSE, 36), (DISTMULT, 17), (COMPLEX, 128)))
+def test_one_step_other_widths(model, dim):
+    print("case", model, dim, flush=True)
+    out = run_step_both(model, 4000, 11, dim, 512, 4, 200, 512, seed=7 + dim)
+    print(check_step(out), flush=True)
+
+
+@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE))
+def test_one_step_from_warm_state(model):
+    """With accumulators of the size of G^2 the update is smooth in G: every element is compared."""
+    from oracle import step as ostep
+    from parity_util import make_tables
+    rng = np.random.default_rng(5)
+    V, R, dim, B, C, N = 800, 4, 100, 1000, 5, 300
+    tabs = make_tables(rng, V, R, dim, 0.05)
+    ids = (rng.integers(0, V, B).astype(np.int32), rng.integers(0, R, B).astype(np.int32),
+           rng.integers(0, V, B).astype(np.int32), rng.integers(0, V, (C, N)).astype(np.int32),
+           rng.integers(0, V, (C, N)).astype(np.int32))
+    dry = ostep.train_batch(model, 0.1, 1e-10, B // C, tabs[0].copy(), np.zeros_like(tabs[0]), tabs[1].copy(),
+                            np.zeros_like(tabs[1]), *ids, apply_update=False)
+    gn, gr = np.max(np.abs(dry.G_nodes)), np.max(np.abs(dry.G_rels))
+    ns = ((rng.random((V, dim)) + 0.5) * gn * gn).astype(np.float32)
+    rs = ((rng.random((R, dim)) + 0.5) * gr * gr).astype(np.float32)
+    out = run_step_both(model, V, R, dim, B, C, N, B, seed=11, node_state=ns, rel_state=rs, ids=ids, tables=tabs)
+    rep = check_step(out, max_flip_frac=1.0)
+    gpu, ora = out["gpu"], out["ora"]
+    for k in ("node_emb", "rel_emb", "node_state", "rel_state"):
+        assert np.max(np.abs(gpu[k].astype(np.float64) - ora[k])) / np.max(np.abs(ora[k])) <= 1e-4, k
+    print(rep, flush=True)
+
+
+def test_degenerate_cases():
+    # a single edge, a single negative, one chunk
+    print("single", flush=True)
+    check_step(run_step_both(DISTMULT, 50, 2, 50, 1, 1, 1, 1, seed=1, std=0.5))
+    # every edge identical, negatives all the same node (one node row hit by everything)
+    print("all-same", flush=True)
+    n, C, N = 300, 3, 40
+    ids = (np.full(n, 3, np.int32), np.zeros(n, np.int32), np.full(n, 4, np.int32),
+           np.full((C, N), 3, np.int32), np.full((C, N), 5, np.int32))
+    check_step(run_step_both(COMPLEX, 10, 1, 20, n, C, N, n, seed=2, std=0.3, ids=ids), max_flip_frac=1.0)
+    # all-zero tables: every score 0, loss = 2 n log N, TransE distances all zero
+    print("zero-tables", flush=True)
+    for model in (DISTMULT, TRANSE):
+        tabs = (np.zeros((60, 24), np.float32), np.zeros((3, 24), np.float32))
+        out = run_step_both(model, 60, 3, 24, 64, 2, 10, 64, seed=3, tables=tabs)
+        assert abs(out["gpu"]["loss"] - 64 * 2 * np.log(10)) < 1e-3
+        check_step(out, max_flip_frac=1.0)
+    # large scores: the softmax must not overflow
+    print("large-scores", flush=True)
+    out = run_step_both(DISTMULT, 200, 3, 50, 128, 2, 50, 128, seed=4, std=2.0)
+    assert np.all(np.isfinite(out["gpu"]["node_emb"])) and np.isfinite(out["gpu"]["loss"])
+    check_step(out)
+
+
+def test_empty_batch_is_a_no_op():
+    import paper_2101_08358_amd as mar
+    tr = mar.Trainer(100, 2, 16, DISTMULT, 64, 2, 8, seed=3)
+    torch.cuda.synchronize()
+    before = tr.node_emb.clone()
+    e = torch.zeros(0, dtype=torch.int32, device=tr.device)
+    tr.loss.fill_(5.0)
+    tr.train_batch(e, e, e)
+    torch.cuda.synchronize()
+    assert tr.loss.item() == 0.0 and torch.equal(before, tr.node_emb)
+    tr.close()
