@@ -8,7 +8,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmarius_hip.so")
+_LIB_PATH = os.environ.get("MARIUS_HIP_LIB") or os.path.join(_HERE, "libmarius_hip.so")
 _lib = None
 
 MODEL_DISTMULT, MODEL_COMPLEX, MODEL_TRANSE = 0, 1, 2

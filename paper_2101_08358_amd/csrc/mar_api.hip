@@ -58,6 +58,24 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   d->u_max = ids < n_occ ? ids : n_occ;
   d->nwords = (ids + 31) / 32;
   if (!mar_flash_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the contraction kernels", d->dk);
+  // Small batches give too few (chunk-side, 64-row stripe) workgroups to fill 256 CUs: let several
+  // workgroups share a stripe, each streaming a slice of the other matrix.
+  d->ty = mar_flash_tile_rows(d->dk);
+  long target = 2048;
+  if (const char* e = getenv("MAR_FLASH_TARGET_WGS")) { const long v = atol(e); if (v > 0) target = v; }
+  auto split = [&](int n_x, int n_y, int32_t* sy, int32_t* tps) {
+    const long wgs = 2L * d->C * ((n_x + 63) / 64);
+    const int ntiles = (n_y + d->ty - 1) / d->ty;
+    long want = (target + wgs - 1) / wgs;
+    if (want > 8) want = 8;
+    if (want > ntiles) want = ntiles;
+    if (want < 1) want = 1;
+    *tps = (int32_t)((ntiles + want - 1) / want);
+    *sy = (int32_t)((ntiles + *tps - 1) / *tps);
+  };
+  split(d->S, d->N, &d->sy1, &d->tps1);
+  split(d->N, d->S, &d->sy2, &d->tps2);
+  d->n_pos_max = 3 * (int64_t)cfg->batch_size + 2 * cn * d->sy2;
   return MAR_OK;
 }
 
@@ -69,10 +87,10 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
     off += (bytes + 255) & ~(size_t)255;
     return p;
   };
-  const size_t n_occ = (size_t)d.n_occ_max, u1 = (size_t)d.u_max + 1;
+  const size_t n_occ = (size_t)d.n_occ_max, n_pos = (size_t)d.n_pos_max, u1 = (size_t)d.u_max + 1;
   const size_t B = d.B, CN = (size_t)d.C * d.N, dk = d.dk;
   const size_t scan_elems = (size_t)d.nwords > u1 ? (size_t)d.nwords : u1;
-  const size_t tasks = (n_occ + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
+  const size_t tasks = (n_pos + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
   MarLayout l;
   l.scalars = (int32_t*)take(16 * 4);
   l.bitmap = (uint32_t*)take((size_t)d.nwords * 4);
@@ -84,15 +102,16 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.inv = (int32_t*)take(n_occ * 4);
   l.slot = (int32_t*)take(n_occ * 4);
   l.occ_pos = (int32_t*)take(n_occ * 4);
-  l.rank_sorted = (int32_t*)take(n_occ * 4);
+  l.rank_sorted = (int32_t*)take(n_pos * 4);
   l.Q = (float*)take(2 * B * dk * 4);
   l.Km = (float*)take(2 * CN * dk * 4);
   l.qq = (float*)take(2 * B * 4);
   l.kk = (float*)take(2 * CN * 4);
   l.pos = (float*)take(B * 4);
   l.lse = (float*)take(2 * B * 4);
-  l.gQ = (float*)take(2 * B * dk * 4);
-  l.G = (float*)take(n_occ * dk * 4);
+  l.gQ = (float*)take((size_t)d.sy1 * 2 * B * dk * 4);
+  l.ml = (float*)take((size_t)d.sy1 * 2 * B * 2 * 4);
+  l.G = (float*)take(n_pos * dk * 4);
   l.carry = (float*)take(tasks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);
   l.rank_tmp = (int32_t*)take(2 * B * 4);
@@ -169,6 +188,7 @@ static int make_batch(const mar_ctx* c, const int32_t* src, const int32_t* rel, 
   b->nchunks = (n + c->dm.S - 1) / c->dm.S;
   b->cn = b->nchunks * c->dm.N;
   b->n_occ = 3 * (int64_t)n + 2 * (int64_t)b->cn;
+  b->n_pos = 3 * (int64_t)n + 2 * (int64_t)b->cn * c->dm.sy2;
   return MAR_OK;
 }
 

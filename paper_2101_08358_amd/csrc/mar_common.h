@@ -29,7 +29,8 @@ struct MarLayout {
   float*    kk;           // [2][chunks*N] squared norms of Km rows (TransE)
   float*    pos;          // [batch] positive scores
   float*    lse;          // [2][batch] log-sum-exp per edge and side
-  float*    gQ;           // [2][batch][dk] gradient w.r.t. Q rows
+  float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
+  float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
   float*    G;            // [n_occ][dk] one gradient row per occurrence, in row-sorted order
   float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders
   float*    loss_part;    // per-block partial loss sums
@@ -41,6 +42,10 @@ struct MarDims {
   int32_t B, C, S, N, Ndeg;
   int64_t num_nodes; int32_t num_rels;
   int64_t n_occ_max;               // 3B + 2CN
+  int64_t n_pos_max;               // 3B + 2CN*sy2: gradient rows per step
+  int32_t sy1, sy2;                // how many workgroups share the streamed rows of one stripe (pass 1 / 2)
+  int32_t tps1, tps2;              // streamed tiles per workgroup
+  int32_t ty;                      // rows per streamed tile
   int64_t u_max;                   // min(num_nodes + num_rels, n_occ_max)
   int64_t nwords;                  // bitmap words
 };
@@ -77,6 +82,7 @@ struct MarBatch {
   int32_t nchunks;  // ceil(n / S)
   int32_t cn;       // nchunks * N
   int64_t n_occ;    // 3n + 2cn
+  int64_t n_pos;    // 3n + 2cn*sy2 gradient rows
 };
 
 hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st);
@@ -87,3 +93,4 @@ hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st)
 hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st);
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
 int mar_flash_supported(int dk);
+int mar_flash_tile_rows(int dk);

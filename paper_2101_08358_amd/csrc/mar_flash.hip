@@ -24,12 +24,16 @@ struct FlashArgs {
   const float* Y;      // streamed matrix
   const float* xx;     // squared row norms (TransE)
   const float* yy;
-  float* lse;          // [2][B]: written by pass 1, read by pass 2
+  float* ml;           // [sy1][2][B][2]: per part, the softmax reference and the sum of exp(score - reference);
+                       // written by pass 1, combined into the log-sum-exp by pass 2
   const float* pos;    // [B] positive scores (pass 3)
-  float* out;          // pass 1: gQ rows [2][B][dk]; pass 2: gradient rows G
-  const int32_t* rowmap;  // pass 2: occ_pos of the negatives' occurrences
+  float* out;          // pass 1: unnormalised gQ rows [sy][2][B][dk]; pass 2: gradient rows G
+  const int32_t* rowmap;  // pass 2: occ_pos of the negatives' occurrences (each owns sy consecutive rows)
   int32_t* rank_dst; int32_t* rank_src;   // pass 3
   int32_t n, B, C, N, S, cn, nchunks, dk, nstripes;
+  int32_t sy;          // workgroups sharing one stripe, each streaming `tps` tiles
+  int32_t tps;
+  int32_t sy_ml;       // parts pass 1 was split into
 };
 
 __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
@@ -45,8 +49,11 @@ struct FlashGeom {
 };
 
 // PASS: 1 online softmax + gQ, 2 gK with given lse, 3 rank counts.  L2: TransE scores.
+#ifndef MAR_FLASH_WAVES_SMALL
+#define MAR_FLASH_WAVES_SMALL 4
+#endif
 template <int NK, int NC, int TY, int PASS, int L2>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, (NK <= 32 ? MAR_FLASH_WAVES_SMALL : (NK <= 64 ? 2 : 1)))
 k_flash(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
@@ -61,8 +68,9 @@ k_flash(FlashArgs a) {
   // workgroup -> (chunk-side, stripe); consecutive workgroup ids rotate over the 8 XCDs, so all
   // stripes of one chunk-side are given ids with the same residue and share one L2.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int cs = (slot / a.nstripes) * 8 + xcd;
-  const int stripe = slot % a.nstripes;
+  const int part = slot % a.sy, slot2 = slot / a.sy;
+  const int cs = (slot2 / a.nstripes) * 8 + xcd;
+  const int stripe = slot2 % a.nstripes;
   if (cs >= 2 * a.nchunks) return;
   const int side = cs & 1, c = cs >> 1;
   const int ne = min(a.S, a.n - c * a.S);                 // edges in this chunk
@@ -103,7 +111,9 @@ k_flash(FlashArgs a) {
   int cnt = 0;
 
   // ---- streamed tiles, register-staged prefetch
-  const int ntiles = (n_y + TY - 1) / TY;
+  const int ntiles_all = (n_y + TY - 1) / TY;
+  const int t_begin = part * a.tps;
+  const int ntiles = min(ntiles_all, t_begin + a.tps);     // this part streams tiles [t_begin, ntiles); may be empty
   float4 stage[NU];
   float st_aux = 0.f, st_auy = 0.f;
   auto load_tile = [&](int t) {
@@ -119,13 +129,23 @@ k_flash(FlashArgs a) {
     }
     if (threadIdx.x < TY) {
       const int yr = y0 + threadIdx.x;
-      if (PASS == 2) st_aux = yr < n_y ? a.lse[y_base + yr] : __builtin_inff();
+      if (PASS == 2) {
+        // log-sum-exp of streamed row yr from the parts of pass 1
+        st_aux = __builtin_inff();
+        if (yr < n_y) {
+          const size_t pr = (size_t)2 * a.B;
+          float mm = -3.0e38f, ll = 0.f;
+          for (int p = 0; p < a.sy_ml; ++p) mm = fmaxf(mm, a.ml[(p * pr + y_base + yr) * 2]);
+          for (int p = 0; p < a.sy_ml; ++p) ll += a.ml[(p * pr + y_base + yr) * 2 + 1] * __expf(a.ml[(p * pr + y_base + yr) * 2] - mm);
+          st_aux = mm + logf(ll);
+        }
+      }
       if (L2) st_auy = yr < n_y ? a.yy[y_base + yr] : 0.f;
     }
   };
-  load_tile(0);
+  if (t_begin < ntiles) load_tile(t_begin);
 
-  for (int t = 0; t < ntiles; ++t) {
+  for (int t = t_begin; t < ntiles; ++t) {
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
@@ -180,20 +200,25 @@ k_flash(FlashArgs a) {
       }
       float w[4];
       if (PASS == 1) {
-        float mloc = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float mnew = fmaxf(mrun, mloc);
-        const float alpha = __expf(mrun - mnew);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) w[r] = __expf(sc[r] - mnew);
-        lrun = lrun * alpha + ((w[0] + w[1]) + (w[2] + w[3]));
-        if (__any(alpha != 1.f)) {
+        // Online softmax with a lazily updated reference: the common reference mrun of row x only
+        // moves when some score exceeds it by more than 16 (always true for the first block), so
+        // the cross-lane maximum and the rescale of the accumulators are off the common path;
+        // exp(score - mrun) <= e^16 cannot overflow.
+        const float mloc = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        if (__any(mloc > mrun + 16.f)) {
+          float mall = fmaxf(mloc, __shfl_xor(mloc, 16));
+          mall = fmaxf(mall, __shfl_xor(mall, 32));
+          const float mnew = fmaxf(mrun, mall);
+          const float alpha = __expf(mrun - mnew);
+          lrun *= alpha;
 #pragma unroll
           for (int cb = 0; cb < NC; ++cb) oacc[cb] *= alpha;
           if (L2) wsum *= alpha;
+          mrun = mnew;
         }
-        mrun = mnew;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w[r] = __expf(sc[r] - mrun);
+        lrun += (w[0] + w[1]) + (w[2] + w[3]);
       } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r) w[r] = __expf(sc[r] - aux[yl + r]);
@@ -220,20 +245,18 @@ k_flash(FlashArgs a) {
     if (g == 0 && xv) (side == MAR_SIDE_DST ? a.rank_dst : a.rank_src)[(size_t)c * a.S + x] = 1 + cnt;
     return;
   }
-  float scale = 1.f;
   if (PASS == 1) {
     float ltot = lrun + __shfl_xor(lrun, 16);
     ltot += __shfl_xor(ltot, 32);
-    if (g == 0 && xv) a.lse[x_base + x] = mrun + logf(ltot);
-    scale = 1.f / ltot;
+    if (g == 0 && xv) *reinterpret_cast<float2*>(a.ml + (((size_t)part * 2 * a.B) + x_base + x) * 2) = make_float2(mrun, ltot);
   }
   if (L2) {
     wsum += __shfl_xor(wsum, 16);
     wsum += __shfl_xor(wsum, 32);
   }
   if (!xv) return;
-  float* orow = PASS == 1 ? a.out + (x_base + x) * dk
-                          : a.out + (size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] * dk;
+  float* orow = PASS == 1 ? a.out + ((size_t)part * 2 * a.B + x_base + x) * dk
+                          : a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] + part) * dk;
 #pragma unroll
   for (int cb = 0; cb < NC; ++cb) {
     const int col = 16 * cb + 4 * g;                       // O^T rows 16cb + 4g + r of lane's column x
@@ -243,7 +266,6 @@ k_flash(FlashArgs a) {
         const float4 xs = *reinterpret_cast<const float4*>(xrow + col);
         o.x -= xs.x * wsum; o.y -= xs.y * wsum; o.z -= xs.z * wsum; o.w -= xs.w * wsum;
       }
-      o.x *= scale; o.y *= scale; o.z *= scale; o.w *= scale;
       *reinterpret_cast<float4*>(orow + col) = o;
     }
   }
@@ -251,6 +273,7 @@ k_flash(FlashArgs a) {
 
 // ------------------------------------------------------------------- launchers -----
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
+int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of the instantiation that serves dk
 
 template <int NK, int NC, int TY>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
@@ -269,14 +292,17 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   FlashArgs a;
   a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;
   a.xx = pass == 2 ? L.kk : L.qq; a.yy = pass == 2 ? L.qq : L.kk;
-  a.lse = L.lse; a.pos = L.pos;
+  a.ml = L.ml; a.pos = L.pos;
   a.out = pass == 1 ? L.gQ : L.G;
   a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
   const int max_nx = pass == 2 ? d.N : (b.n < d.S ? b.n : d.S);
   a.nstripes = (max_nx + 63) / 64;
   const int ncs = 2 * b.nchunks;
-  const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes));
+  a.sy = pass == 1 ? d.sy1 : (pass == 2 ? d.sy2 : 1);
+  a.tps = pass == 1 ? d.tps1 : (pass == 2 ? d.tps2 : (1 << 30));
+  a.sy_ml = d.sy1;
+  const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
   if (nk <= 13) return launch_sized<13, 4, 64>(a, pass, l2, grid, st);

@@ -105,17 +105,42 @@ __device__ __forceinline__ int32_t occ_unified_id(const OccArgs& a, int64_t k) {
   return a.neg_src[k - a.cn];
 }
 
-// Marks the bitmap and zeroes the per-rank counters for this step.
+// For every lane: the set of lanes of the wave that hold the same key (inactive lanes get 0).
+// Every lane of the wave must call this.
+__device__ __forceinline__ uint64_t wave_match(int key, bool active) {
+  uint64_t mine = 0;
+  uint64_t pend = __ballot(active);
+  while (pend) {
+    const int leader = __ffsll((unsigned long long)pend) - 1;
+    const int k = __shfl(key, leader);
+    const uint64_t m = __ballot(active && key == k);
+    if (active && key == k) mine = m;
+    pend &= ~m;
+  }
+  return mine;
+}
+
+// Marks the bitmap and zeroes the per-rank counters for this step.  Same-address atomics
+// serialise (tens of ns each), so a hot id must not issue one per occurrence: identical ids
+// inside a wave issue one, the bit is tested first with a device-coherent load, and the grid
+// is small enough that later rounds of the loop already see the bits of hot ids.
 __global__ void __launch_bounds__(256)
 k_mark(OccArgs a, int64_t n_occ, uint32_t* __restrict__ bitmap, uint32_t* __restrict__ count, int64_t n_count) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & 63;
   for (int64_t i = t0; i < n_count; i += stride) count[i] = 0u;
-  for (int64_t k = t0; k < n_occ; k += stride) {
-    const uint32_t id = (uint32_t)occ_unified_id(a, k);
-    const uint32_t bit = 1u << (id & 31u);
-    uint32_t* w = bitmap + (id >> 5);
-    if (!(*w & bit)) atomicOr(w, bit);
+  const int64_t rounds = (n_occ + stride - 1) / stride;
+  for (int64_t it = 0; it < rounds; ++it) {
+    const int64_t k = it * stride + t0;
+    const bool active = k < n_occ;
+    const uint32_t id = active ? (uint32_t)occ_unified_id(a, k) : 0u;
+    const uint64_t same = wave_match((int)id, active);
+    if (active && (__ffsll((unsigned long long)same) - 1) == lane) {
+      const uint32_t bit = 1u << (id & 31u);
+      uint32_t* w = bitmap + (id >> 5);
+      if (!(__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(w, bit);
+    }
   }
 }
 
@@ -237,46 +262,43 @@ static hipError_t scan_u32(const uint32_t* in, int64_t n, uint32_t* out, uint32_
 }
 
 // -------------------------------------------------------- rank + slot per occurrence -----
-// Wave-aggregated counter increment: lanes that share a key issue one atomic together.
-// Every lane of the wave must call this (inactive lanes pass active = false).
-__device__ __forceinline__ int wave_agg_inc(uint32_t* __restrict__ counters, int key, bool active) {
+// Wave-aggregated counter increment by `mult` per lane (the same for every active lane of the
+// wave): lanes that share a key issue one atomic together, and all leaders issue theirs in the
+// same instruction.  Every lane of the wave must call this.
+__device__ __forceinline__ int wave_agg_inc(uint32_t* __restrict__ counters, int key, bool active, int mult) {
   const int lane = threadIdx.x & 63;
-  int result = 0;
-  bool pending = active;
-  for (;;) {
-    const uint64_t pend = __ballot(pending);
-    if (!pend) break;
-    const int leader = __ffsll((unsigned long long)pend) - 1;
-    const int k = __shfl(key, leader);
-    const bool mine = pending && key == k;
-    const uint64_t m = __ballot(mine);
-    int base = 0;
-    if (lane == leader) base = (int)atomicAdd(&counters[k], (uint32_t)__popcll(m));
-    base = __shfl(base, leader);
-    if (mine) {
-      result = base + __popcll(m & ((1ull << lane) - 1ull));
-      pending = false;
-    }
-  }
-  return result;
+  const uint64_t same = wave_match(key, active);
+  const int leader = active ? __ffsll((unsigned long long)same) - 1 : lane;
+  int base = 0;
+  if (active && leader == lane) base = (int)atomicAdd(&counters[key], (uint32_t)(mult * __popcll(same)));
+  base = __shfl(base, leader);
+  return base + mult * __popcll(same & ((1ull << lane) - 1ull));
 }
 
+// Rank of every occurrence's row and its slot inside the row's segment.  An occurrence of a
+// negative takes neg_mult consecutive slots (one gradient row per workgroup that shares its
+// stripe); the two kinds are walked in separate passes so a wave never mixes multiplicities.
 __global__ void __launch_bounds__(256)
-k_count(OccArgs a, int64_t n_occ, const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ word_prefix,
+k_count(OccArgs a, int64_t n_occ, int neg_mult, const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ word_prefix,
         uint32_t* __restrict__ count, int32_t* __restrict__ inv, int32_t* __restrict__ slot) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  const int64_t rounds = (n_occ + stride - 1) / stride;          // same trip count for every lane
-  for (int64_t it = 0; it < rounds; ++it) {
-    const int64_t k = it * stride + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool active = k < n_occ;
-    int rank = 0;
-    if (active) {
-      const uint32_t id = (uint32_t)occ_unified_id(a, k);
-      const uint32_t w = id >> 5, bit = 1u << (id & 31u);
-      rank = (int)(word_prefix[w] + __popc(bitmap[w] & (bit - 1u)));
+  const int64_t n_pos_occ = 3 * (int64_t)a.n;
+  for (int pass = 0; pass < 2; ++pass) {
+    const int64_t lo = pass == 0 ? 0 : n_pos_occ, hi = pass == 0 ? n_pos_occ : n_occ;
+    const int mult = pass == 0 ? 1 : neg_mult;
+    const int64_t rounds = (hi - lo + stride - 1) / stride;        // same trip count for every lane
+    for (int64_t it = 0; it < rounds; ++it) {
+      const int64_t k = lo + it * stride + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+      const bool active = k < hi;
+      int rank = 0;
+      if (active) {
+        const uint32_t id = (uint32_t)occ_unified_id(a, k);
+        const uint32_t w = id >> 5, bit = 1u << (id & 31u);
+        rank = (int)(word_prefix[w] + __popc(bitmap[w] & (bit - 1u)));
+      }
+      const int sl = wave_agg_inc(count, rank, active, mult);
+      if (active) { inv[k] = rank; slot[k] = sl; }
     }
-    const int sl = wave_agg_inc(count, rank, active);
-    if (active) { inv[k] = rank; slot[k] = sl; }
   }
 }
 
@@ -341,11 +363,11 @@ hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st)
   OccArgs a{b.src, b.rel, b.dst, b.neg_src, b.neg_dst, b.n, b.cn, (int32_t)d.num_nodes};
   const int64_t n_count = d.u_max + 1;
   const int64_t work = b.n_occ > n_count ? b.n_occ : n_count;
-  hipLaunchKernelGGL(k_mark, dim3(grid_for(work, 256, 2048)), dim3(256), 0, st, a, b.n_occ, L.bitmap, L.count, n_count);
+  hipLaunchKernelGGL(k_mark, dim3(grid_for(work / 8, 256, 256)), dim3(256), 0, st, a, b.n_occ, L.bitmap, L.count, n_count);
   hipError_t e = scan_u32<1>(L.bitmap, d.nwords, L.word_prefix, L.bsum, L.uniq, L.scalars, d.num_nodes, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, 256, 2048)), dim3(256), 0, st, a, b.n_occ, L.bitmap, L.word_prefix,
-                     L.count, L.inv, L.slot);
+  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, 256, 2048)), dim3(256), 0, st, a, b.n_occ, (int)d.sy2, L.bitmap,
+                     L.word_prefix, L.count, L.inv, L.slot);
   return scan_u32<0>(L.count, n_count, L.seg_off, L.bsum, nullptr, nullptr, -1, st);
 }
 

@@ -10,6 +10,7 @@ struct RowArgs {
   int32_t n, cn, B, C, N, S, dim, dk, model;
   int64_t n_occ;
   int32_t num_nodes;
+  int32_t sy1, sy2;      // parts per stripe in the two contraction passes
 };
 
 template <int GL> __device__ __forceinline__ float group_sum(float v) {
@@ -39,7 +40,8 @@ k_prep(RowArgs a, int train, int nbA, int nbB, const uint32_t* __restrict__ seg_
       const int r = inv[k];
       const int p = (int)seg_off[r] + slot[k];
       occ_pos[k] = p;
-      rank_sorted[p] = r;
+      const int rows = k < 3 * (int64_t)a.n ? 1 : a.sy2;       // a negative gets one gradient row per part
+      for (int i = 0; i < rows; ++i) rank_sorted[p + i] = r;
       // unified id of the occurrence (same numbering as the index kernels)
       int64_t kk2 = k; uint32_t id;
       if (kk2 < a.n) id = a.src[kk2];
@@ -119,20 +121,55 @@ k_prep(RowArgs a, int train, int nbA, int nbB, const uint32_t* __restrict__ seg_
 // fixed order.
 template <int GL>
 __global__ void __launch_bounds__(256)
-k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ pos, const float* __restrict__ lse,
-        const int32_t* __restrict__ occ_pos, float* __restrict__ G, float* __restrict__ loss_part) {
+k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, const float* __restrict__ pos,
+        float* __restrict__ lse, const int32_t* __restrict__ occ_pos, float* __restrict__ G, float* __restrict__ loss_part) {
   constexpr int GPB = 256 / GL;
+  constexpr int MAXP = 8;
   __shared__ float lsum[GPB];
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
   const int e = blockIdx.x * GPB + grp;
   const int dim = a.dim, dk = a.dk;
   float le = 0.f;
   if (e < a.n) {
+    // Merge the parts of the online softmax: part p holds (m_p, l_p) and O_p = sum_j exp(a_j - m_p) n_j.
+    const size_t part_rows = (size_t)2 * a.B;
+    float fu[MAXP], fw[MAXP], lse_u, lse_w;
+    {
+      const size_t ru = (size_t)MAR_SIDE_DST * a.B + e, rw = (size_t)MAR_SIDE_SRC * a.B + e;
+      float mu = -3.0e38f, mw = -3.0e38f;
+      for (int p = 0; p < a.sy1; ++p) {
+        mu = fmaxf(mu, ml[(p * part_rows + ru) * 2]);
+        mw = fmaxf(mw, ml[(p * part_rows + rw) * 2]);
+      }
+      float lu = 0.f, lw = 0.f;
+#pragma unroll
+      for (int p = 0; p < MAXP; ++p) {
+        fu[p] = 0.f; fw[p] = 0.f;
+        if (p < a.sy1) {
+          fu[p] = __expf(ml[(p * part_rows + ru) * 2] - mu);
+          fw[p] = __expf(ml[(p * part_rows + rw) * 2] - mw);
+          lu += fu[p] * ml[(p * part_rows + ru) * 2 + 1];
+          lw += fw[p] * ml[(p * part_rows + rw) * 2 + 1];
+        }
+      }
+      const float iu = 1.f / lu, iw = 1.f / lw;
+#pragma unroll
+      for (int p = 0; p < MAXP; ++p) { fu[p] *= iu; fw[p] *= iw; }
+      lse_u = mu + logf(lu); lse_w = mw + logf(lw);
+      if (l == 0) { lse[ru] = lse_u; lse[rw] = lse_w; }
+    }
+    const float* gu0 = gQ + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
+    const float* gw0 = gQ + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
+    const size_t pstride = part_rows * dk;
+    auto merged = [&](const float* base, const float* f, int k) {
+      float v = 0.f;
+#pragma unroll
+      for (int p = 0; p < MAXP; ++p) if (p < a.sy1) v += f[p] * base[p * pstride + k];
+      return v;
+    };
     const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
     const float* r_row = a.rel_emb + (size_t)a.rel[e] * dim;
     const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
-    const float* gu = gQ + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
-    const float* gw = gQ + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
     float* gs = G + (size_t)occ_pos[e] * dk;
     float* gd = G + (size_t)occ_pos[a.n + e] * dk;
     float* gr = G + (size_t)occ_pos[2 * (size_t)a.n + e] * dk;
@@ -140,7 +177,8 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ pos, 
       const int h = dim >> 1;
       for (int k = l; k < h; k += GL) {
         const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
-        const float ure = gu[k], uim = gu[h + k], wre = gw[k], wim = gw[h + k];
+        const float ure = merged(gu0, fu, k), uim = merged(gu0, fu, h + k);
+        const float wre = merged(gw0, fw, k), wim = merged(gw0, fw, h + k);
         // g_s = conj(r) (gU - 2 d);  g_d = r (gW - 2 s)
         const float zr = ure - 2.f * dr, zi = uim - 2.f * di;
         gs[k] = rr * zr + ri * zi;  gs[h + k] = rr * zi - ri * zr;
@@ -152,7 +190,7 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ pos, 
       }
     } else if (a.model == MAR_MODEL_DISTMULT) {
       for (int k = l; k < dim; k += GL) {
-        const float s = s_row[k], r = r_row[k], d = d_row[k], u = gu[k], w = gw[k];
+        const float s = s_row[k], r = r_row[k], d = d_row[k], u = merged(gu0, fu, k), w = merged(gw0, fw, k);
         gs[k] = r * (u - 2.f * d);
         gd[k] = r * (w - 2.f * s);
         gr[k] = s * u + d * w - 2.f * s * d;
@@ -162,14 +200,14 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ pos, 
       const float inv2 = dist > 0.f ? 2.f / dist : 0.f;
       for (int k = l; k < dim; k += GL) {
         const float dl = (s_row[k] + r_row[k] - d_row[k]) * inv2;     // 2 * unit(s + r - d)
-        const float u = gu[k], w = gw[k];
+        const float u = merged(gu0, fu, k), w = merged(gw0, fw, k);
         gs[k] = u + dl;
         gr[k] = u - w + dl;
         gd[k] = w - dl;
       }
     }
     for (int k = dim + l; k < dk; k += GL) { gs[k] = 0.f; gd[k] = 0.f; gr[k] = 0.f; }
-    le = -2.f * pos[e] + lse[(size_t)MAR_SIDE_DST * a.B + e] + lse[(size_t)MAR_SIDE_SRC * a.B + e];
+    le = -2.f * pos[e] + lse_u + lse_w;
   }
   if (l == 0) lsum[grp] = le;
   __syncthreads();
@@ -217,7 +255,8 @@ __device__ __forceinline__ void adagrad_cols(const ReduceArgs& a, int rank, int 
 // One wave per task of MAR_TASK_ROWS consecutive positions.  Rows of one segment (= one unique
 // table row) are summed; a segment that lies inside the task is finished here, one that
 // crosses the task's borders leaves a partial sum (slot 0: began earlier, slot 1: continues).
-template <int NV>
+// Rows are fetched BATCH at a time so that many loads are in flight per wave.
+template <int NV, int BATCH>
 __global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -244,34 +283,47 @@ __global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
     }
   };
 
-  for (int i = 0; i < cnt; ++i) {
-    const int r = __shfl(my_rank, i);
-    if (r != cur) {
-      flush(cur);
+  for (int i0 = 0; i0 < cnt; i0 += BATCH) {
+    float4 rows[BATCH][NV];
 #pragma unroll
-      for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-      cur = r;
+    for (int j = 0; j < BATCH; ++j) {
+      const float* row = a.G + (size_t)(p0 + i0 + j) * a.dk;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int q = lane + 64 * v;
+        rows[j][v] = (i0 + j < cnt && q < nq) ? *reinterpret_cast<const float4*>(row + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
-    const float* row = a.G + (size_t)(p0 + i) * a.dk;
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const int q = lane + 64 * v;
-      if (q < nq) {
-        const float4 g = *reinterpret_cast<const float4*>(row + 4 * q);
-        acc[v].x += g.x; acc[v].y += g.y; acc[v].z += g.z; acc[v].w += g.w;
+    for (int j = 0; j < BATCH; ++j) {
+      if (i0 + j < cnt) {
+        const int r = __shfl(my_rank, i0 + j);
+        if (r != cur) {
+          flush(cur);
+#pragma unroll
+          for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+          cur = r;
+        }
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          acc[v].x += rows[j][v].x; acc[v].y += rows[j][v].y; acc[v].z += rows[j][v].z; acc[v].w += rows[j][v].w;
+        }
       }
     }
   }
   flush(cur);
 }
 
-// Finishes the segments that span several tasks: the task in which such a segment begins
-// adds its own tail partial and the head partials of the following tasks, in task order.
-// Block 0 also adds up the per-block loss terms in a fixed order.
+// Finishes the segments that span several tasks.  One workgroup per task; it has work only if
+// a spanning segment begins in its task: then its four waves add that task's tail partial and
+// the head partials of the following tasks (wave w takes every fourth), the partial sums are
+// combined through LDS in wave order, and wave 0 applies the update.  Block 0 also adds up the
+// per-block loss terms in a fixed order.
 template <int NV>
 __global__ void __launch_bounds__(256)
 k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, float* __restrict__ loss_out) {
-  const int lane = threadIdx.x & 63;
+  __shared__ float4 part[4][64 * NV];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (blockIdx.x == 0 && threadIdx.x < 64 && loss_out) {
     float t = 0.f;
     for (int i = lane; i < n_loss_part; i += 64) t += loss_part[i];
@@ -279,34 +331,55 @@ k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, floa
     for (int o = 32; o >= 1; o >>= 1) t += __shfl_xor(t, o);
     if (lane == 0) *loss_out = t;
   }
-  const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t task = blockIdx.x;
   const int64_t p0 = task * MAR_TASK_ROWS;
   if (p0 >= a.n_occ) return;
   const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_occ ? p0 + MAR_TASK_ROWS : a.n_occ;
   const int rank = a.rank_sorted[p1 - 1];
   const int64_t lo = a.seg_off[rank], hi = a.seg_off[rank + 1];
-  if (!(lo >= p0 && hi > p1)) return;
+  if (!(lo >= p0 && hi > p1)) return;                       // uniform over the workgroup
   const int nq = a.dk >> 2;
   const int64_t last_task = (hi - 1) / MAR_TASK_ROWS;
   float4 acc[NV];
 #pragma unroll
   for (int v = 0; v < NV; ++v) {
     const int q = lane + 64 * v;
-    acc[v] = q < nq ? *reinterpret_cast<const float4*>(a.carry + ((size_t)task * 2 + 1) * a.dk + 4 * q)
-                    : make_float4(0.f, 0.f, 0.f, 0.f);
+    acc[v] = (wave == 0 && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)task * 2 + 1) * a.dk + 4 * q)
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  for (int64_t t = task + 1; t <= last_task; ++t) {
+  constexpr int FB = 8;
+  for (int64_t t = task + 1 + wave; t <= last_task; t += 4 * FB) {
+    float4 rows[FB][NV];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const int q = lane + 64 * v;
-      if (q < nq) {
-        const float4 g = *reinterpret_cast<const float4*>(a.carry + ((size_t)t * 2) * a.dk + 4 * q);
-        acc[v].x += g.x; acc[v].y += g.y; acc[v].z += g.z; acc[v].w += g.w;
+    for (int j = 0; j < FB; ++j) {
+      const int64_t tt = t + 4 * j;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int q = lane + 64 * v;
+        rows[j][v] = (tt <= last_task && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)tt * 2) * a.dk + 4 * q)
+                                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < FB; ++j) {
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        acc[v].x += rows[j][v].x; acc[v].y += rows[j][v].y; acc[v].z += rows[j][v].z; acc[v].w += rows[j][v].w;
       }
     }
   }
 #pragma unroll
-  for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) adagrad_cols(a, rank, q, acc[v]); }
+  for (int v = 0; v < NV; ++v) part[wave][lane + 64 * v] = acc[v];
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int q = lane + 64 * v;
+      float4 s = part[0][q];
+      for (int w = 1; w < 4; ++w) { const float4 o = part[w][q]; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+      if (q < nq) adagrad_cols(a, rank, q, s);
+    }
+  }
 }
 
 // ------------------------------------------------------------------- launchers -----
@@ -317,6 +390,7 @@ static RowArgs row_args(const mar_ctx* c, const MarBatch& b) {
   a.src = b.src; a.rel = b.rel; a.dst = b.dst; a.neg_src = b.neg_src; a.neg_dst = b.neg_dst;
   a.n = b.n; a.cn = b.cn; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.dim = d.dim; a.dk = d.dk; a.model = c->cfg.model;
   a.n_occ = b.n_occ; a.num_nodes = (int32_t)d.num_nodes;
+  a.sy1 = d.sy1; a.sy2 = d.sy2;
   return a;
 }
 
@@ -342,7 +416,7 @@ hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st)
   RowArgs a = row_args(c, b);
   const int GL = lane_group(a.dk), gpb = 256 / GL;
   const dim3 grid((b.n + gpb - 1) / gpb), blk(256);
-#define CHAIN(GLV) hipLaunchKernelGGL(k_chain<GLV>, grid, blk, 0, st, a, L.gQ, L.pos, L.lse, L.occ_pos, L.G, L.loss_part)
+#define CHAIN(GLV) hipLaunchKernelGGL(k_chain<GLV>, grid, blk, 0, st, a, L.gQ, L.ml, L.pos, L.lse, L.occ_pos, L.G, L.loss_part)
   if (GL == 16) CHAIN(16); else if (GL == 32) CHAIN(32); else CHAIN(64);
 #undef CHAIN
   return hipGetLastError();
@@ -354,18 +428,18 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
   ReduceArgs a;
   a.node_emb = c->node_emb; a.node_state = c->node_state; a.rel_emb = c->rel_emb; a.rel_state = c->rel_state;
   a.G = L.G; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.seg_off = L.seg_off; a.uniq = L.uniq;
-  a.dbg_grad = dbg_grad; a.n_occ = b.n_occ; a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk;
+  a.dbg_grad = dbg_grad; a.n_occ = b.n_pos; a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk;
   a.lr = c->cfg.lr; a.eps = c->cfg.eps;
-  const int64_t tasks = (b.n_occ + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
-  const dim3 grid((unsigned)((tasks + 3) / 4)), blk(256);
+  const int64_t tasks = (b.n_pos + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
+  const dim3 grid((unsigned)((tasks + 3) / 4)), gridf((unsigned)tasks), blk(256);
   const int GL = lane_group(d.dk), gpb = 256 / GL;
   const int n_loss_part = (b.n + gpb - 1) / gpb;
   if (d.dk <= 256) {
-    hipLaunchKernelGGL(k_reduce<1>, grid, blk, 0, st, a);
-    hipLaunchKernelGGL(k_fixup<1>, grid, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    hipLaunchKernelGGL((k_reduce<1, 16>), grid, blk, 0, st, a);
+    hipLaunchKernelGGL(k_fixup<1>, gridf, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
   } else {
-    hipLaunchKernelGGL(k_reduce<2>, grid, blk, 0, st, a);
-    hipLaunchKernelGGL(k_fixup<2>, grid, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    hipLaunchKernelGGL((k_reduce<2, 8>), grid, blk, 0, st, a);
+    hipLaunchKernelGGL(k_fixup<2>, gridf, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
   }
   return hipGetLastError();
 }
