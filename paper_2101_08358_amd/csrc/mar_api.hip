@@ -64,7 +64,8 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   long target = 2048;
   if (const char* e = getenv("MAR_FLASH_TARGET_WGS")) { const long v = atol(e); if (v > 0) target = v; }
   auto split = [&](int n_x, int n_y, int32_t* sy, int32_t* tps) {
-    const long wgs = 2L * d->C * ((n_x + 63) / 64);
+    const int sr = mar_flash_stripe_rows(d->dk);
+    const long wgs = 2L * d->C * ((n_x + sr - 1) / sr);
     const int ntiles = (n_y + d->ty - 1) / d->ty;
     long want = (target + wgs - 1) / wgs;
     if (want > 8) want = 8;

@@ -49,15 +49,21 @@ struct FlashGeom {
 };
 
 // PASS: 1 online softmax + gQ, 2 gK with given lse, 3 rank counts.  L2: TransE scores.
-#ifndef MAR_FLASH_WAVES_SMALL
-#define MAR_FLASH_WAVES_SMALL 4
-#endif
-template <int NK, int NC, int TY, int PASS, int L2>
-__global__ void __launch_bounds__(256, (NK <= 32 ? MAR_FLASH_WAVES_SMALL : (NK <= 64 ? 2 : 1)))
+// XB: 16-row x-blocks per wave (a workgroup's stripe has 64*XB stationary rows); every LDS
+// fragment of Y then feeds XB matrix instructions.
+// LDS reads run one phase ahead of the matrix instructions that consume them: the first
+// fragments of the next block's score product are fetched before the current block's
+// second product is issued, and each row of the second product is fetched while the
+// previous row is being multiplied.
+template <int NK, int NC, int TY, int XB, int PASS, int L2>
+__global__ void __launch_bounds__(256, (NK * XB <= 32 ? 3 : (NK * XB <= 64 ? 2 : 1)))
 k_flash(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
+  constexpr int N16 = GM::N16, NT = GM::NT;
+  constexpr int PD = N16 <= 8 ? N16 : 4;                  // float4 fragments of the score product kept in flight
   constexpr int NU = (TY * NK + 255) / 256;              // float4 units staged per thread
+  constexpr int SR = 64 * XB;                             // stationary rows per workgroup
   __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
   __shared__ float aux[TY];                               // per streamed row: lse (pass 2)
   __shared__ float auy[TY];                               // per streamed row: squared norm (TransE)
@@ -65,8 +71,8 @@ k_flash(FlashArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, m = lane & 15;
 
-  // workgroup -> (chunk-side, stripe); consecutive workgroup ids rotate over the 8 XCDs, so all
-  // stripes of one chunk-side are given ids with the same residue and share one L2.
+  // workgroup -> (chunk-side, stripe, part); consecutive workgroup ids rotate over the 8 XCDs, so
+  // all workgroups of one chunk-side are given ids with the same residue and share one L2.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int part = slot % a.sy, slot2 = slot / a.sy;
   const int cs = (slot2 / a.nstripes) * 8 + xcd;
@@ -76,7 +82,7 @@ k_flash(FlashArgs a) {
   const int ne = min(a.S, a.n - c * a.S);                 // edges in this chunk
   const int n_x = PASS == 2 ? a.N : ne;
   const int n_y = PASS == 2 ? ne : a.N;
-  if (stripe * 64 >= n_x) return;
+  if (stripe * SR >= n_x) return;
   const size_t q_base = (size_t)side * a.B + (size_t)c * a.S;       // first Q row of the chunk
   const size_t k_base = (size_t)side * a.C * a.N + (size_t)c * a.N; // first K row of the chunk
   const size_t x_base = PASS == 2 ? k_base : q_base;
@@ -84,33 +90,41 @@ k_flash(FlashArgs a) {
   const int dk = a.dk;
 
   // ---- stationary fragments: xf[4s+i] = X[x][16s + 4g + i], tail xf[4*N16+j] = X[x][16*N16 + 4j + g]
-  const int x = stripe * 64 + wave * 16 + m;
-  const bool xv = x < n_x;
-  const float* xrow = a.X + (x_base + (xv ? x : 0)) * dk;
-  float xf[NK];
+  int x[XB]; bool xv[XB]; const float* xrow[XB];
+  float xf[XB][NK], xnorm[XB], posx[XB];
 #pragma unroll
-  for (int s = 0; s < GM::N16; ++s) {
-    const int col = 16 * s + 4 * g;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (xv && col < dk) v = *reinterpret_cast<const float4*>(xrow + col);
-    xf[4 * s + 0] = v.x; xf[4 * s + 1] = v.y; xf[4 * s + 2] = v.z; xf[4 * s + 3] = v.w;
+  for (int b = 0; b < XB; ++b) {
+    x[b] = stripe * SR + (wave * XB + b) * 16 + m;
+    xv[b] = x[b] < n_x;
+    xrow[b] = a.X + (x_base + (xv[b] ? x[b] : 0)) * dk;
+#pragma unroll
+    for (int s = 0; s < N16; ++s) {
+      const int col = 16 * s + 4 * g;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (xv[b] && col < dk) v = *reinterpret_cast<const float4*>(xrow[b] + col);
+      xf[b][4 * s + 0] = v.x; xf[b][4 * s + 1] = v.y; xf[b][4 * s + 2] = v.z; xf[b][4 * s + 3] = v.w;
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int col = 16 * N16 + 4 * j + g;
+      xf[b][4 * N16 + j] = (xv[b] && col < dk) ? xrow[b][col] : 0.f;
+    }
+    xnorm[b] = 0.f; posx[b] = 0.f;
+    if (L2) xnorm[b] = xv[b] ? a.xx[x_base + x[b]] : 0.f;
+    if (PASS == 3) posx[b] = xv[b] ? a.pos[(size_t)c * a.S + x[b]] : 0.f;
   }
+
+  v4f oacc[XB][NC];
+  float mrun[XB], lrun[XB], wsum[XB];
+  int cnt[XB];
 #pragma unroll
-  for (int j = 0; j < GM::NT; ++j) {
-    const int col = 16 * GM::N16 + 4 * j + g;
-    xf[4 * GM::N16 + j] = (xv && col < dk) ? xrow[col] : 0.f;
+  for (int b = 0; b < XB; ++b) {
+#pragma unroll
+    for (int cb = 0; cb < NC; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+    mrun[b] = -3.0e38f; lrun[b] = 0.f; wsum[b] = 0.f; cnt[b] = 0;
   }
-  float xnorm = 0.f, posx = 0.f;
-  if (L2) xnorm = xv ? a.xx[x_base + x] : 0.f;
-  if (PASS == 3) posx = xv ? a.pos[(size_t)c * a.S + x] : 0.f;
 
-  v4f oacc[NC];
-#pragma unroll
-  for (int cb = 0; cb < NC; ++cb) oacc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
-  float mrun = -3.0e38f, lrun = 0.f, wsum = 0.f;
-  int cnt = 0;
-
-  // ---- streamed tiles, register-staged prefetch
+  // ---- streamed tiles, register-staged prefetch of the next tile
   const int ntiles_all = (n_y + TY - 1) / TY;
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);     // this part streams tiles [t_begin, ntiles); may be empty
@@ -145,6 +159,17 @@ k_flash(FlashArgs a) {
   };
   if (t_begin < ntiles) load_tile(t_begin);
 
+  // fragments of the score product: q16[s] = Y[yb*16 + m][16s + 4g .. +3], q1[j] the tail columns
+  float4 q16[PD];
+  float q1[NT > 0 ? NT : 1];
+  auto load_head = [&](int yb) {
+    const float* yrow = &tile[(yb * 16 + m) * PITCH + 4 * g];
+#pragma unroll
+    for (int s = 0; s < PD; ++s) q16[s] = *reinterpret_cast<const float4*>(yrow + 16 * s);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) q1[j] = tile[(yb * 16 + m) * PITCH + 16 * N16 + 4 * j + g];
+  };
+
   for (int t = t_begin; t < ntiles; ++t) {
     __syncthreads();
 #pragma unroll
@@ -161,112 +186,156 @@ k_flash(FlashArgs a) {
     if (t + 1 < ntiles) load_tile(t + 1);
 
     const int y0 = t * TY;
+    const int nblk = min(TY / 16, (n_y - y0 + 15) / 16);
+    load_head(0);
 #pragma unroll 1
-    for (int yb = 0; yb < TY / 16; ++yb) {
-      if (y0 + yb * 16 >= n_y) break;
-      // -- T[y][x]: lane (g, m), register r holds y = yb*16 + 4g + r, x = m
-      v4f tacc = (v4f){0.f, 0.f, 0.f, 0.f};
-      const float* yrow = &tile[(yb * 16 + m) * PITCH + 4 * g];
-#pragma unroll
-      for (int s = 0; s < GM::N16; ++s) {
-        const float4 yv = *reinterpret_cast<const float4*>(yrow + 16 * s);
-        tacc = mfma16(yv.x, xf[4 * s + 0], tacc);
-        tacc = mfma16(yv.y, xf[4 * s + 1], tacc);
-        tacc = mfma16(yv.z, xf[4 * s + 2], tacc);
-        tacc = mfma16(yv.w, xf[4 * s + 3], tacc);
-      }
-#pragma unroll
-      for (int j = 0; j < GM::NT; ++j) {
-        const float yv = tile[(yb * 16 + m) * PITCH + 16 * GM::N16 + 4 * j + g];
-        tacc = mfma16(yv, xf[4 * GM::N16 + j], tacc);
-      }
-      // -- scores
-      float sc[4], dist[4];
+    for (int yb = 0; yb < nblk; ++yb) {
       const int yl = yb * 16 + 4 * g;                      // first of this lane's 4 streamed rows
+      const float* yrow = &tile[(yb * 16 + m) * PITCH + 4 * g];
+      const float* ycol = &tile[yl * PITCH + m];
+      // row 0 of the second product's A operand, fetched under the score product
+      float ya[NC];
+      if (PASS != 3) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        sc[r] = tacc[r];
-        if (L2) {
-          const float d2 = fmaxf(xnorm + auy[yl + r] - 2.f * tacc[r], 0.f);
-          dist[r] = sqrtf(d2);
-          sc[r] = -dist[r];
-        }
-        if (PASS != 2 && y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
+        for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[16 * cb];
       }
-      if (PASS == 3) {
+      // -- T[y][x]: lane (g, m), register r holds y = yb*16 + 4g + r, x = m
+      v4f tacc[XB];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) cnt += sc[r] > posx ? 1 : 0;
-        continue;
+      for (int b = 0; b < XB; ++b) tacc[b] = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < N16; ++s) {
+        const float4 yv = q16[s % PD];
+        if (s + PD < N16) q16[s % PD] = *reinterpret_cast<const float4*>(yrow + 16 * (s + PD));
+#pragma unroll
+        for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.x, xf[b][4 * s + 0], tacc[b]);
+#pragma unroll
+        for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.y, xf[b][4 * s + 1], tacc[b]);
+#pragma unroll
+        for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.z, xf[b][4 * s + 2], tacc[b]);
+#pragma unroll
+        for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.w, xf[b][4 * s + 3], tacc[b]);
       }
-      float w[4];
-      if (PASS == 1) {
-        // Online softmax with a lazily updated reference: the common reference mrun of row x only
-        // moves when some score exceeds it by more than 16 (always true for the first block), so
-        // the cross-lane maximum and the rescale of the accumulators are off the common path;
-        // exp(score - mrun) <= e^16 cannot overflow.
-        const float mloc = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-        if (__any(mloc > mrun + 16.f)) {
-          float mall = fmaxf(mloc, __shfl_xor(mloc, 16));
-          mall = fmaxf(mall, __shfl_xor(mall, 32));
-          const float mnew = fmaxf(mrun, mall);
-          const float alpha = __expf(mrun - mnew);
-          lrun *= alpha;
 #pragma unroll
-          for (int cb = 0; cb < NC; ++cb) oacc[cb] *= alpha;
-          if (L2) wsum *= alpha;
-          mrun = mnew;
-        }
+      for (int j = 0; j < NT; ++j) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) w[r] = __expf(sc[r] - mrun);
-        lrun += (w[0] + w[1]) + (w[2] + w[3]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) w[r] = __expf(sc[r] - aux[yl + r]);
+        for (int b = 0; b < XB; ++b) tacc[b] = mfma16(q1[j], xf[b][4 * N16 + j], tacc[b]);
       }
+      // -- scores and weights
+      float w[XB][4];
+      float yy4[4] = {0.f, 0.f, 0.f, 0.f}, ls4[4] = {0.f, 0.f, 0.f, 0.f};
       if (L2) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) w[r] = dist[r] > 0.f ? w[r] / dist[r] : 0.f;
-        wsum += (w[0] + w[1]) + (w[2] + w[3]);
+        for (int r = 0; r < 4; ++r) yy4[r] = auy[yl + r];
       }
-      // -- O^T[c][x] += sum_y Y[y][c] W[y][x]: A = Y fragment (row c), B = W (lane x)
-      const float* ycol = &tile[yl * PITCH + m];
+      if (PASS == 2) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 4; ++r) ls4[r] = aux[yl + r];
+      }
 #pragma unroll
-        for (int cb = 0; cb < NC; ++cb) oacc[cb] = mfma16(ycol[r * PITCH + 16 * cb], w[r], oacc[cb]);
+      for (int b = 0; b < XB; ++b) {
+        float sc[4], dist[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          sc[r] = tacc[b][r];
+          if (L2) {
+            const float d2 = fmaxf(xnorm[b] + yy4[r] - 2.f * tacc[b][r], 0.f);
+            dist[r] = sqrtf(d2);
+            sc[r] = -dist[r];
+          }
+          if (PASS != 2 && y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
+        }
+        if (PASS == 3) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cnt[b] += sc[r] > posx[b] ? 1 : 0;
+        } else if (PASS == 1) {
+          // Online softmax with a lazily updated reference: the common reference mrun of row x only
+          // moves when some score exceeds it by more than 16 (always true for the first block), so
+          // the cross-lane maximum and the rescale of the accumulators are off the common path;
+          // exp(score - mrun) <= e^16 cannot overflow.
+          const float mloc = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+          if (__any(mloc > mrun[b] + 16.f)) {
+            float mall = fmaxf(mloc, __shfl_xor(mloc, 16));
+            mall = fmaxf(mall, __shfl_xor(mall, 32));
+            const float mnew = fmaxf(mrun[b], mall);
+            const float alpha = __expf(mrun[b] - mnew);
+            lrun[b] *= alpha;
+#pragma unroll
+            for (int cb = 0; cb < NC; ++cb) oacc[b][cb] *= alpha;
+            if (L2) wsum[b] *= alpha;
+            mrun[b] = mnew;
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) w[b][r] = __expf(sc[r] - mrun[b]);
+          lrun[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) w[b][r] = __expf(sc[r] - ls4[r]);
+        }
+        if (PASS != 3 && L2) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) w[b][r] = dist[r] > 0.f ? w[b][r] / dist[r] : 0.f;
+          wsum[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
+        }
+      }
+      // first fragments of the next block's score product, fetched under the second product
+      if (yb + 1 < nblk) load_head(yb + 1);
+      if (PASS != 3) {
+        // -- O^T[c][x] += sum_y Y[y][c] W[y][x]: A = Y fragment (row c), B = W (lane x)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float cur[NC];
+#pragma unroll
+          for (int cb = 0; cb < NC; ++cb) cur[cb] = ya[cb];
+          if (r < 3) {
+#pragma unroll
+            for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[(r + 1) * PITCH + 16 * cb];
+          }
+#pragma unroll
+          for (int cb = 0; cb < NC; ++cb) {
+#pragma unroll
+            for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
+          }
+        }
       }
     }
   }
 
   // ---- epilogue
-  if (PASS == 3) {
-    cnt += __shfl_xor(cnt, 16);
-    cnt += __shfl_xor(cnt, 32);
-    if (g == 0 && xv) (side == MAR_SIDE_DST ? a.rank_dst : a.rank_src)[(size_t)c * a.S + x] = 1 + cnt;
-    return;
-  }
-  if (PASS == 1) {
-    float ltot = lrun + __shfl_xor(lrun, 16);
-    ltot += __shfl_xor(ltot, 32);
-    if (g == 0 && xv) *reinterpret_cast<float2*>(a.ml + (((size_t)part * 2 * a.B) + x_base + x) * 2) = make_float2(mrun, ltot);
-  }
-  if (L2) {
-    wsum += __shfl_xor(wsum, 16);
-    wsum += __shfl_xor(wsum, 32);
-  }
-  if (!xv) return;
-  float* orow = PASS == 1 ? a.out + ((size_t)part * 2 * a.B + x_base + x) * dk
-                          : a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] + part) * dk;
 #pragma unroll
-  for (int cb = 0; cb < NC; ++cb) {
-    const int col = 16 * cb + 4 * g;                       // O^T rows 16cb + 4g + r of lane's column x
-    if (col < dk) {
-      float4 o = make_float4(oacc[cb][0], oacc[cb][1], oacc[cb][2], oacc[cb][3]);
-      if (L2) {
-        const float4 xs = *reinterpret_cast<const float4*>(xrow + col);
-        o.x -= xs.x * wsum; o.y -= xs.y * wsum; o.z -= xs.z * wsum; o.w -= xs.w * wsum;
+  for (int b = 0; b < XB; ++b) {
+    if (PASS == 3) {
+      int cn = cnt[b];
+      cn += __shfl_xor(cn, 16);
+      cn += __shfl_xor(cn, 32);
+      if (g == 0 && xv[b]) (side == MAR_SIDE_DST ? a.rank_dst : a.rank_src)[(size_t)c * a.S + x[b]] = 1 + cn;
+      continue;
+    }
+    if (PASS == 1) {
+      float ltot = lrun[b] + __shfl_xor(lrun[b], 16);
+      ltot += __shfl_xor(ltot, 32);
+      if (g == 0 && xv[b])
+        *reinterpret_cast<float2*>(a.ml + (((size_t)part * 2 * a.B) + x_base + x[b]) * 2) = make_float2(mrun[b], ltot);
+    }
+    float ws = wsum[b];
+    if (L2) {
+      ws += __shfl_xor(ws, 16);
+      ws += __shfl_xor(ws, 32);
+    }
+    if (!xv[b]) continue;
+    float* orow = PASS == 1 ? a.out + ((size_t)part * 2 * a.B + x_base + x[b]) * dk
+                            : a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x[b]] + part) * dk;
+#pragma unroll
+    for (int cb = 0; cb < NC; ++cb) {
+      const int col = 16 * cb + 4 * g;                       // O^T rows 16cb + 4g + r of lane's column x
+      if (col < dk) {
+        float4 o = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
+        if (L2) {
+          const float4 xs = *reinterpret_cast<const float4*>(xrow[b] + col);
+          o.x -= xs.x * ws; o.y -= xs.y * ws; o.z -= xs.z * ws; o.w -= xs.w * ws;
+        }
+        *reinterpret_cast<float4*>(orow + col) = o;
       }
-      *reinterpret_cast<float4*>(orow + col) = o;
     }
   }
 }
@@ -275,9 +344,11 @@ k_flash(FlashArgs a) {
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
 int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of the instantiation that serves dk
 
-template <int NK, int NC, int TY>
+int mar_flash_stripe_rows(int dk) { return dk / 4 <= 32 ? 128 : 64; }   // 64 * XB of the instantiation
+
+template <int NK, int NC, int TY, int XB>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
-#define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, TY, P, L>), grid, dim3(256), 0, st, a)
+#define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, TY, XB, P, L>), grid, dim3(256), 0, st, a)
   if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
   else if (pass == 2) { if (l2) FL(2, 1); else FL(2, 0); }
   else { if (l2) FL(3, 1); else FL(3, 0); }
@@ -297,7 +368,8 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
   const int max_nx = pass == 2 ? d.N : (b.n < d.S ? b.n : d.S);
-  a.nstripes = (max_nx + 63) / 64;
+  const int sr = mar_flash_stripe_rows(d.dk);
+  a.nstripes = (max_nx + sr - 1) / sr;
   const int ncs = 2 * b.nchunks;
   a.sy = pass == 1 ? d.sy1 : (pass == 2 ? d.sy2 : 1);
   a.tps = pass == 1 ? d.tps1 : (pass == 2 ? d.tps2 : (1 << 30));
@@ -305,9 +377,9 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
-  if (nk <= 13) return launch_sized<13, 4, 64>(a, pass, l2, grid, st);
-  if (nk <= 25) return launch_sized<25, 7, 64>(a, pass, l2, grid, st);
-  if (nk <= 32) return launch_sized<32, 8, 64>(a, pass, l2, grid, st);
-  if (nk <= 64) return launch_sized<64, 16, 32>(a, pass, l2, grid, st);
-  return launch_sized<100, 25, 32>(a, pass, l2, grid, st);
+  if (nk <= 13) return launch_sized<13, 4, 64, 2>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 7, 64, 2>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 64, 2>(a, pass, l2, grid, st);
+  if (nk <= 64) return launch_sized<64, 16, 32, 1>(a, pass, l2, grid, st);
+  return launch_sized<100, 25, 32, 1>(a, pass, l2, grid, st);
 }
