@@ -56,7 +56,8 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   d->n_occ_max = n_occ;
   const int64_t ids = cfg->num_nodes + cfg->num_rels;
   d->u_max = ids < n_occ ? ids : n_occ;
-  d->nwords = (ids + 31) / 32;
+  d->ipw_log2 = ids <= ((int64_t)1 << 22) ? 2 : 5;       // small id spaces: one byte per id, no atomics
+  d->nwords = (ids + (1 << d->ipw_log2) - 1) >> d->ipw_log2;
   if (!mar_flash_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the contraction kernels", d->dk);
   // Small batches give too few (chunk-side, 64-row stripe) workgroups to fill 256 CUs: let several
   // workgroups share a stripe, each streaming a slice of the other matrix.
@@ -113,6 +114,7 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.gQ = (float*)take((size_t)d.sy1 * 2 * B * dk * 4);
   l.ml = (float*)take((size_t)d.sy1 * 2 * B * 2 * 4);
   l.G = (float*)take(n_pos * dk * 4);
+  l.Gu = (float*)take(u1 * dk * 4);
   l.carry = (float*)take(tasks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);
   l.rank_tmp = (int32_t*)take(2 * B * 4);
@@ -149,8 +151,12 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
   c->workspace = workspace; c->workspace_bytes = workspace_bytes;
   carve(d, (char*)workspace, &c->L);
   c->bitmap_dirty = 0; c->prof_max = 0; c->prof_steps = 0; c->prof_events = nullptr;
-  const hipError_t e = mar_launch_init(c, fill, (hipStream_t)hip_stream);
-  if (e != hipSuccess) { delete c; return hip_fail(e, "init kernels"); }
+  c->aux = nullptr; c->ev_fork = c->ev_index = c->ev_pass1 = c->ev_chain = nullptr;
+  hipError_t e = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking);
+  hipEvent_t* evs[4] = {&c->ev_fork, &c->ev_index, &c->ev_pass1, &c->ev_chain};
+  for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(evs[i], hipEventDisableTiming);
+  if (e == hipSuccess) e = mar_launch_init(c, fill, (hipStream_t)hip_stream);
+  if (e != hipSuccess) { mar_destroy(c); return hip_fail(e, "context set-up"); }
   *out = c;
   return MAR_OK;
 }
@@ -158,9 +164,12 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
 extern "C" int mar_destroy(mar_ctx* c) {
   if (!c) return MAR_OK;
   if (c->prof_events) {
-    for (int i = 0; i < c->prof_max * (MAR_NUM_PHASES + 1); ++i) (void)hipEventDestroy(c->prof_events[i]);
+    for (int i = 0; i < c->prof_max * 2 * MAR_NUM_PHASES; ++i) (void)hipEventDestroy(c->prof_events[i]);
     free(c->prof_events);
   }
+  hipEvent_t evs[4] = {c->ev_fork, c->ev_index, c->ev_pass1, c->ev_chain};
+  for (int i = 0; i < 4; ++i) if (evs[i]) (void)hipEventDestroy(evs[i]);
+  if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
   delete c;
   return MAR_OK;
 }
@@ -211,24 +220,40 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
     HIP_TRY(mar_launch_clear_bitmap(c, st), "bitmap reset");
     c->bitmap_dirty = 0;
   }
+  // Two streams: the caller's carries the gather and the two contraction passes; the index build
+  // (needed first by pass 2) and the chain rule (needs pass 1 only) run beside them on `aux`.
+  hipStream_t ax = c->aux;
   hipEvent_t* ev = nullptr;
-  if (c->prof_events && c->prof_steps < c->prof_max) ev = c->prof_events + (size_t)c->prof_steps * (MAR_NUM_PHASES + 1);
-  int evi = 0;
-#define MARK() do { if (ev) HIP_TRY(hipEventRecord(ev[evi++], st), "event record"); } while (0)
-  MARK();
-  HIP_TRY(mar_launch_index(c, b, st), "index kernels");
-  if (dbg) HIP_TRY(mar_launch_debug_copy(c, b, dbg, st), "debug copy");
-  MARK();
-  HIP_TRY(mar_launch_prep(c, b, 1, dbg ? dbg->pos : nullptr, st), "gather kernel");
-  MARK();
+  if (c->prof_events && c->prof_steps < c->prof_max) ev = c->prof_events + (size_t)c->prof_steps * 2 * MAR_NUM_PHASES;
+#define MARK(phase, end, stream) do { if (ev) HIP_TRY(hipEventRecord(ev[2 * (phase) + (end)], stream), "event record"); } while (0)
+  HIP_TRY(hipEventRecord(c->ev_fork, st), "fork");
+  HIP_TRY(hipStreamWaitEvent(ax, c->ev_fork, 0), "fork");
+  MARK(0, 0, ax);
+  HIP_TRY(mar_launch_index(c, b, ax), "index kernels");
+  HIP_TRY(mar_launch_positions(c, b, ax), "position kernel");
+  if (dbg) HIP_TRY(mar_launch_debug_copy(c, b, dbg, ax), "debug copy");
+  MARK(0, 1, ax);
+  HIP_TRY(hipEventRecord(c->ev_index, ax), "join");
+  MARK(1, 0, st);
+  HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, st), "gather kernel");
+  MARK(1, 1, st);
+  MARK(2, 0, st);
   HIP_TRY(mar_launch_flash(c, b, 1, nullptr, nullptr, st), "score/softmax kernel");
-  MARK();
+  MARK(2, 1, st);
+  HIP_TRY(hipEventRecord(c->ev_pass1, st), "fork");
+  HIP_TRY(hipStreamWaitEvent(ax, c->ev_pass1, 0), "fork");
+  MARK(4, 0, ax);
+  HIP_TRY(mar_launch_chain(c, b, ax), "chain-rule kernel");
+  MARK(4, 1, ax);
+  HIP_TRY(hipEventRecord(c->ev_chain, ax), "join");
+  HIP_TRY(hipStreamWaitEvent(st, c->ev_index, 0), "join");
+  MARK(3, 0, st);
   HIP_TRY(mar_launch_flash(c, b, 2, nullptr, nullptr, st), "negative-gradient kernel");
-  MARK();
-  HIP_TRY(mar_launch_chain(c, b, st), "chain-rule kernel");
-  MARK();
+  MARK(3, 1, st);
+  HIP_TRY(hipStreamWaitEvent(st, c->ev_chain, 0), "join");
+  MARK(5, 0, st);
   HIP_TRY(mar_launch_reduce(c, b, loss_sum_out, dbg ? dbg->grad_rows : nullptr, st), "reduce/Adagrad kernels");
-  MARK();
+  MARK(5, 1, st);
 #undef MARK
   if (ev) c->prof_steps++;
   if (dbg) {
@@ -248,7 +273,7 @@ extern "C" int mar_eval_scores(mar_ctx* c, const int32_t* src, const int32_t* re
   if (!rank_dst || !rank_src) return fail(MAR_EINVAL, "a rank output pointer is NULL");
   if (n_edges == 0) return MAR_OK;
   hipStream_t st = (hipStream_t)hip_stream;
-  HIP_TRY(mar_launch_prep(c, b, 0, pos_scores, st), "gather kernel");
+  HIP_TRY(mar_launch_prep(c, b, pos_scores, st), "gather kernel");
   HIP_TRY(mar_launch_flash(c, b, 3, rank_dst, rank_src, st), "rank kernel");
   return MAR_OK;
 }
@@ -258,13 +283,13 @@ extern "C" int mar_profile_enable(mar_ctx* c, int32_t max_steps) {
   if (!c) return fail(MAR_EINVAL, "context is NULL");
   if (max_steps < 0 || max_steps > MAR_MAX_PROFILE_STEPS) return fail(MAR_ERANGE, "max_steps outside 0..%d", MAR_MAX_PROFILE_STEPS);
   if (c->prof_events) {
-    for (int i = 0; i < c->prof_max * (MAR_NUM_PHASES + 1); ++i) (void)hipEventDestroy(c->prof_events[i]);
+    for (int i = 0; i < c->prof_max * 2 * MAR_NUM_PHASES; ++i) (void)hipEventDestroy(c->prof_events[i]);
     free(c->prof_events);
     c->prof_events = nullptr;
   }
   c->prof_max = 0; c->prof_steps = 0;
   if (max_steps == 0) return MAR_OK;
-  const size_t ne = (size_t)max_steps * (MAR_NUM_PHASES + 1);
+  const size_t ne = (size_t)max_steps * 2 * MAR_NUM_PHASES;
   c->prof_events = (hipEvent_t*)calloc(ne, sizeof(hipEvent_t));
   if (!c->prof_events) return fail(MAR_ENOMEM, "out of host memory");
   for (size_t i = 0; i < ne; ++i) {
@@ -284,12 +309,13 @@ extern "C" int mar_profile_read(mar_ctx* c, double* ms, int32_t* steps) {
   for (int p = 0; p < MAR_NUM_PHASES; ++p) ms[p] = 0.0;
   *steps = c->prof_steps;
   for (int s = 0; s < c->prof_steps; ++s) {
-    hipEvent_t* ev = c->prof_events + (size_t)s * (MAR_NUM_PHASES + 1);
-    hipError_t e = hipEventSynchronize(ev[MAR_NUM_PHASES]);
+    hipEvent_t* ev = c->prof_events + (size_t)s * 2 * MAR_NUM_PHASES;
+    hipError_t e = hipEventSynchronize(ev[2 * MAR_NUM_PHASES - 1]);
+    if (e == hipSuccess) e = hipEventSynchronize(ev[2 * 4 + 1]);
     if (e != hipSuccess) return hip_fail(e, "event synchronize");
     for (int p = 0; p < MAR_NUM_PHASES; ++p) {
       float t = 0.f;
-      e = hipEventElapsedTime(&t, ev[p], ev[p + 1]);
+      e = hipEventElapsedTime(&t, ev[2 * p], ev[2 * p + 1]);
       if (e != hipSuccess) return hip_fail(e, "event elapsed time");
       ms[p] += t;
     }

@@ -32,6 +32,7 @@ struct MarLayout {
   float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
   float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
   float*    G;            // [n_occ][dk] one gradient row per occurrence, in row-sorted order
+  float*    Gu;           // [u_max][dk] summed gradient per unique row
   float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders
   float*    loss_part;    // per-block partial loss sums
   int32_t*  rank_tmp;     // [2][batch] scratch ranks when the caller passes none
@@ -47,7 +48,8 @@ struct MarDims {
   int32_t tps1, tps2;              // streamed tiles per workgroup
   int32_t ty;                      // rows per streamed tile
   int64_t u_max;                   // min(num_nodes + num_rels, n_occ_max)
-  int64_t nwords;                  // bitmap words
+  int64_t nwords;                  // words of the touched-id map
+  int32_t ipw_log2;                // ids per word: 5 = one bit per id (atomic marks), 2 = one byte per id (plain stores)
 };
 
 #define MAR_MAX_PROFILE_STEPS 4096
@@ -59,9 +61,12 @@ struct mar_ctx {
   void* workspace; size_t workspace_bytes;
   MarLayout L;
   int bitmap_dirty;                // a failed step may leave bits set
+  // second stream for work that is independent of the contraction passes, and its fork/join events
+  hipStream_t aux;
+  hipEvent_t ev_fork, ev_index, ev_pass1, ev_chain;
   // profiling
   int32_t prof_max, prof_steps;
-  hipEvent_t* prof_events;         // (MAR_NUM_PHASES + 1) per step
+  hipEvent_t* prof_events;         // 2 * MAR_NUM_PHASES per step (begin, end of each phase)
 };
 
 void mar_set_error(const char* fmt, ...);
@@ -86,7 +91,8 @@ struct MarBatch {
 };
 
 hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st);
-hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, int train, float* pos_out, hipStream_t st);
+hipError_t mar_launch_positions(const mar_ctx* c, const MarBatch& b, hipStream_t st);
+hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, hipStream_t st);
 hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32_t* rank_dst, int32_t* rank_src,
                             hipStream_t st);
 hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st);

@@ -344,7 +344,7 @@ k_flash(FlashArgs a) {
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
 int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of the instantiation that serves dk
 
-int mar_flash_stripe_rows(int dk) { return dk / 4 <= 32 ? 128 : 64; }   // 64 * XB of the instantiation
+int mar_flash_stripe_rows(int dk) { (void)dk; return 64; }   // 64 * XB of the instantiation
 
 template <int NK, int NC, int TY, int XB>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
@@ -377,9 +377,9 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
-  if (nk <= 13) return launch_sized<13, 4, 64, 2>(a, pass, l2, grid, st);
-  if (nk <= 25) return launch_sized<25, 7, 64, 2>(a, pass, l2, grid, st);
-  if (nk <= 32) return launch_sized<32, 8, 64, 2>(a, pass, l2, grid, st);
+  if (nk <= 13) return launch_sized<13, 4, 64, 1>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 7, 64, 1>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 64, 1>(a, pass, l2, grid, st);
   if (nk <= 64) return launch_sized<64, 16, 32, 1>(a, pass, l2, grid, st);
   return launch_sized<100, 25, 32, 1>(a, pass, l2, grid, st);
 }

@@ -105,57 +105,79 @@ __device__ __forceinline__ int32_t occ_unified_id(const OccArgs& a, int64_t k) {
   return a.neg_src[k - a.cn];
 }
 
-// For every lane: the set of lanes of the wave that hold the same key (inactive lanes get 0).
-// Every lane of the wave must call this.
-__device__ __forceinline__ uint64_t wave_match(int key, bool active) {
-  uint64_t mine = 0;
-  uint64_t pend = __ballot(active);
-  while (pend) {
-    const int leader = __ffsll((unsigned long long)pend) - 1;
-    const int k = __shfl(key, leader);
-    const uint64_t m = __ballot(active && key == k);
-    if (active && key == k) mine = m;
-    pend &= ~m;
-  }
-  return mine;
+// ------------------------------------------------------------- touched-id map -----
+// One word holds 2^L ids: L = 5 is a bitmap (marks need atomics), L = 2 one byte per id
+// (marks are plain byte stores).  Same-address -- in practice same-cache-line -- atomics
+// serialise at tens of ns each, so the bitmap is only used when the id space is large and
+// therefore sparse; small dense id spaces take the byte map.
+__device__ __forceinline__ uint32_t map_bitpos(uint32_t id, int L) { return (id & ((1u << L) - 1u)) * (32u >> L); }
+
+// Block-wide grouping of equal keys through an LDS hash table (open addressing).
+#define AGG_THREADS 1024
+#define AGG_SLOTS 2048
+struct BlockAgg {
+  int key[AGG_SLOTS];
+  uint32_t cnt[AGG_SLOTS];
+  uint32_t base[AGG_SLOTS];
+};
+
+__device__ __forceinline__ void agg_clear(BlockAgg& t) {
+  for (int i = threadIdx.x; i < AGG_SLOTS; i += AGG_THREADS) { t.key[i] = -1; t.cnt[i] = 0u; }
 }
 
-// Marks the bitmap and zeroes the per-rank counters for this step.  Same-address atomics
-// serialise (tens of ns each), so a hot id must not issue one per occurrence: identical ids
-// inside a wave issue one, the bit is tested first with a device-coherent load, and the grid
-// is small enough that later rounds of the loop already see the bits of hot ids.
-__global__ void __launch_bounds__(256)
-k_mark(OccArgs a, int64_t n_occ, uint32_t* __restrict__ bitmap, uint32_t* __restrict__ count, int64_t n_count) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int lane = threadIdx.x & 63;
+// Inserts key, adds mult to its group; returns the slot through `h` and the group-local offset.
+__device__ __forceinline__ uint32_t agg_insert(BlockAgg& t, int key, uint32_t mult, int* h_out) {
+  int h = (int)(((uint32_t)key * 2654435761u) >> 21);          // 11 bits
+  for (;;) {
+    const int prev = atomicCAS(&t.key[h], -1, key);
+    if (prev == -1 || prev == key) break;
+    h = (h + 1) & (AGG_SLOTS - 1);
+  }
+  *h_out = h;
+  return atomicAdd(&t.cnt[h], mult);
+}
+
+// Marks the touched-id map and zeroes the per-rank counters for this step.
+__global__ void __launch_bounds__(AGG_THREADS)
+k_mark(OccArgs a, int64_t n_occ, int L, uint32_t* __restrict__ bitmap, uint32_t* __restrict__ count, int64_t n_count) {
+  __shared__ BlockAgg tab;
+  const int64_t stride = (int64_t)gridDim.x * AGG_THREADS;
+  const int64_t t0 = (int64_t)blockIdx.x * AGG_THREADS + threadIdx.x;
   for (int64_t i = t0; i < n_count; i += stride) count[i] = 0u;
+  if (L == 2) {
+    unsigned char* bytes = reinterpret_cast<unsigned char*>(bitmap);
+    for (int64_t k = t0; k < n_occ; k += stride) bytes[(uint32_t)occ_unified_id(a, k)] = 1;
+    return;
+  }
+  // bitmap: one atomic per distinct id of the block, and none if the bit is already visible
   const int64_t rounds = (n_occ + stride - 1) / stride;
   for (int64_t it = 0; it < rounds; ++it) {
+    agg_clear(tab);
+    __syncthreads();
     const int64_t k = it * stride + t0;
-    const bool active = k < n_occ;
-    const uint32_t id = active ? (uint32_t)occ_unified_id(a, k) : 0u;
-    const uint64_t same = wave_match((int)id, active);
-    if (active && (__ffsll((unsigned long long)same) - 1) == lane) {
-      const uint32_t bit = 1u << (id & 31u);
-      uint32_t* w = bitmap + (id >> 5);
-      if (!(__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(w, bit);
+    if (k < n_occ) { int h; agg_insert(tab, occ_unified_id(a, k), 0u, &h); }
+    __syncthreads();
+    for (int i = threadIdx.x; i < AGG_SLOTS; i += AGG_THREADS) {
+      const int key = tab.key[i];
+      if (key >= 0) {
+        const uint32_t id = (uint32_t)key, bit = 1u << (id & 31u);
+        uint32_t* w = bitmap + (id >> 5);
+        if (!(__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(w, bit);
+      }
     }
+    __syncthreads();
   }
 }
 
 // ------------------------------------------------------------------------- scans -----
-// Exclusive prefix sums over f(in[i]); f = popcount for the bitmap, identity for counts.
-// Elements per block: 256 threads x 16.
-#define SCAN_PER_THREAD 16
-#define SCAN_BLOCK_ELEMS (256 * SCAN_PER_THREAD)
-
+// Exclusive prefix sums over f(in[i]); f = popcount for the touched-id map, identity for counts.
 template <int POPC> __device__ __forceinline__ uint32_t scan_f(uint32_t v) { return POPC ? (uint32_t)__popc(v) : v; }
 
-// Block-wide exclusive scan of one value per thread (256 threads); returns the exclusive
+// Block-wide exclusive scan of one value per thread (BT threads); returns the exclusive
 // prefix and the block total through `total`.
-__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* total) {
-  __shared__ uint32_t wave_tot[4];
+template <int BT>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* total) {
+  __shared__ uint32_t wave_tot[BT / 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t inc = v;
 #pragma unroll
@@ -168,7 +190,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
   __syncthreads();
   uint32_t base = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
+  for (int w = 0; w < BT / 64; ++w) {
     const uint32_t t = wave_tot[w];
     if (w < wave) base += t;
     tot += t;
@@ -176,6 +198,9 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
   *total = tot;
   return base + inc - v;
 }
+
+#define SCAN_PER_THREAD 16
+#define SCAN_BLOCK_ELEMS (256 * SCAN_PER_THREAD)
 
 template <int POPC>
 __global__ void __launch_bounds__(256)
@@ -185,7 +210,7 @@ k_scan_block_sums(const uint32_t* __restrict__ in, int64_t n, uint32_t* __restri
 #pragma unroll
   for (int j = 0; j < SCAN_PER_THREAD; ++j) if (base + j < n) s += scan_f<POPC>(in[base + j]);
   uint32_t tot;
-  block_exclusive_scan_256(s, &tot);
+  block_exclusive_scan<256>(s, &tot);
   if (threadIdx.x == 0) bsum[blockIdx.x] = tot;
 }
 
@@ -196,109 +221,110 @@ __global__ void __launch_bounds__(256) k_scan_bsum(uint32_t* __restrict__ bsum, 
     const int64_t i = b0 + threadIdx.x;
     const uint32_t v = i < nb ? bsum[i] : 0u;
     uint32_t tot;
-    const uint32_t ex = block_exclusive_scan_256(v, &tot);
+    const uint32_t ex = block_exclusive_scan<256>(v, &tot);
     if (i < nb) bsum[i] = carry + ex;
     carry += tot;
   }
 }
 
-// Writes out[i] = exclusive prefix.  With POPC: also emits the ascending ids of the set bits,
-// the unique-row total into scalars[0] and the number of set bits below `split_bit` (the
-// first relation's unified id) into scalars[1].  With `single_block` the kernel loops over the
-// whole input itself and needs no block sums.
-template <int POPC>
-__global__ void __launch_bounds__(256)
-k_scan_apply(const uint32_t* __restrict__ in, int64_t n, const uint32_t* __restrict__ bsum, int single_block,
-             uint32_t* __restrict__ out, int32_t* __restrict__ uniq, int32_t* __restrict__ scalars, int64_t split_bit) {
-  const int64_t nblk = (n + SCAN_BLOCK_ELEMS - 1) / SCAN_BLOCK_ELEMS;
+// Writes out[i] = exclusive prefix.  With POPC: also emits the ascending ids of the marked
+// positions (L = log2 ids per word), the unique-row total into scalars[0] and the number of
+// marks below `split_id` (the first relation's unified id) into scalars[1].  With
+// `single_block` the kernel loops over the whole input itself and needs no block sums.
+template <int POPC, int BT, int PER>
+__global__ void __launch_bounds__(BT)
+k_scan_apply(const uint32_t* __restrict__ in, int64_t n, const uint32_t* __restrict__ bsum, int single_block, int L,
+             uint32_t* __restrict__ out, int32_t* __restrict__ uniq, int32_t* __restrict__ scalars, int64_t split_id) {
+  constexpr int ELEMS = BT * PER;
+  const int64_t nblk = (n + ELEMS - 1) / ELEMS;
+  const int bpi = 32 >> L;                                   // bits per id
   uint32_t carry = 0;
   for (int64_t blk = single_block ? 0 : blockIdx.x; blk < nblk; blk += single_block ? 1 : gridDim.x) {
-    const int64_t base = blk * SCAN_BLOCK_ELEMS + (int64_t)threadIdx.x * SCAN_PER_THREAD;
-    uint32_t v[SCAN_PER_THREAD];
+    const int64_t base = blk * ELEMS + (int64_t)threadIdx.x * PER;
+    uint32_t v[PER];
     uint32_t s = 0;
 #pragma unroll
-    for (int j = 0; j < SCAN_PER_THREAD; ++j) {
+    for (int j = 0; j < PER; ++j) {
       v[j] = base + j < n ? in[base + j] : 0u;
       s += scan_f<POPC>(v[j]);
     }
     uint32_t tot;
-    uint32_t run = block_exclusive_scan_256(s, &tot) + (single_block ? carry : bsum[blk]);
+    uint32_t run = block_exclusive_scan<BT>(s, &tot) + (single_block ? carry : bsum[blk]);
     carry += tot;
 #pragma unroll
-    for (int j = 0; j < SCAN_PER_THREAD; ++j) {
+    for (int j = 0; j < PER; ++j) {
       if (base + j < n) {
         out[base + j] = run;
         if (POPC) {
           uint32_t w = v[j];
-          const int64_t id0 = (base + j) << 5;
-          if (id0 <= split_bit && split_bit < id0 + 32)
-            scalars[1] = (int32_t)(run + __popc(w & ((1u << (split_bit - id0)) - 1u)));
+          const int64_t id0 = (base + j) << L;
+          if (id0 <= split_id && split_id < id0 + (1 << L))
+            scalars[1] = (int32_t)(run + __popc(w & ((1u << ((split_id - id0) * bpi)) - 1u)));
           uint32_t r = run;
           while (w) {
             const int b = __ffs(w) - 1;
-            uniq[r++] = (int32_t)(id0 + b);
+            uniq[r++] = (int32_t)(id0 + b / bpi);
             w &= w - 1;
           }
         }
         run += scan_f<POPC>(v[j]);
       }
     }
-    if (POPC && base <= n - 1 && n - 1 < base + SCAN_PER_THREAD) scalars[0] = (int32_t)run;   // thread owning the last word
+    if (POPC && base <= n - 1 && n - 1 < base + PER) scalars[0] = (int32_t)run;   // thread owning the last word
   }
 }
 
 template <int POPC>
-static hipError_t scan_u32(const uint32_t* in, int64_t n, uint32_t* out, uint32_t* bsum, int32_t* uniq,
-                           int32_t* scalars, int64_t split_bit, hipStream_t st) {
-  const int64_t nblk = (n + SCAN_BLOCK_ELEMS - 1) / SCAN_BLOCK_ELEMS;
-  if (nblk <= 16) {
-    hipLaunchKernelGGL(k_scan_apply<POPC>, dim3(1), dim3(256), 0, st, in, n, bsum, 1, out, uniq, scalars, split_bit);
-    return hipGetLastError();
+static hipError_t scan_u32(const uint32_t* in, int64_t n, int L, uint32_t* out, uint32_t* bsum, int32_t* uniq,
+                           int32_t* scalars, int64_t split_id, hipStream_t st) {
+  if (n <= 1024) {
+    hipLaunchKernelGGL((k_scan_apply<POPC, 1024, 1>), dim3(1), dim3(1024), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
+  } else if (n <= 4096 * 4) {
+    hipLaunchKernelGGL((k_scan_apply<POPC, 1024, 4>), dim3(1), dim3(1024), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
+  } else if (n <= 16384 * 8) {
+    hipLaunchKernelGGL((k_scan_apply<POPC, 1024, 16>), dim3(1), dim3(1024), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
+  } else {
+    const int64_t nblk = (n + SCAN_BLOCK_ELEMS - 1) / SCAN_BLOCK_ELEMS;
+    hipLaunchKernelGGL(k_scan_block_sums<POPC>, dim3((unsigned)nblk), dim3(256), 0, st, in, n, bsum);
+    hipLaunchKernelGGL(k_scan_bsum, dim3(1), dim3(256), 0, st, bsum, nblk);
+    hipLaunchKernelGGL((k_scan_apply<POPC, 256, SCAN_PER_THREAD>), dim3((unsigned)nblk), dim3(256), 0, st, in, n, bsum, 0, L, out,
+                       uniq, scalars, split_id);
   }
-  hipLaunchKernelGGL(k_scan_block_sums<POPC>, dim3((unsigned)nblk), dim3(256), 0, st, in, n, bsum);
-  hipLaunchKernelGGL(k_scan_bsum, dim3(1), dim3(256), 0, st, bsum, nblk);
-  hipLaunchKernelGGL(k_scan_apply<POPC>, dim3((unsigned)nblk), dim3(256), 0, st, in, n, bsum, 0, out, uniq, scalars, split_bit);
   return hipGetLastError();
 }
 
 // -------------------------------------------------------- rank + slot per occurrence -----
-// Wave-aggregated counter increment by `mult` per lane (the same for every active lane of the
-// wave): lanes that share a key issue one atomic together, and all leaders issue theirs in the
-// same instruction.  Every lane of the wave must call this.
-__device__ __forceinline__ int wave_agg_inc(uint32_t* __restrict__ counters, int key, bool active, int mult) {
-  const int lane = threadIdx.x & 63;
-  const uint64_t same = wave_match(key, active);
-  const int leader = active ? __ffsll((unsigned long long)same) - 1 : lane;
-  int base = 0;
-  if (active && leader == lane) base = (int)atomicAdd(&counters[key], (uint32_t)(mult * __popcll(same)));
-  base = __shfl(base, leader);
-  return base + mult * __popcll(same & ((1ull << lane) - 1ull));
-}
-
-// Rank of every occurrence's row and its slot inside the row's segment.  An occurrence of a
-// negative takes neg_mult consecutive slots (one gradient row per workgroup that shares its
-// stripe); the two kinds are walked in separate passes so a wave never mixes multiplicities.
-__global__ void __launch_bounds__(256)
-k_count(OccArgs a, int64_t n_occ, int neg_mult, const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ word_prefix,
-        uint32_t* __restrict__ count, int32_t* __restrict__ inv, int32_t* __restrict__ slot) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+// Rank of every occurrence's row and its slot inside the row's segment.  Equal ranks inside a
+// block are grouped in LDS and issue one global atomic together (a hot row is hit by a large
+// share of the occurrences).  An occurrence of a negative takes neg_mult consecutive slots (one
+// gradient row per workgroup that shares its stripe).
+__global__ void __launch_bounds__(AGG_THREADS)
+k_count(OccArgs a, int64_t n_occ, int neg_mult, int L, const uint32_t* __restrict__ bitmap,
+        const uint32_t* __restrict__ word_prefix, uint32_t* __restrict__ count, int32_t* __restrict__ inv,
+        int32_t* __restrict__ slot) {
+  __shared__ BlockAgg tab;
+  const int64_t stride = (int64_t)gridDim.x * AGG_THREADS;
+  const int64_t rounds = (n_occ + stride - 1) / stride;          // same trip count for every thread
   const int64_t n_pos_occ = 3 * (int64_t)a.n;
-  for (int pass = 0; pass < 2; ++pass) {
-    const int64_t lo = pass == 0 ? 0 : n_pos_occ, hi = pass == 0 ? n_pos_occ : n_occ;
-    const int mult = pass == 0 ? 1 : neg_mult;
-    const int64_t rounds = (hi - lo + stride - 1) / stride;        // same trip count for every lane
-    for (int64_t it = 0; it < rounds; ++it) {
-      const int64_t k = lo + it * stride + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-      const bool active = k < hi;
-      int rank = 0;
-      if (active) {
-        const uint32_t id = (uint32_t)occ_unified_id(a, k);
-        const uint32_t w = id >> 5, bit = 1u << (id & 31u);
-        rank = (int)(word_prefix[w] + __popc(bitmap[w] & (bit - 1u)));
-      }
-      const int sl = wave_agg_inc(count, rank, active, mult);
-      if (active) { inv[k] = rank; slot[k] = sl; }
+  for (int64_t it = 0; it < rounds; ++it) {
+    agg_clear(tab);
+    __syncthreads();
+    const int64_t k = it * stride + (int64_t)blockIdx.x * AGG_THREADS + threadIdx.x;
+    const bool active = k < n_occ;
+    int rank = 0, h = 0;
+    uint32_t local = 0;
+    if (active) {
+      const uint32_t id = (uint32_t)occ_unified_id(a, k);
+      const uint32_t w = id >> L;
+      rank = (int)(word_prefix[w] + __popc(bitmap[w] & ((1u << map_bitpos(id, L)) - 1u)));
+      local = agg_insert(tab, rank, k < n_pos_occ ? 1u : (uint32_t)neg_mult, &h);
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < AGG_SLOTS; i += AGG_THREADS)
+      if (tab.key[i] >= 0) tab.base[i] = atomicAdd(&count[tab.key[i]], tab.cnt[i]);
+    __syncthreads();
+    if (active) { inv[k] = rank; slot[k] = (int32_t)(tab.base[h] + local); }
+    __syncthreads();
   }
 }
 
@@ -363,12 +389,13 @@ hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st)
   OccArgs a{b.src, b.rel, b.dst, b.neg_src, b.neg_dst, b.n, b.cn, (int32_t)d.num_nodes};
   const int64_t n_count = d.u_max + 1;
   const int64_t work = b.n_occ > n_count ? b.n_occ : n_count;
-  hipLaunchKernelGGL(k_mark, dim3(grid_for(work / 8, 256, 256)), dim3(256), 0, st, a, b.n_occ, L.bitmap, L.count, n_count);
-  hipError_t e = scan_u32<1>(L.bitmap, d.nwords, L.word_prefix, L.bsum, L.uniq, L.scalars, d.num_nodes, st);
+  hipLaunchKernelGGL(k_mark, dim3(grid_for(work, AGG_THREADS, 1024)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.ipw_log2,
+                     L.bitmap, L.count, n_count);
+  hipError_t e = scan_u32<1>(L.bitmap, d.nwords, d.ipw_log2, L.word_prefix, L.bsum, L.uniq, L.scalars, d.num_nodes, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, 256, 2048)), dim3(256), 0, st, a, b.n_occ, (int)d.sy2, L.bitmap,
-                     L.word_prefix, L.count, L.inv, L.slot);
-  return scan_u32<0>(L.count, n_count, L.seg_off, L.bsum, nullptr, nullptr, -1, st);
+  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, AGG_THREADS, 1024)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.sy2,
+                     (int)d.ipw_log2, L.bitmap, L.word_prefix, L.count, L.inv, L.slot);
+  return scan_u32<0>(L.count, n_count, 5, L.seg_off, L.bsum, nullptr, nullptr, -1, st);
 }
 
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st) {

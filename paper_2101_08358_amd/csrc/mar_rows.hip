@@ -19,9 +19,31 @@ template <int GL> __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// -------------------------------------------------------------------- positions -----
+// Occurrence -> position in row-sorted order (a negative owns sy2 consecutive positions, one
+// per workgroup sharing its stripe in the second contraction pass); also clears the
+// occurrence's word of the touched-id map for the next step.
+__global__ void __launch_bounds__(256)
+k_positions(RowArgs a, int ipw_log2, const uint32_t* __restrict__ seg_off, const int32_t* __restrict__ inv,
+            const int32_t* __restrict__ slot, int32_t* __restrict__ occ_pos, int32_t* __restrict__ rank_sorted,
+            uint32_t* __restrict__ bitmap) {
+  const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (k >= a.n_occ) return;
+  const int r = inv[k];
+  const int p = (int)seg_off[r] + slot[k];
+  occ_pos[k] = p;
+  const int rows = k < 3 * (int64_t)a.n ? 1 : a.sy2;
+  for (int i = 0; i < rows; ++i) rank_sorted[p + i] = r;
+  // unified id of the occurrence (same numbering as the index kernels)
+  int64_t kk2 = k; uint32_t id;
+  if (kk2 < a.n) id = a.src[kk2];
+  else if (kk2 < 2 * (int64_t)a.n) id = a.dst[kk2 - a.n];
+  else if (kk2 < 3 * (int64_t)a.n) id = a.num_nodes + a.rel[kk2 - 2 * (int64_t)a.n];
+  else { kk2 -= 3 * (int64_t)a.n; id = kk2 < a.cn ? a.neg_dst[kk2] : a.neg_src[kk2 - a.cn]; }
+  bitmap[id >> ipw_log2] = 0u;
+}
+
 // ---------------------------------------------------------------------- gather -----
-// Section A (train only): occurrence -> position in row-sorted order; clears the occurrence's
-//   bitmap word for the next step.
 // Section B: one lane group per edge builds the two edge-side operands
 //     side DST (negatives replace d): a_ej = <q, n_j>,  q = s*r (DistMult), s.r complex (ComplEx)
 //     side SRC (negatives replace s): b_ej = <q, m_j>,  q = r*d,            conj(r).d
@@ -29,29 +51,10 @@ template <int GL> __device__ __forceinline__ float group_sum(float v) {
 // Section C: one lane group per negative copies its row into the dense per-chunk matrix.
 template <int GL>
 __global__ void __launch_bounds__(256)
-k_prep(RowArgs a, int train, int nbA, int nbB, const uint32_t* __restrict__ seg_off, const int32_t* __restrict__ inv,
-       const int32_t* __restrict__ slot, int32_t* __restrict__ occ_pos, int32_t* __restrict__ rank_sorted,
-       uint32_t* __restrict__ bitmap, float* __restrict__ Q, float* __restrict__ Km, float* __restrict__ qq,
+k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float* __restrict__ qq,
        float* __restrict__ kk, float* __restrict__ pos, float* __restrict__ pos_user) {
   const int blk = blockIdx.x;
-  if (blk < nbA) {
-    const int64_t k = (int64_t)blk * 256 + threadIdx.x;
-    if (k < a.n_occ) {
-      const int r = inv[k];
-      const int p = (int)seg_off[r] + slot[k];
-      occ_pos[k] = p;
-      const int rows = k < 3 * (int64_t)a.n ? 1 : a.sy2;       // a negative gets one gradient row per part
-      for (int i = 0; i < rows; ++i) rank_sorted[p + i] = r;
-      // unified id of the occurrence (same numbering as the index kernels)
-      int64_t kk2 = k; uint32_t id;
-      if (kk2 < a.n) id = a.src[kk2];
-      else if (kk2 < 2 * (int64_t)a.n) id = a.dst[kk2 - a.n];
-      else if (kk2 < 3 * (int64_t)a.n) id = a.num_nodes + a.rel[kk2 - 2 * (int64_t)a.n];
-      else { kk2 -= 3 * (int64_t)a.n; id = kk2 < a.cn ? a.neg_dst[kk2] : a.neg_src[kk2 - a.cn]; }
-      bitmap[id >> 5] = 0u;
-    }
-    return;
-  }
+  constexpr int nbA = 0;
   constexpr int GPB = 256 / GL;                  // lane groups per block
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
   const int dim = a.dim, dk = a.dk;
@@ -221,66 +224,47 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
 // ------------------------------------------------- per-row reduce + Adagrad scatter -----
 struct ReduceArgs {
   float *node_emb, *node_state, *rel_emb, *rel_state;
-  const float* G;
-  float* carry;
+  const float* G;            // [n_rows][dk] gradient rows in row-sorted order
+  float* Gu;                 // [unique rows][dk] summed gradient per unique row
+  float* carry;              // [tasks][2][dk]
   const int32_t* rank_sorted;
   const uint32_t* seg_off;
   const int32_t* uniq;
+  const int32_t* scalars;    // [0] = number of unique rows
   float* dbg_grad;
-  int64_t n_occ;
+  int64_t n_rows;
   int32_t num_nodes, dim, dk;
   float lr, eps;
 };
 
-// Adagrad (Sec. 5.1): state += g^2; theta -= lr * g / (sqrt(state) + eps), on columns
-// 4*q .. 4*q+3 of the row with the given rank.
-__device__ __forceinline__ void adagrad_cols(const ReduceArgs& a, int rank, int q, float4 g) {
-  const int32_t id = a.uniq[rank];
-  float *emb, *st;
-  if (id < a.num_nodes) { emb = a.node_emb + (size_t)id * a.dim; st = a.node_state + (size_t)id * a.dim; }
-  else { emb = a.rel_emb + (size_t)(id - a.num_nodes) * a.dim; st = a.rel_state + (size_t)(id - a.num_nodes) * a.dim; }
-  const float gv[4] = {g.x, g.y, g.z, g.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int col = 4 * q + i;
-    if (col < a.dim) {
-      const float s = st[col] + gv[i] * gv[i];
-      st[col] = s;
-      emb[col] = emb[col] - a.lr * gv[i] / (sqrtf(s) + a.eps);
-      if (a.dbg_grad) a.dbg_grad[(size_t)rank * a.dim + col] = gv[i];
-    }
-  }
-}
-
 // One wave per task of MAR_TASK_ROWS consecutive positions.  Rows of one segment (= one unique
 // table row) are summed; a segment that lies inside the task is finished here, one that
 // crosses the task's borders leaves a partial sum (slot 0: began earlier, slot 1: continues).
-// Rows are fetched BATCH at a time so that many loads are in flight per wave.
+// Rows are fetched BATCH at a time so that many loads are in flight per wave, and each lane
+// fetches its position's segment bounds up front so that no load depends on another.
 template <int NV, int BATCH>
 __global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t p0 = task * MAR_TASK_ROWS;
-  if (p0 >= a.n_occ) return;
-  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_occ ? p0 + MAR_TASK_ROWS : a.n_occ;
+  if (p0 >= a.n_rows) return;
+  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_rows ? p0 + MAR_TASK_ROWS : a.n_rows;
   const int cnt = (int)(p1 - p0);
   const int nq = a.dk >> 2;
   const int my_rank = lane < cnt ? a.rank_sorted[p0 + lane] : -1;
-  int cur = __shfl(my_rank, 0);
+  const int64_t my_lo = lane < cnt ? (int64_t)a.seg_off[my_rank] : 0;
+  const int64_t my_hi = lane < cnt ? (int64_t)a.seg_off[my_rank + 1] : 0;
+  int cur = __shfl(my_rank, 0), cur_i = 0;
   float4 acc[NV];
 #pragma unroll
   for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-  auto flush = [&](int rank) {
-    const int64_t lo = a.seg_off[rank], hi = a.seg_off[rank + 1];
-    if (lo >= p0 && hi <= p1) {
+  auto flush = [&](int rank, int first_lane) {
+    const int64_t lo = __shfl(my_lo, first_lane), hi = __shfl(my_hi, first_lane);
+    float* dst = (lo >= p0 && hi <= p1) ? a.Gu + (size_t)rank * a.dk
+                                        : a.carry + ((size_t)task * 2 + (lo < p0 ? 0 : 1)) * a.dk;
 #pragma unroll
-      for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) adagrad_cols(a, rank, q, acc[v]); }
-    } else {
-      float* c = a.carry + ((size_t)task * 2 + (lo < p0 ? 0 : 1)) * a.dk;
-#pragma unroll
-      for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) *reinterpret_cast<float4*>(c + 4 * q) = acc[v]; }
-    }
+    for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) *reinterpret_cast<float4*>(dst + 4 * q) = acc[v]; }
   };
 
   for (int i0 = 0; i0 < cnt; i0 += BATCH) {
@@ -299,10 +283,10 @@ __global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
       if (i0 + j < cnt) {
         const int r = __shfl(my_rank, i0 + j);
         if (r != cur) {
-          flush(cur);
+          flush(cur, cur_i);
 #pragma unroll
           for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-          cur = r;
+          cur = r; cur_i = i0 + j;
         }
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
@@ -311,14 +295,14 @@ __global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
       }
     }
   }
-  flush(cur);
+  flush(cur, cur_i);
 }
 
 // Finishes the segments that span several tasks.  One workgroup per task; it has work only if
 // a spanning segment begins in its task: then its four waves add that task's tail partial and
-// the head partials of the following tasks (wave w takes every fourth), the partial sums are
-// combined through LDS in wave order, and wave 0 applies the update.  Block 0 also adds up the
-// per-block loss terms in a fixed order.
+// the head partials of the following tasks (wave w takes every fourth), and the partial sums
+// are combined through LDS in wave order.  Block 0 also adds up the per-block loss terms in a
+// fixed order.
 template <int NV>
 __global__ void __launch_bounds__(256)
 k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, float* __restrict__ loss_out) {
@@ -333,8 +317,8 @@ k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, floa
   }
   const int64_t task = blockIdx.x;
   const int64_t p0 = task * MAR_TASK_ROWS;
-  if (p0 >= a.n_occ) return;
-  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_occ ? p0 + MAR_TASK_ROWS : a.n_occ;
+  if (p0 >= a.n_rows) return;
+  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_rows ? p0 + MAR_TASK_ROWS : a.n_rows;
   const int rank = a.rank_sorted[p1 - 1];
   const int64_t lo = a.seg_off[rank], hi = a.seg_off[rank + 1];
   if (!(lo >= p0 && hi > p1)) return;                       // uniform over the workgroup
@@ -377,7 +361,44 @@ k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, floa
       const int q = lane + 64 * v;
       float4 s = part[0][q];
       for (int w = 1; w < 4; ++w) { const float4 o = part[w][q]; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
-      if (q < nq) adagrad_cols(a, rank, q, s);
+      if (q < nq) *reinterpret_cast<float4*>(a.Gu + (size_t)rank * a.dk + 4 * q) = s;
+    }
+  }
+}
+
+// Sparse Adagrad scatter (Sec. 5.1): one thread per (unique row, 4 columns):
+// state += g^2; theta -= lr * g / (sqrt(state) + eps).
+__global__ void __launch_bounds__(256) k_adagrad(ReduceArgs a) {
+  const int nq = a.dk >> 2;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int rank = (int)(i / nq), q = (int)(i % nq);
+  if (rank >= a.scalars[0]) return;
+  const float4 g = *reinterpret_cast<const float4*>(a.Gu + (size_t)rank * a.dk + 4 * q);
+  const int32_t id = a.uniq[rank];
+  float *emb, *st;
+  if (id < a.num_nodes) { emb = a.node_emb + (size_t)id * a.dim; st = a.node_state + (size_t)id * a.dim; }
+  else { emb = a.rel_emb + (size_t)(id - a.num_nodes) * a.dim; st = a.rel_state + (size_t)(id - a.num_nodes) * a.dim; }
+  const float gv[4] = {g.x, g.y, g.z, g.w};
+  if ((a.dim & 3) == 0) {                       // rows are 16-byte aligned: vector access
+    const float4 s0 = *reinterpret_cast<const float4*>(st + 4 * q);
+    const float4 e0 = *reinterpret_cast<const float4*>(emb + 4 * q);
+    float4 s1, e1;
+    s1.x = s0.x + g.x * g.x; s1.y = s0.y + g.y * g.y; s1.z = s0.z + g.z * g.z; s1.w = s0.w + g.w * g.w;
+    e1.x = e0.x - a.lr * g.x / (sqrtf(s1.x) + a.eps); e1.y = e0.y - a.lr * g.y / (sqrtf(s1.y) + a.eps);
+    e1.z = e0.z - a.lr * g.z / (sqrtf(s1.z) + a.eps); e1.w = e0.w - a.lr * g.w / (sqrtf(s1.w) + a.eps);
+    *reinterpret_cast<float4*>(st + 4 * q) = s1;
+    *reinterpret_cast<float4*>(emb + 4 * q) = e1;
+    if (a.dbg_grad) *reinterpret_cast<float4*>(a.dbg_grad + (size_t)rank * a.dim + 4 * q) = g;
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int col = 4 * q + k;
+      if (col < a.dim) {
+        const float s = st[col] + gv[k] * gv[k];
+        st[col] = s;
+        emb[col] = emb[col] - a.lr * gv[k] / (sqrtf(s) + a.eps);
+        if (a.dbg_grad) a.dbg_grad[(size_t)rank * a.dim + col] = gv[k];
+      }
     }
   }
 }
@@ -396,16 +417,22 @@ static RowArgs row_args(const mar_ctx* c, const MarBatch& b) {
 
 static inline int lane_group(int dk) { return dk <= 64 ? 16 : (dk <= 128 ? 32 : 64); }
 
-hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, int train, float* pos_out, hipStream_t st) {
+hipError_t mar_launch_positions(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
+  const MarLayout& L = c->L;
+  RowArgs a = row_args(c, b);
+  hipLaunchKernelGGL(k_positions, dim3((unsigned)((b.n_occ + 255) / 256)), dim3(256), 0, st, a, (int)c->dm.ipw_log2, L.seg_off,
+                     L.inv, L.slot, L.occ_pos, L.rank_sorted, L.bitmap);
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, hipStream_t st) {
   const MarLayout& L = c->L;
   RowArgs a = row_args(c, b);
   const int GL = lane_group(a.dk), gpb = 256 / GL;
-  const int nbA = train ? (int)((b.n_occ + 255) / 256) : 0;
   const int nbB = (b.n + gpb - 1) / gpb;
   const int nbC = (2 * b.cn + gpb - 1) / gpb;
-  const dim3 grid(nbA + nbB + nbC), blk(256);
-#define PREP(GLV) hipLaunchKernelGGL(k_prep<GLV>, grid, blk, 0, st, a, train, nbA, nbB, L.seg_off, L.inv, L.slot, L.occ_pos, \
-                                   L.rank_sorted, L.bitmap, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
+  const dim3 grid(nbB + nbC), blk(256);
+#define PREP(GLV) hipLaunchKernelGGL(k_prep<GLV>, grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
   if (GL == 16) PREP(16); else if (GL == 32) PREP(32); else PREP(64);
 #undef PREP
   return hipGetLastError();
@@ -427,8 +454,8 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
   const MarDims& d = c->dm;
   ReduceArgs a;
   a.node_emb = c->node_emb; a.node_state = c->node_state; a.rel_emb = c->rel_emb; a.rel_state = c->rel_state;
-  a.G = L.G; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.seg_off = L.seg_off; a.uniq = L.uniq;
-  a.dbg_grad = dbg_grad; a.n_occ = b.n_pos; a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk;
+  a.G = L.G; a.Gu = L.Gu; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.seg_off = L.seg_off; a.uniq = L.uniq;
+  a.scalars = L.scalars; a.dbg_grad = dbg_grad; a.n_rows = b.n_pos; a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk;
   a.lr = c->cfg.lr; a.eps = c->cfg.eps;
   const int64_t tasks = (b.n_pos + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
   const dim3 grid((unsigned)((tasks + 3) / 4)), gridf((unsigned)tasks), blk(256);
@@ -441,5 +468,9 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
     hipLaunchKernelGGL((k_reduce<2, 8>), grid, blk, 0, st, a);
     hipLaunchKernelGGL(k_fixup<2>, gridf, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
   }
+  // at most min(unique-row capacity, occurrences of this batch) rows can be touched
+  const int64_t umax = d.u_max < b.n_occ ? d.u_max : b.n_occ;
+  const int64_t threads = umax * (d.dk >> 2);
+  hipLaunchKernelGGL(k_adagrad, dim3((unsigned)((threads + 255) / 256)), blk, 0, st, a);
   return hipGetLastError();
 }
