@@ -62,7 +62,7 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   // Small batches give too few (chunk-side, 64-row stripe) workgroups to fill 256 CUs: let several
   // workgroups share a stripe, each streaming a slice of the other matrix.
   d->ty = mar_flash_tile_rows(d->dk);
-  long target = 2048;
+  long target = 640;
   if (const char* e = getenv("MAR_FLASH_TARGET_WGS")) { const long v = atol(e); if (v > 0) target = v; }
   auto split = [&](int n_x, int n_y, int32_t* sy, int32_t* tps) {
     const int sr = mar_flash_stripe_rows(d->dk);

@@ -113,8 +113,10 @@ __device__ __forceinline__ int32_t occ_unified_id(const OccArgs& a, int64_t k) {
 __device__ __forceinline__ uint32_t map_bitpos(uint32_t id, int L) { return (id & ((1u << L) - 1u)) * (32u >> L); }
 
 // Block-wide grouping of equal keys through an LDS hash table (open addressing).
-#define AGG_THREADS 1024
-#define AGG_SLOTS 2048
+// Blocks of the index kernels stay at 256 threads: they run beside the contraction kernel on
+// a second stream and have to fit into the wave slots and registers it leaves free on a CU.
+#define AGG_THREADS 256
+#define AGG_SLOTS 512
 struct BlockAgg {
   int key[AGG_SLOTS];
   uint32_t cnt[AGG_SLOTS];
@@ -127,7 +129,7 @@ __device__ __forceinline__ void agg_clear(BlockAgg& t) {
 
 // Inserts key, adds mult to its group; returns the slot through `h` and the group-local offset.
 __device__ __forceinline__ uint32_t agg_insert(BlockAgg& t, int key, uint32_t mult, int* h_out) {
-  int h = (int)(((uint32_t)key * 2654435761u) >> 21);          // 11 bits
+  int h = (int)(((uint32_t)key * 2654435761u) >> 23);          // 9 bits
   for (;;) {
     const int prev = atomicCAS(&t.key[h], -1, key);
     if (prev == -1 || prev == key) break;
@@ -232,7 +234,7 @@ __global__ void __launch_bounds__(256) k_scan_bsum(uint32_t* __restrict__ bsum, 
 // marks below `split_id` (the first relation's unified id) into scalars[1].  With
 // `single_block` the kernel loops over the whole input itself and needs no block sums.
 template <int POPC, int BT, int PER>
-__global__ void __launch_bounds__(BT)
+__global__ void __launch_bounds__(BT, 8)
 k_scan_apply(const uint32_t* __restrict__ in, int64_t n, const uint32_t* __restrict__ bsum, int single_block, int L,
              uint32_t* __restrict__ out, int32_t* __restrict__ uniq, int32_t* __restrict__ scalars, int64_t split_id) {
   constexpr int ELEMS = BT * PER;
@@ -277,12 +279,12 @@ k_scan_apply(const uint32_t* __restrict__ in, int64_t n, const uint32_t* __restr
 template <int POPC>
 static hipError_t scan_u32(const uint32_t* in, int64_t n, int L, uint32_t* out, uint32_t* bsum, int32_t* uniq,
                            int32_t* scalars, int64_t split_id, hipStream_t st) {
-  if (n <= 1024) {
-    hipLaunchKernelGGL((k_scan_apply<POPC, 1024, 1>), dim3(1), dim3(1024), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
-  } else if (n <= 4096 * 4) {
-    hipLaunchKernelGGL((k_scan_apply<POPC, 1024, 4>), dim3(1), dim3(1024), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
-  } else if (n <= 16384 * 8) {
-    hipLaunchKernelGGL((k_scan_apply<POPC, 1024, 16>), dim3(1), dim3(1024), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
+  if (n <= 256) {
+    hipLaunchKernelGGL((k_scan_apply<POPC, 256, 1>), dim3(1), dim3(256), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
+  } else if (n <= 1024 * 4) {
+    hipLaunchKernelGGL((k_scan_apply<POPC, 256, 4>), dim3(1), dim3(256), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
+  } else if (n <= 4096 * 8) {
+    hipLaunchKernelGGL((k_scan_apply<POPC, 256, 16>), dim3(1), dim3(256), 0, st, in, n, bsum, 1, L, out, uniq, scalars, split_id);
   } else {
     const int64_t nblk = (n + SCAN_BLOCK_ELEMS - 1) / SCAN_BLOCK_ELEMS;
     hipLaunchKernelGGL(k_scan_block_sums<POPC>, dim3((unsigned)nblk), dim3(256), 0, st, in, n, bsum);
@@ -389,11 +391,11 @@ hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st)
   OccArgs a{b.src, b.rel, b.dst, b.neg_src, b.neg_dst, b.n, b.cn, (int32_t)d.num_nodes};
   const int64_t n_count = d.u_max + 1;
   const int64_t work = b.n_occ > n_count ? b.n_occ : n_count;
-  hipLaunchKernelGGL(k_mark, dim3(grid_for(work, AGG_THREADS, 1024)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.ipw_log2,
+  hipLaunchKernelGGL(k_mark, dim3(grid_for(work, AGG_THREADS, 2048)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.ipw_log2,
                      L.bitmap, L.count, n_count);
   hipError_t e = scan_u32<1>(L.bitmap, d.nwords, d.ipw_log2, L.word_prefix, L.bsum, L.uniq, L.scalars, d.num_nodes, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, AGG_THREADS, 1024)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.sy2,
+  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, AGG_THREADS, 2048)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.sy2,
                      (int)d.ipw_log2, L.bitmap, L.word_prefix, L.count, L.inv, L.slot);
   return scan_u32<0>(L.count, n_count, 5, L.seg_off, L.bsum, nullptr, nullptr, -1, st);
 }

@@ -123,51 +123,45 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
 // the occurrences' row-sorted positions.  Also the per-edge loss terms, summed per block in a
 // fixed order.
 template <int GL>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 8)
 k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, const float* __restrict__ pos,
         float* __restrict__ lse, const int32_t* __restrict__ occ_pos, float* __restrict__ G, float* __restrict__ loss_part) {
   constexpr int GPB = 256 / GL;
   constexpr int MAXP = 8;
   __shared__ float lsum[GPB];
+  __shared__ float fac[GPB][2][MAXP];          // per edge and side: exp(m_p - m) / l for each part p
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
   const int e = blockIdx.x * GPB + grp;
   const int dim = a.dim, dk = a.dk;
+  const size_t part_rows = (size_t)2 * a.B;
   float le = 0.f;
-  if (e < a.n) {
-    // Merge the parts of the online softmax: part p holds (m_p, l_p) and O_p = sum_j exp(a_j - m_p) n_j.
-    const size_t part_rows = (size_t)2 * a.B;
-    float fu[MAXP], fw[MAXP], lse_u, lse_w;
-    {
-      const size_t ru = (size_t)MAR_SIDE_DST * a.B + e, rw = (size_t)MAR_SIDE_SRC * a.B + e;
-      float mu = -3.0e38f, mw = -3.0e38f;
-      for (int p = 0; p < a.sy1; ++p) {
-        mu = fmaxf(mu, ml[(p * part_rows + ru) * 2]);
-        mw = fmaxf(mw, ml[(p * part_rows + rw) * 2]);
-      }
-      float lu = 0.f, lw = 0.f;
-#pragma unroll
-      for (int p = 0; p < MAXP; ++p) {
-        fu[p] = 0.f; fw[p] = 0.f;
-        if (p < a.sy1) {
-          fu[p] = __expf(ml[(p * part_rows + ru) * 2] - mu);
-          fw[p] = __expf(ml[(p * part_rows + rw) * 2] - mw);
-          lu += fu[p] * ml[(p * part_rows + ru) * 2 + 1];
-          lw += fw[p] * ml[(p * part_rows + rw) * 2 + 1];
-        }
-      }
-      const float iu = 1.f / lu, iw = 1.f / lw;
-#pragma unroll
-      for (int p = 0; p < MAXP; ++p) { fu[p] *= iu; fw[p] *= iw; }
-      lse_u = mu + logf(lu); lse_w = mw + logf(lw);
-      if (l == 0) { lse[ru] = lse_u; lse[rw] = lse_w; }
+  // Merge the parts of the online softmax: part p holds (m_p, l_p) and O_p = sum_j exp(a_j - m_p) n_j.
+  if (e < a.n && l < 2) {
+    const int side = l == 0 ? MAR_SIDE_DST : MAR_SIDE_SRC;
+    const size_t row = (size_t)side * a.B + e;
+    float mx = -3.0e38f;
+    for (int p = 0; p < a.sy1; ++p) mx = fmaxf(mx, ml[(p * part_rows + row) * 2]);
+    float ls = 0.f;
+    for (int p = 0; p < a.sy1; ++p) {
+      const float f = __expf(ml[(p * part_rows + row) * 2] - mx);
+      fac[grp][l][p] = f;
+      ls += f * ml[(p * part_rows + row) * 2 + 1];
     }
+    const float il = 1.f / ls;
+    for (int p = 0; p < a.sy1; ++p) fac[grp][l][p] *= il;
+    lse[row] = mx + logf(ls);
+  }
+  __syncthreads();
+  if (e < a.n) {
     const float* gu0 = gQ + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
     const float* gw0 = gQ + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
     const size_t pstride = part_rows * dk;
+    const float* fu = fac[grp][0];
+    const float* fw = fac[grp][1];
     auto merged = [&](const float* base, const float* f, int k) {
       float v = 0.f;
-#pragma unroll
-      for (int p = 0; p < MAXP; ++p) if (p < a.sy1) v += f[p] * base[p * pstride + k];
+#pragma unroll 1
+      for (int p = 0; p < a.sy1; ++p) v += f[p] * base[p * pstride + k];
       return v;
     };
     const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
@@ -210,7 +204,7 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
       }
     }
     for (int k = dim + l; k < dk; k += GL) { gs[k] = 0.f; gd[k] = 0.f; gr[k] = 0.f; }
-    le = -2.f * pos[e] + lse_u + lse_w;
+    le = -2.f * pos[e] + lse[(size_t)MAR_SIDE_DST * a.B + e] + lse[(size_t)MAR_SIDE_SRC * a.B + e];
   }
   if (l == 0) lsum[grp] = le;
   __syncthreads();
