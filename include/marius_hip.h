@@ -13,6 +13,9 @@
  *     the workspace handed to mar_init_tables.
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t cast to void*, NULL = the
  *     default stream); they do not synchronise.  Scalar results land in device memory.
+ *     mar_train_batch also runs part of its work on a second stream owned by the context,
+ *     forked from and joined back into `hip_stream` with events (default priority), so for the
+ *     caller everything is ordered on `hip_stream`.
  *   - Return value: MAR_OK (0) or a negative MAR_E* code.  Nothing is enqueued when an
  *     argument check fails.  mar_last_error gives a text for the last failure of the
  *     calling thread.
@@ -135,7 +138,9 @@ int mar_eval_scores(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const 
                     float* pos_scores, int32_t* rank_dst, int32_t* rank_src, void* hip_stream);
 
 /*
- * Per-phase device timing of mar_train_batch with HIP events on the call's stream.
+ * Per-phase device timing of mar_train_batch with HIP events on the stream each phase runs on
+ * (phases 0 and 4 run on the context's second stream beside phases 1-3, so the six times
+ * overlap and do not add up to the step time).
  * Phases: 0 index build (unique set, occurrence order), 1 row gather and operand build,
  * 2 score + softmax + gradient w.r.t. the edge side (MFMA), 3 gradient w.r.t. the
  * negatives (MFMA), 4 chain rule, 5 per-row reduce + Adagrad scatter.

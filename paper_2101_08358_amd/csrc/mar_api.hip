@@ -113,6 +113,7 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.lse = (float*)take(2 * B * 4);
   l.gQ = (float*)take((size_t)d.sy1 * 2 * B * dk * 4);
   l.ml = (float*)take((size_t)d.sy1 * 2 * B * 2 * 4);
+  l.T = (float*)take(2 * B * (size_t)((d.N + 3) & ~3) * 4);
   l.G = (float*)take(n_pos * dk * 4);
   l.Gu = (float*)take(u1 * dk * 4);
   l.carry = (float*)take(tasks * 2 * dk * 4);
@@ -150,6 +151,7 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
   c->node_emb = node_emb; c->node_state = node_state; c->rel_emb = rel_emb; c->rel_state = rel_state;
   c->workspace = workspace; c->workspace_bytes = workspace_bytes;
   carve(d, (char*)workspace, &c->L);
+  if (getenv("MAR_RECOMPUTE_SCORES")) c->L.T = nullptr;       // timing experiments: pass 2 recomputes the score block
   c->bitmap_dirty = 0; c->prof_max = 0; c->prof_steps = 0; c->prof_events = nullptr;
   c->aux = nullptr; c->ev_fork = c->ev_index = c->ev_pass1 = c->ev_chain = nullptr;
   hipError_t e = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking);

@@ -19,6 +19,10 @@
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
+#ifndef MAR_FLASH_ABL
+#define MAR_FLASH_ABL 0      // timing experiments only, bit mask: 1 no exp, 2 no second product, 4 no score product, 8 no tile refill
+#endif
+
 struct FlashArgs {
   const float* X;      // stationary matrix, rows of dk floats
   const float* Y;      // streamed matrix
@@ -34,6 +38,9 @@ struct FlashArgs {
   int32_t sy;          // workgroups sharing one stripe, each streaming `tps` tiles
   int32_t tps;
   int32_t sy_ml;       // parts pass 1 was split into
+  float* T;            // [2*nchunks][S][tpitch] raw scores of every (edge, negative) pair: written by pass 1,
+                       // read by the negatives' gradient pass (which then needs no score product)
+  int32_t tpitch;      // N rounded up to 4
 };
 
 __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
@@ -183,7 +190,7 @@ k_flash(FlashArgs a) {
       if (L2) auy[threadIdx.x] = st_auy;
     }
     __syncthreads();
-    if (t + 1 < ntiles) load_tile(t + 1);
+    if (t + 1 < ntiles && !(MAR_FLASH_ABL & 8)) load_tile(t + 1);
 
     const int y0 = t * TY;
     const int nblk = min(TY / 16, (n_y - y0 + 15) / 16);
@@ -203,6 +210,7 @@ k_flash(FlashArgs a) {
       v4f tacc[XB];
 #pragma unroll
       for (int b = 0; b < XB; ++b) tacc[b] = (v4f){0.f, 0.f, 0.f, 0.f};
+#if !(MAR_FLASH_ABL & 4)
 #pragma unroll
       for (int s = 0; s < N16; ++s) {
         const float4 yv = q16[s % PD];
@@ -221,6 +229,7 @@ k_flash(FlashArgs a) {
 #pragma unroll
         for (int b = 0; b < XB; ++b) tacc[b] = mfma16(q1[j], xf[b][4 * N16 + j], tacc[b]);
       }
+#endif
       // -- scores and weights
       float w[XB][4];
       float yy4[4] = {0.f, 0.f, 0.f, 0.f}, ls4[4] = {0.f, 0.f, 0.f, 0.f};
@@ -243,6 +252,15 @@ k_flash(FlashArgs a) {
             dist[r] = sqrtf(d2);
             sc[r] = -dist[r];
           }
+        }
+        if (PASS == 1 && a.T) {
+          // keep the raw scores for the negatives' gradient pass: row = edge, 4 consecutive negatives
+          const int yc = y0 + yl;
+          if (xv[b] && yc < a.tpitch)
+            *reinterpret_cast<float4*>(a.T + ((size_t)cs * a.S + x[b]) * a.tpitch + yc) = make_float4(sc[0], sc[1], sc[2], sc[3]);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
           if (PASS != 2 && y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
         }
         if (PASS == 3) {
@@ -266,11 +284,11 @@ k_flash(FlashArgs a) {
             mrun[b] = mnew;
           }
 #pragma unroll
-          for (int r = 0; r < 4; ++r) w[b][r] = __expf(sc[r] - mrun[b]);
+          for (int r = 0; r < 4; ++r) w[b][r] = (MAR_FLASH_ABL & 1) ? sc[r] : __expf(sc[r] - mrun[b]);
           lrun[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
         } else {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) w[b][r] = __expf(sc[r] - ls4[r]);
+          for (int r = 0; r < 4; ++r) w[b][r] = (MAR_FLASH_ABL & 1) ? sc[r] : __expf(sc[r] - ls4[r]);
         }
         if (PASS != 3 && L2) {
 #pragma unroll
@@ -280,7 +298,7 @@ k_flash(FlashArgs a) {
       }
       // first fragments of the next block's score product, fetched under the second product
       if (yb + 1 < nblk) load_head(yb + 1);
-      if (PASS != 3) {
+      if (PASS != 3 && !(MAR_FLASH_ABL & 2)) {
         // -- O^T[c][x] += sum_y Y[y][c] W[y][x]: A = Y fragment (row c), B = W (lane x)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -340,6 +358,155 @@ k_flash(FlashArgs a) {
   }
 }
 
+// Gradient w.r.t. the negatives' rows from stored scores: gK[j] = sum_e exp(T[e][j] - lse[e]) Q[e]
+// (TransE: weights divided by the distance, minus n_j times their sum).  A workgroup owns 64
+// negatives (16 per wave) and streams the chunk's edges in tiles of TY: the Q rows and the
+// matching 64-wide slice of the score rows go through LDS; only the second product runs on the
+// matrix cores.  Lane (g, m) of wave w takes T[e = 4g + r][j = 16w + m], which is the B-operand
+// layout of O^T[c][j] += sum_e Q[e][c] W[e][j].
+template <int NK, int NC, int TY, int L2>
+__global__ void __launch_bounds__(256, (NK <= 32 ? 3 : (NK <= 64 ? 2 : 1)))
+k_flash_bwd(FlashArgs a) {
+  typedef FlashGeom<NK> GM;
+  constexpr int PITCH = GM::PITCH;
+  constexpr int TP = 68;                                  // LDS pitch of the score slice: 4 mod 8
+  constexpr int NU = (TY * NK + 255) / 256;              // float4 units of the Q tile staged per thread
+  constexpr int TU = TY * 16 / 256;                       // float4 units of the score slice per thread
+  __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
+  __shared__ __attribute__((aligned(16))) float tt[TY * TP];
+  __shared__ float aux[TY];                               // log-sum-exp of the streamed edges
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, m = lane & 15;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int part = slot % a.sy, slot2 = slot / a.sy;
+  const int cs = (slot2 / a.nstripes) * 8 + xcd;
+  const int stripe = slot2 % a.nstripes;
+  if (cs >= 2 * a.nchunks) return;
+  const int side = cs & 1, c = cs >> 1;
+  const int n_y = min(a.S, a.n - c * a.S);                // edges in this chunk (streamed)
+  const int n_x = a.N;                                    // negatives (stationary)
+  if (stripe * 64 >= n_x) return;
+  const size_t y_base = (size_t)side * a.B + (size_t)c * a.S;        // first Q row of the chunk
+  const size_t x_base = (size_t)side * a.C * a.N + (size_t)c * a.N;  // first K row of the chunk
+  const int dk = a.dk;
+  const int x = stripe * 64 + wave * 16 + m;
+  const bool xv = x < n_x;
+
+  v4f oacc[NC];
+#pragma unroll
+  for (int cb = 0; cb < NC; ++cb) oacc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+  float wsum = 0.f;
+
+  const int ntiles_all = (n_y + TY - 1) / TY;
+  const int t_begin = part * a.tps;
+  const int ntiles = min(ntiles_all, t_begin + a.tps);
+  float4 stage[NU], tstage[TU];
+  float st_aux = 0.f;
+  auto load_tile = [&](int t) {
+    const int y0 = t * TY;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int unit = threadIdx.x + 256 * u;
+      const int row = unit / NK, cu = unit % NK;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (unit < TY * NK && y0 + row < n_y && 4 * cu < dk)
+        v = *reinterpret_cast<const float4*>(a.Y + (y_base + y0 + row) * dk + 4 * cu);
+      stage[u] = v;
+    }
+#pragma unroll
+    for (int u = 0; u < TU; ++u) {
+      const int unit = threadIdx.x + 256 * u;
+      const int row = unit >> 4, j0 = stripe * 64 + 4 * (unit & 15);
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (y0 + row < n_y && j0 < a.tpitch)
+        v = *reinterpret_cast<const float4*>(a.T + ((size_t)cs * a.S + y0 + row) * a.tpitch + j0);
+      tstage[u] = v;
+    }
+    if (threadIdx.x < TY) {
+      const int yr = y0 + threadIdx.x;
+      st_aux = __builtin_inff();
+      if (yr < n_y) {
+        const size_t pr = (size_t)2 * a.B;
+        float mm = -3.0e38f, ll = 0.f;
+        for (int p = 0; p < a.sy_ml; ++p) mm = fmaxf(mm, a.ml[(p * pr + y_base + yr) * 2]);
+        for (int p = 0; p < a.sy_ml; ++p) ll += a.ml[(p * pr + y_base + yr) * 2 + 1] * __expf(a.ml[(p * pr + y_base + yr) * 2] - mm);
+        st_aux = mm + logf(ll);
+      }
+    }
+  };
+  if (t_begin < ntiles) load_tile(t_begin);
+
+  for (int t = t_begin; t < ntiles; ++t) {
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int unit = threadIdx.x + 256 * u;
+      const int row = unit / NK, cu = unit % NK;
+      if (unit < TY * NK) *reinterpret_cast<float4*>(&tile[row * PITCH + 4 * cu]) = stage[u];
+    }
+#pragma unroll
+    for (int u = 0; u < TU; ++u) {
+      const int unit = threadIdx.x + 256 * u;
+      *reinterpret_cast<float4*>(&tt[(unit >> 4) * TP + 4 * (unit & 15)]) = tstage[u];
+    }
+    if (threadIdx.x < TY) aux[threadIdx.x] = st_aux;
+    __syncthreads();
+    if (t + 1 < ntiles) load_tile(t + 1);
+
+    const int y0 = t * TY;
+    const int nblk = min(TY / 16, (n_y - y0 + 15) / 16);
+#pragma unroll 1
+    for (int yb = 0; yb < nblk; ++yb) {
+      const int yl = yb * 16 + 4 * g;
+      const float* ycol = &tile[yl * PITCH + m];
+      float ya[NC];
+#pragma unroll
+      for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[16 * cb];
+      float w[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float sc = tt[(yl + r) * TP + wave * 16 + m];
+        w[r] = __expf(sc - aux[yl + r]);               // 0 for rows beyond the chunk (lse = +inf)
+        if (L2) w[r] = sc < 0.f ? w[r] / -sc : 0.f;      // score = -distance
+      }
+      if (L2) wsum += (w[0] + w[1]) + (w[2] + w[3]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float cur[NC];
+#pragma unroll
+        for (int cb = 0; cb < NC; ++cb) cur[cb] = ya[cb];
+        if (r < 3) {
+#pragma unroll
+          for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[(r + 1) * PITCH + 16 * cb];
+        }
+#pragma unroll
+        for (int cb = 0; cb < NC; ++cb) oacc[cb] = mfma16(cur[cb], w[r], oacc[cb]);
+      }
+    }
+  }
+
+  if (L2) {
+    wsum += __shfl_xor(wsum, 16);
+    wsum += __shfl_xor(wsum, 32);
+  }
+  if (!xv) return;
+  const float* xrow = a.X + (x_base + x) * dk;
+  float* orow = a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] + part) * dk;
+#pragma unroll
+  for (int cb = 0; cb < NC; ++cb) {
+    const int col = 16 * cb + 4 * g;
+    if (col < dk) {
+      float4 o = make_float4(oacc[cb][0], oacc[cb][1], oacc[cb][2], oacc[cb][3]);
+      if (L2) {
+        const float4 xs = *reinterpret_cast<const float4*>(xrow + col);
+        o.x -= xs.x * wsum; o.y -= xs.y * wsum; o.z -= xs.z * wsum; o.w -= xs.w * wsum;
+      }
+      *reinterpret_cast<float4*>(orow + col) = o;
+    }
+  }
+}
+
 // ------------------------------------------------------------------- launchers -----
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
 int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of the instantiation that serves dk
@@ -350,7 +517,12 @@ template <int NK, int NC, int TY, int XB>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
 #define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, TY, XB, P, L>), grid, dim3(256), 0, st, a)
   if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
-  else if (pass == 2) { if (l2) FL(2, 1); else FL(2, 0); }
+  else if (pass == 2) {
+    if (a.T) {
+      if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, 1>), grid, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, 0>), grid, dim3(256), 0, st, a);
+    } else { if (l2) FL(2, 1); else FL(2, 0); }
+  }
   else { if (l2) FL(3, 1); else FL(3, 0); }
 #undef FL
   return hipGetLastError();
@@ -364,6 +536,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;
   a.xx = pass == 2 ? L.kk : L.qq; a.yy = pass == 2 ? L.qq : L.kk;
   a.ml = L.ml; a.pos = L.pos;
+  a.T = pass == 3 ? nullptr : L.T; a.tpitch = (d.N + 3) & ~3;
   a.out = pass == 1 ? L.gQ : L.G;
   a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
