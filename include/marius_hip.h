@@ -144,13 +144,14 @@ int mar_eval_scores(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const 
  * Phases: 0 index build (unique set, occurrence order), 1 row gather and operand build,
  * 2 score + softmax + gradient w.r.t. the edge side (MFMA), 3 gradient w.r.t. the
  * negatives (MFMA), 4 chain rule, 5 per-row reduce + Adagrad scatter.
- * mar_profile_enable(ctx, max_steps) starts recording (max_steps <= 4096; 0 stops);
- * mar_profile_read synchronises with the recorded events, adds each phase's elapsed
+ * mar_profile_enable(ctx, max_steps, phase_mask) starts recording the phases whose bit is set in
+ * phase_mask (max_steps <= 4096; 0 stops; every recorded phase costs two event records per step);
+ * mar_profile_read synchronises with the recorded events, adds each recorded phase's elapsed
  * milliseconds over the recorded steps into ms[MAR_NUM_PHASES], reports how many steps
  * were recorded, and resets the recording.
  */
 #define MAR_NUM_PHASES 6
-int mar_profile_enable(mar_ctx* ctx, int32_t max_steps);
+int mar_profile_enable(mar_ctx* ctx, int32_t max_steps, uint32_t phase_mask);
 int mar_profile_read(mar_ctx* ctx, double* ms, int32_t* steps);
 
 /* Releases the host-side context (device memory stays with the caller). */

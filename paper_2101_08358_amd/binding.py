@@ -60,7 +60,7 @@ def load_library():
     lib.mar_sample_negatives.argtypes = [vp, u64, vp, vp, i64, vp, vp, vp]
     lib.mar_train_batch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, ctypes.POINTER(MarDebugOut), vp]
     lib.mar_eval_scores.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
-    lib.mar_profile_enable.argtypes = [vp, i32]
+    lib.mar_profile_enable.argtypes = [vp, i32, ctypes.c_uint32]
     lib.mar_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.mar_destroy.argtypes = [vp]
     lib.mar_last_error.argtypes = [vp]
@@ -128,8 +128,8 @@ def mar_eval_scores(ctx, src, rel, dst, n_edges, neg_src, neg_dst, pos_scores, r
                                           _stream(stream)))
 
 
-def mar_profile_enable(ctx, max_steps):
-    _check(load_library().mar_profile_enable(ctx, int(max_steps)))
+def mar_profile_enable(ctx, max_steps, phase_mask=(1 << NUM_PHASES) - 1):
+    _check(load_library().mar_profile_enable(ctx, int(max_steps), int(phase_mask)))
 
 
 def mar_profile_read(ctx):

@@ -152,7 +152,7 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
   c->workspace = workspace; c->workspace_bytes = workspace_bytes;
   carve(d, (char*)workspace, &c->L);
   if (getenv("MAR_RECOMPUTE_SCORES")) c->L.T = nullptr;       // timing experiments: pass 2 recomputes the score block
-  c->bitmap_dirty = 0; c->prof_max = 0; c->prof_steps = 0; c->prof_events = nullptr;
+  c->bitmap_dirty = 0; c->prof_max = 0; c->prof_steps = 0; c->prof_mask = 0; c->prof_events = nullptr;
   c->aux = nullptr; c->ev_fork = c->ev_index = c->ev_pass1 = c->ev_chain = nullptr;
   hipError_t e = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking);
   hipEvent_t* evs[4] = {&c->ev_fork, &c->ev_index, &c->ev_pass1, &c->ev_chain};
@@ -227,7 +227,7 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   hipStream_t ax = c->aux;
   hipEvent_t* ev = nullptr;
   if (c->prof_events && c->prof_steps < c->prof_max) ev = c->prof_events + (size_t)c->prof_steps * 2 * MAR_NUM_PHASES;
-#define MARK(phase, end, stream) do { if (ev) HIP_TRY(hipEventRecord(ev[2 * (phase) + (end)], stream), "event record"); } while (0)
+#define MARK(phase, end, stream) do { if (ev && (c->prof_mask >> (phase) & 1u)) HIP_TRY(hipEventRecord(ev[2 * (phase) + (end)], stream), "event record"); } while (0)
   HIP_TRY(hipEventRecord(c->ev_fork, st), "fork");
   HIP_TRY(hipStreamWaitEvent(ax, c->ev_fork, 0), "fork");
   MARK(0, 0, ax);
@@ -281,7 +281,7 @@ extern "C" int mar_eval_scores(mar_ctx* c, const int32_t* src, const int32_t* re
 }
 
 // ----------------------------------------------------------------------- profiling -----
-extern "C" int mar_profile_enable(mar_ctx* c, int32_t max_steps) {
+extern "C" int mar_profile_enable(mar_ctx* c, int32_t max_steps, uint32_t phase_mask) {
   if (!c) return fail(MAR_EINVAL, "context is NULL");
   if (max_steps < 0 || max_steps > MAR_MAX_PROFILE_STEPS) return fail(MAR_ERANGE, "max_steps outside 0..%d", MAR_MAX_PROFILE_STEPS);
   if (c->prof_events) {
@@ -289,7 +289,7 @@ extern "C" int mar_profile_enable(mar_ctx* c, int32_t max_steps) {
     free(c->prof_events);
     c->prof_events = nullptr;
   }
-  c->prof_max = 0; c->prof_steps = 0;
+  c->prof_max = 0; c->prof_steps = 0; c->prof_mask = phase_mask & ((1u << MAR_NUM_PHASES) - 1u);
   if (max_steps == 0) return MAR_OK;
   const size_t ne = (size_t)max_steps * 2 * MAR_NUM_PHASES;
   c->prof_events = (hipEvent_t*)calloc(ne, sizeof(hipEvent_t));
@@ -312,10 +312,10 @@ extern "C" int mar_profile_read(mar_ctx* c, double* ms, int32_t* steps) {
   *steps = c->prof_steps;
   for (int s = 0; s < c->prof_steps; ++s) {
     hipEvent_t* ev = c->prof_events + (size_t)s * 2 * MAR_NUM_PHASES;
-    hipError_t e = hipEventSynchronize(ev[2 * MAR_NUM_PHASES - 1]);
-    if (e == hipSuccess) e = hipEventSynchronize(ev[2 * 4 + 1]);
-    if (e != hipSuccess) return hip_fail(e, "event synchronize");
     for (int p = 0; p < MAR_NUM_PHASES; ++p) {
+      if (!(c->prof_mask >> p & 1u)) continue;
+      hipError_t e = hipEventSynchronize(ev[2 * p + 1]);
+      if (e != hipSuccess) return hip_fail(e, "event synchronize");
       float t = 0.f;
       e = hipEventElapsedTime(&t, ev[2 * p], ev[2 * p + 1]);
       if (e != hipSuccess) return hip_fail(e, "event elapsed time");

@@ -67,6 +67,7 @@ struct mar_ctx {
   hipEvent_t ev_fork, ev_index, ev_pass1, ev_chain;
   // profiling
   int32_t prof_max, prof_steps;
+  uint32_t prof_mask;
   hipEvent_t* prof_events;         // 2 * MAR_NUM_PHASES per step (begin, end of each phase)
 };
 

@@ -78,7 +78,7 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.mar_train_batch(None, None, None, None, 0, None, None, None, None, None) == -1
     assert lib.mar_sample_negatives(None, 0, None, None, 0, None, None, None) == -1
     assert lib.mar_eval_scores(None, None, None, None, 0, None, None, None, None, None, None) == -1
-    assert lib.mar_profile_enable(None, 1) == -1
+    assert lib.mar_profile_enable(None, 1, 63) == -1
     assert lib.mar_destroy(None) == 0
 
 
