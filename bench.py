@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--workload", default="kg_small")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--edges", type=int, default=0, help="shorten the synthetic edge list (the per-step work is unchanged)")
+    ap.add_argument("--nodes", type=int, default=0, help="shrink the node table (row width and batch geometry are unchanged)")
     ap.add_argument("--no-phase-events", action="store_true", help="time the steps without the per-phase HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -80,6 +81,8 @@ def main():
     w = synth.get_workload(args.workload)
     if args.edges:
         w = w.scaled(num_edges=args.edges)
+    if args.nodes:
+        w = w.scaled(num_nodes=args.nodes)
     src, rel, dst = synth.make_graph(w.num_nodes, w.num_rels, w.num_edges, w.node_zipf, w.rel_zipf, seed=w.seed,
                                      device=dev if w.num_edges > 10_000_000 else "cpu")
     d_src, d_rel, d_dst = src.to(dev), rel.to(dev), dst.to(dev)

@@ -64,8 +64,8 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   d->ty = mar_flash_tile_rows(d->dk);
   long target = 640;
   if (const char* e = getenv("MAR_FLASH_TARGET_WGS")) { const long v = atol(e); if (v > 0) target = v; }
-  auto split = [&](int n_x, int n_y, int32_t* sy, int32_t* tps) {
-    const int sr = mar_flash_stripe_rows(d->dk);
+  auto split = [&](int pass, int n_x, int n_y, int32_t* sy, int32_t* tps) {
+    const int sr = mar_flash_stripe_rows(d->dk, pass);
     const long wgs = 2L * d->C * ((n_x + sr - 1) / sr);
     const int ntiles = (n_y + d->ty - 1) / d->ty;
     long want = (target + wgs - 1) / wgs;
@@ -75,8 +75,8 @@ static int check_config(const mar_config* cfg, MarDims* d) {
     *tps = (int32_t)((ntiles + want - 1) / want);
     *sy = (int32_t)((ntiles + *tps - 1) / *tps);
   };
-  split(d->S, d->N, &d->sy1, &d->tps1);
-  split(d->N, d->S, &d->sy2, &d->tps2);
+  split(1, d->S, d->N, &d->sy1, &d->tps1);
+  split(2, d->N, d->S, &d->sy2, &d->tps2);
   d->n_pos_max = 3 * (int64_t)cfg->batch_size + 2 * cn * d->sy2;
   return MAR_OK;
 }

@@ -102,4 +102,4 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
 int mar_flash_supported(int dk);
 int mar_flash_tile_rows(int dk);
-int mar_flash_stripe_rows(int dk);
+int mar_flash_stripe_rows(int dk, int pass);

@@ -359,19 +359,20 @@ k_flash(FlashArgs a) {
 }
 
 // Gradient w.r.t. the negatives' rows from stored scores: gK[j] = sum_e exp(T[e][j] - lse[e]) Q[e]
-// (TransE: weights divided by the distance, minus n_j times their sum).  A workgroup owns 64
-// negatives (16 per wave) and streams the chunk's edges in tiles of TY: the Q rows and the
-// matching 64-wide slice of the score rows go through LDS; only the second product runs on the
-// matrix cores.  Lane (g, m) of wave w takes T[e = 4g + r][j = 16w + m], which is the B-operand
-// layout of O^T[c][j] += sum_e Q[e][c] W[e][j].
-template <int NK, int NC, int TY, int L2>
-__global__ void __launch_bounds__(256, (NK <= 32 ? 3 : (NK <= 64 ? 2 : 1)))
+// (TransE: weights divided by the distance, minus n_j times their sum).  A workgroup owns 64*XB
+// negatives (16*XB per wave) and streams the chunk's edges in tiles of TY: the Q rows and the
+// matching slice of the score rows go through LDS; only the second product runs on the matrix
+// cores.  Lane (g, m) takes T[e = 4g + r][j = m] of its 16-negative block, which is the
+// B-operand layout of O^T[c][j] += sum_e Q[e][c] W[e][j].
+template <int NK, int NC, int TY, int XB, int L2>
+__global__ void __launch_bounds__(256, (NK * XB <= 32 ? 3 : (NK * XB <= 64 ? 2 : 1)))
 k_flash_bwd(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
-  constexpr int TP = 68;                                  // LDS pitch of the score slice: 4 mod 8
+  constexpr int SR = 64 * XB;                             // negatives per workgroup
+  constexpr int TP = SR + 4;                              // LDS pitch of the score slice: 4 mod 8
   constexpr int NU = (TY * NK + 255) / 256;              // float4 units of the Q tile staged per thread
-  constexpr int TU = TY * 16 / 256;                       // float4 units of the score slice per thread
+  constexpr int TU = TY * (SR / 4) / 256;                 // float4 units of the score slice per thread
   __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
   __shared__ __attribute__((aligned(16))) float tt[TY * TP];
   __shared__ float aux[TY];                               // log-sum-exp of the streamed edges
@@ -386,17 +387,19 @@ k_flash_bwd(FlashArgs a) {
   const int side = cs & 1, c = cs >> 1;
   const int n_y = min(a.S, a.n - c * a.S);                // edges in this chunk (streamed)
   const int n_x = a.N;                                    // negatives (stationary)
-  if (stripe * 64 >= n_x) return;
+  if (stripe * SR >= n_x) return;
   const size_t y_base = (size_t)side * a.B + (size_t)c * a.S;        // first Q row of the chunk
   const size_t x_base = (size_t)side * a.C * a.N + (size_t)c * a.N;  // first K row of the chunk
   const int dk = a.dk;
-  const int x = stripe * 64 + wave * 16 + m;
-  const bool xv = x < n_x;
 
-  v4f oacc[NC];
+  v4f oacc[XB][NC];
+  float wsum[XB];
 #pragma unroll
-  for (int cb = 0; cb < NC; ++cb) oacc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
-  float wsum = 0.f;
+  for (int b = 0; b < XB; ++b) {
+#pragma unroll
+    for (int cb = 0; cb < NC; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+    wsum[b] = 0.f;
+  }
 
   const int ntiles_all = (n_y + TY - 1) / TY;
   const int t_begin = part * a.tps;
@@ -417,7 +420,7 @@ k_flash_bwd(FlashArgs a) {
 #pragma unroll
     for (int u = 0; u < TU; ++u) {
       const int unit = threadIdx.x + 256 * u;
-      const int row = unit >> 4, j0 = stripe * 64 + 4 * (unit & 15);
+      const int row = unit / (SR / 4), j0 = stripe * SR + 4 * (unit % (SR / 4));
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (y0 + row < n_y && j0 < a.tpitch)
         v = *reinterpret_cast<const float4*>(a.T + ((size_t)cs * a.S + y0 + row) * a.tpitch + j0);
@@ -448,7 +451,7 @@ k_flash_bwd(FlashArgs a) {
 #pragma unroll
     for (int u = 0; u < TU; ++u) {
       const int unit = threadIdx.x + 256 * u;
-      *reinterpret_cast<float4*>(&tt[(unit >> 4) * TP + 4 * (unit & 15)]) = tstage[u];
+      *reinterpret_cast<float4*>(&tt[(unit / (SR / 4)) * TP + 4 * (unit % (SR / 4))]) = tstage[u];
     }
     if (threadIdx.x < TY) aux[threadIdx.x] = st_aux;
     __syncthreads();
@@ -463,14 +466,22 @@ k_flash_bwd(FlashArgs a) {
       float ya[NC];
 #pragma unroll
       for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[16 * cb];
-      float w[4];
+      float w[XB][4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float sc = tt[(yl + r) * TP + wave * 16 + m];
-        w[r] = __expf(sc - aux[yl + r]);               // 0 for rows beyond the chunk (lse = +inf)
-        if (L2) w[r] = sc < 0.f ? w[r] / -sc : 0.f;      // score = -distance
+        const float ls = aux[yl + r];
+#pragma unroll
+        for (int b = 0; b < XB; ++b) {
+          const float sc = tt[(yl + r) * TP + (wave * XB + b) * 16 + m];
+          float v = __expf(sc - ls);                       // 0 for rows beyond the chunk (lse = +inf)
+          if (L2) v = sc < 0.f ? v / -sc : 0.f;            // score = -distance
+          w[b][r] = v;
+        }
       }
-      if (L2) wsum += (w[0] + w[1]) + (w[2] + w[3]);
+      if (L2) {
+#pragma unroll
+        for (int b = 0; b < XB; ++b) wsum[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         float cur[NC];
@@ -481,28 +492,36 @@ k_flash_bwd(FlashArgs a) {
           for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[(r + 1) * PITCH + 16 * cb];
         }
 #pragma unroll
-        for (int cb = 0; cb < NC; ++cb) oacc[cb] = mfma16(cur[cb], w[r], oacc[cb]);
+        for (int cb = 0; cb < NC; ++cb) {
+#pragma unroll
+          for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
+        }
       }
     }
   }
 
-  if (L2) {
-    wsum += __shfl_xor(wsum, 16);
-    wsum += __shfl_xor(wsum, 32);
-  }
-  if (!xv) return;
-  const float* xrow = a.X + (x_base + x) * dk;
-  float* orow = a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] + part) * dk;
 #pragma unroll
-  for (int cb = 0; cb < NC; ++cb) {
-    const int col = 16 * cb + 4 * g;
-    if (col < dk) {
-      float4 o = make_float4(oacc[cb][0], oacc[cb][1], oacc[cb][2], oacc[cb][3]);
-      if (L2) {
-        const float4 xs = *reinterpret_cast<const float4*>(xrow + col);
-        o.x -= xs.x * wsum; o.y -= xs.y * wsum; o.z -= xs.z * wsum; o.w -= xs.w * wsum;
+  for (int b = 0; b < XB; ++b) {
+    float ws = wsum[b];
+    if (L2) {
+      ws += __shfl_xor(ws, 16);
+      ws += __shfl_xor(ws, 32);
+    }
+    const int x = stripe * SR + (wave * XB + b) * 16 + m;
+    if (x >= n_x) continue;
+    const float* xrow = a.X + (x_base + x) * dk;
+    float* orow = a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] + part) * dk;
+#pragma unroll
+    for (int cb = 0; cb < NC; ++cb) {
+      const int col = 16 * cb + 4 * g;
+      if (col < dk) {
+        float4 o = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
+        if (L2) {
+          const float4 xs = *reinterpret_cast<const float4*>(xrow + col);
+          o.x -= xs.x * ws; o.y -= xs.y * ws; o.z -= xs.z * ws; o.w -= xs.w * ws;
+        }
+        *reinterpret_cast<float4*>(orow + col) = o;
       }
-      *reinterpret_cast<float4*>(orow + col) = o;
     }
   }
 }
@@ -511,16 +530,17 @@ k_flash_bwd(FlashArgs a) {
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
 int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of the instantiation that serves dk
 
-int mar_flash_stripe_rows(int dk) { (void)dk; return 64; }   // 64 * XB of the instantiation
+// Stationary rows per workgroup (64 per x-block of the instantiation that serves dk): pass 1 / 3 and pass 2.
+int mar_flash_stripe_rows(int dk, int pass) { return pass == 2 && dk / 4 <= 32 ? 128 : 64; }
 
-template <int NK, int NC, int TY, int XB>
+template <int NK, int NC, int TY, int XB, int BXB>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
 #define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, TY, XB, P, L>), grid, dim3(256), 0, st, a)
   if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
   else if (pass == 2) {
     if (a.T) {
-      if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, 1>), grid, dim3(256), 0, st, a);
-      else hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, 0>), grid, dim3(256), 0, st, a);
+      if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, BXB, 1>), grid, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, BXB, 0>), grid, dim3(256), 0, st, a);
     } else { if (l2) FL(2, 1); else FL(2, 0); }
   }
   else { if (l2) FL(3, 1); else FL(3, 0); }
@@ -541,7 +561,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
   const int max_nx = pass == 2 ? d.N : (b.n < d.S ? b.n : d.S);
-  const int sr = mar_flash_stripe_rows(d.dk);
+  const int sr = mar_flash_stripe_rows(d.dk, pass);
   a.nstripes = (max_nx + sr - 1) / sr;
   const int ncs = 2 * b.nchunks;
   a.sy = pass == 1 ? d.sy1 : (pass == 2 ? d.sy2 : 1);
@@ -550,9 +570,9 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
-  if (nk <= 13) return launch_sized<13, 4, 64, 1>(a, pass, l2, grid, st);
-  if (nk <= 25) return launch_sized<25, 7, 64, 1>(a, pass, l2, grid, st);
-  if (nk <= 32) return launch_sized<32, 8, 64, 1>(a, pass, l2, grid, st);
-  if (nk <= 64) return launch_sized<64, 16, 32, 1>(a, pass, l2, grid, st);
-  return launch_sized<100, 25, 32, 1>(a, pass, l2, grid, st);
+  if (nk <= 13) return launch_sized<13, 4, 64, 1, 2>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 7, 64, 1, 2>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 64, 1, 2>(a, pass, l2, grid, st);
+  if (nk <= 64) return launch_sized<64, 16, 32, 1, 1>(a, pass, l2, grid, st);
+  return launch_sized<100, 25, 32, 1, 1>(a, pass, l2, grid, st);
 }
