@@ -151,7 +151,6 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
   c->node_emb = node_emb; c->node_state = node_state; c->rel_emb = rel_emb; c->rel_state = rel_state;
   c->workspace = workspace; c->workspace_bytes = workspace_bytes;
   carve(d, (char*)workspace, &c->L);
-  if (getenv("MAR_RECOMPUTE_SCORES")) c->L.T = nullptr;       // timing experiments: pass 2 recomputes the score block
   c->bitmap_dirty = 0; c->prof_max = 0; c->prof_steps = 0; c->prof_mask = 0; c->prof_events = nullptr;
   c->aux = nullptr; c->ev_fork = c->ev_index = c->ev_pass1 = c->ev_chain = nullptr;
   hipError_t e = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking);

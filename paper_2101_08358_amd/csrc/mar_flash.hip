@@ -3,25 +3,24 @@
 // For one chunk and one corrupted side the positives' operands Q (n_e x d) meet the chunk's
 // shared negatives K (N x d): scores A = Q K^T (Sec. 2.1: every edge against the sampled
 // negatives), log-sum-exp per edge (Eq. 1's log term), and with P = softmax rows
-//     gQ = P K   (gradient w.r.t. the edge-side operand)        -- pass 1, online softmax
-//     gK = P^T Q (gradient w.r.t. the negatives' rows)          -- pass 2, needs the final lse
-// The score block is never written to memory.  Both passes are the same loop: a wave owns 16
-// "stationary" rows x (Q rows in pass 1, K rows in pass 2) whose fragments stay in registers,
-// and streams tiles of the other matrix Y through LDS:
-//     T[y][x]   = sum_k Y[y][k] X[x][k]              v_mfma_f32_16x16x4_f32, lane <-> x
-//     W[y][x]   = exp(T - max) or exp(T - lse[y])    in the accumulator registers
-//     O^T[c][x] += sum_y Y[y][c] W[y][x]             the accumulator layout of T is exactly the
+//     gQ = P K   (gradient w.r.t. the edge-side operand)        -- k_flash, online softmax
+//     gK = P^T Q (gradient w.r.t. the negatives' rows)          -- k_flash_bwd, needs the final lse
+// k_flash: a wave owns 16 stationary rows x of Q whose fragments stay in registers, and streams
+// tiles of K through LDS:
+//     T[y][x]   = sum_k K[y][k] Q[x][k]              v_mfma_f32_16x16x4_f32, lane <-> x
+//     W[y][x]   = exp(T - reference[x])              in the accumulator registers
+//     O^T[c][x] += sum_y K[y][c] W[y][x]             the accumulator layout of T is exactly the
 //                                                    B-operand layout the second product needs
-// so every per-x quantity (running max, running sum, rescale factor) is per lane.
-// Pass 3 (evaluation) only counts negatives scoring above the positive.
-// TransE uses |q - n|^2 = |q|^2 + |n|^2 - 2 q.n for the scores and W = P / distance.
+// so every per-x quantity (reference, running sum, rescale factor) is per lane and nothing is
+// transposed.  The raw scores T are also written out once (4 B per pair): fp32 matrix
+// throughput is ~20 flop per HBM byte on this chip while recomputing a score costs 2d flops,
+// so k_flash_bwd reads them back instead of multiplying again and runs only the second product,
+// with the roles of Q and K swapped.  Evaluation (PASS 3) only counts negatives scoring above
+// the positive.  TransE uses |q - n|^2 = |q|^2 + |n|^2 - 2 q.n for the scores and W = P / distance.
 #include "mar_common.h"
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-#ifndef MAR_FLASH_ABL
-#define MAR_FLASH_ABL 0      // timing experiments only, bit mask: 1 no exp, 2 no second product, 4 no score product, 8 no tile refill
-#endif
 
 struct FlashArgs {
   const float* X;      // stationary matrix, rows of dk floats
@@ -55,14 +54,14 @@ struct FlashGeom {
   static constexpr int NT = NK % 4;                                   // remaining k groups of 4
 };
 
-// PASS: 1 online softmax + gQ, 2 gK with given lse, 3 rank counts.  L2: TransE scores.
+// PASS: 1 scores + online softmax + gQ (training), 3 rank counts (evaluation).  L2: TransE scores.
 // XB: 16-row x-blocks per wave (a workgroup's stripe has 64*XB stationary rows); every LDS
 // fragment of Y then feeds XB matrix instructions.
 // LDS reads run one phase ahead of the matrix instructions that consume them: the first
 // fragments of the next block's score product are fetched before the current block's
 // second product is issued, and each row of the second product is fetched while the
 // previous row is being multiplied.
-template <int NK, int NC, int TY, int XB, int PASS, int L2>
+template <int NK, int NC, int VT, int TY, int XB, int PASS, int L2>
 __global__ void __launch_bounds__(256, (NK * XB <= 32 ? 3 : (NK * XB <= 64 ? 2 : 1)))
 k_flash(FlashArgs a) {
   typedef FlashGeom<NK> GM;
@@ -72,7 +71,6 @@ k_flash(FlashArgs a) {
   constexpr int NU = (TY * NK + 255) / 256;              // float4 units staged per thread
   constexpr int SR = 64 * XB;                             // stationary rows per workgroup
   __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
-  __shared__ float aux[TY];                               // per streamed row: lse (pass 2)
   __shared__ float auy[TY];                               // per streamed row: squared norm (TransE)
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -87,13 +85,13 @@ k_flash(FlashArgs a) {
   if (cs >= 2 * a.nchunks) return;
   const int side = cs & 1, c = cs >> 1;
   const int ne = min(a.S, a.n - c * a.S);                 // edges in this chunk
-  const int n_x = PASS == 2 ? a.N : ne;
-  const int n_y = PASS == 2 ? ne : a.N;
+  const int n_x = ne;                                     // stationary: the chunk's edges
+  const int n_y = a.N;                                    // streamed: the chunk's negatives
   if (stripe * SR >= n_x) return;
   const size_t q_base = (size_t)side * a.B + (size_t)c * a.S;       // first Q row of the chunk
   const size_t k_base = (size_t)side * a.C * a.N + (size_t)c * a.N; // first K row of the chunk
-  const size_t x_base = PASS == 2 ? k_base : q_base;
-  const size_t y_base = PASS == 2 ? q_base : k_base;
+  const size_t x_base = q_base;
+  const size_t y_base = k_base;
   const int dk = a.dk;
 
   // ---- stationary fragments: xf[4s+i] = X[x][16s + 4g + i], tail xf[4*N16+j] = X[x][16*N16 + 4j + g]
@@ -121,13 +119,19 @@ k_flash(FlashArgs a) {
     if (PASS == 3) posx[b] = xv[b] ? a.pos[(size_t)c * a.S + x[b]] : 0.f;
   }
 
+  // Output columns [0, 16*NC) of the second product go through the matrix cores; with VT the last
+  // 4 columns [16*NC, 16*NC + 4) are accumulated on the vector ALU instead (per lane over its own 4
+  // streamed rows, summed over the 4 lane groups at the end): a 16-wide block for 4 columns would
+  // waste 3/4 of its matrix instructions.
   v4f oacc[XB][NC];
+  float4 otail[XB];
   float mrun[XB], lrun[XB], wsum[XB];
   int cnt[XB];
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
 #pragma unroll
     for (int cb = 0; cb < NC; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+    otail[b] = make_float4(0.f, 0.f, 0.f, 0.f);
     mrun[b] = -3.0e38f; lrun[b] = 0.f; wsum[b] = 0.f; cnt[b] = 0;
   }
 
@@ -136,7 +140,7 @@ k_flash(FlashArgs a) {
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);     // this part streams tiles [t_begin, ntiles); may be empty
   float4 stage[NU];
-  float st_aux = 0.f, st_auy = 0.f;
+  float st_auy = 0.f;
   auto load_tile = [&](int t) {
     const int y0 = t * TY;
 #pragma unroll
@@ -150,17 +154,6 @@ k_flash(FlashArgs a) {
     }
     if (threadIdx.x < TY) {
       const int yr = y0 + threadIdx.x;
-      if (PASS == 2) {
-        // log-sum-exp of streamed row yr from the parts of pass 1
-        st_aux = __builtin_inff();
-        if (yr < n_y) {
-          const size_t pr = (size_t)2 * a.B;
-          float mm = -3.0e38f, ll = 0.f;
-          for (int p = 0; p < a.sy_ml; ++p) mm = fmaxf(mm, a.ml[(p * pr + y_base + yr) * 2]);
-          for (int p = 0; p < a.sy_ml; ++p) ll += a.ml[(p * pr + y_base + yr) * 2 + 1] * __expf(a.ml[(p * pr + y_base + yr) * 2] - mm);
-          st_aux = mm + logf(ll);
-        }
-      }
       if (L2) st_auy = yr < n_y ? a.yy[y_base + yr] : 0.f;
     }
   };
@@ -186,11 +179,10 @@ k_flash(FlashArgs a) {
       if (unit < TY * NK) *reinterpret_cast<float4*>(&tile[row * PITCH + 4 * cu]) = stage[u];
     }
     if (threadIdx.x < TY) {
-      if (PASS == 2) aux[threadIdx.x] = st_aux;
       if (L2) auy[threadIdx.x] = st_auy;
     }
     __syncthreads();
-    if (t + 1 < ntiles && !(MAR_FLASH_ABL & 8)) load_tile(t + 1);
+    if (t + 1 < ntiles) load_tile(t + 1);
 
     const int y0 = t * TY;
     const int nblk = min(TY / 16, (n_y - y0 + 15) / 16);
@@ -210,7 +202,6 @@ k_flash(FlashArgs a) {
       v4f tacc[XB];
 #pragma unroll
       for (int b = 0; b < XB; ++b) tacc[b] = (v4f){0.f, 0.f, 0.f, 0.f};
-#if !(MAR_FLASH_ABL & 4)
 #pragma unroll
       for (int s = 0; s < N16; ++s) {
         const float4 yv = q16[s % PD];
@@ -229,17 +220,12 @@ k_flash(FlashArgs a) {
 #pragma unroll
         for (int b = 0; b < XB; ++b) tacc[b] = mfma16(q1[j], xf[b][4 * N16 + j], tacc[b]);
       }
-#endif
       // -- scores and weights
       float w[XB][4];
-      float yy4[4] = {0.f, 0.f, 0.f, 0.f}, ls4[4] = {0.f, 0.f, 0.f, 0.f};
+      float yy4[4] = {0.f, 0.f, 0.f, 0.f};
       if (L2) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) yy4[r] = auy[yl + r];
-      }
-      if (PASS == 2) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) ls4[r] = aux[yl + r];
       }
 #pragma unroll
       for (int b = 0; b < XB; ++b) {
@@ -253,7 +239,7 @@ k_flash(FlashArgs a) {
             sc[r] = -dist[r];
           }
         }
-        if (PASS == 1 && a.T) {
+        if (PASS == 1) {
           // keep the raw scores for the negatives' gradient pass: row = edge, 4 consecutive negatives
           const int yc = y0 + yl;
           if (xv[b] && yc < a.tpitch)
@@ -261,7 +247,7 @@ k_flash(FlashArgs a) {
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          if (PASS != 2 && y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
+          if (y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
         }
         if (PASS == 3) {
 #pragma unroll
@@ -280,15 +266,13 @@ k_flash(FlashArgs a) {
             lrun[b] *= alpha;
 #pragma unroll
             for (int cb = 0; cb < NC; ++cb) oacc[b][cb] *= alpha;
+            if (VT) { otail[b].x *= alpha; otail[b].y *= alpha; otail[b].z *= alpha; otail[b].w *= alpha; }
             if (L2) wsum[b] *= alpha;
             mrun[b] = mnew;
           }
 #pragma unroll
-          for (int r = 0; r < 4; ++r) w[b][r] = (MAR_FLASH_ABL & 1) ? sc[r] : __expf(sc[r] - mrun[b]);
+          for (int r = 0; r < 4; ++r) w[b][r] = __expf(sc[r] - mrun[b]);
           lrun[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) w[b][r] = (MAR_FLASH_ABL & 1) ? sc[r] : __expf(sc[r] - ls4[r]);
         }
         if (PASS != 3 && L2) {
 #pragma unroll
@@ -298,7 +282,7 @@ k_flash(FlashArgs a) {
       }
       // first fragments of the next block's score product, fetched under the second product
       if (yb + 1 < nblk) load_head(yb + 1);
-      if (PASS != 3 && !(MAR_FLASH_ABL & 2)) {
+      if (PASS != 3) {
         // -- O^T[c][x] += sum_y Y[y][c] W[y][x]: A = Y fragment (row c), B = W (lane x)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -313,6 +297,14 @@ k_flash(FlashArgs a) {
           for (int cb = 0; cb < NC; ++cb) {
 #pragma unroll
             for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
+          }
+          if (VT) {
+            const float4 yt = *reinterpret_cast<const float4*>(&tile[(yl + r) * PITCH + 16 * NC]);
+#pragma unroll
+            for (int b = 0; b < XB; ++b) {
+              otail[b].x += yt.x * w[b][r]; otail[b].y += yt.y * w[b][r];
+              otail[b].z += yt.z * w[b][r]; otail[b].w += yt.w * w[b][r];
+            }
           }
         }
       }
@@ -340,9 +332,13 @@ k_flash(FlashArgs a) {
       ws += __shfl_xor(ws, 16);
       ws += __shfl_xor(ws, 32);
     }
+    float4 ot = otail[b];
+    if (VT) {
+      ot.x += __shfl_xor(ot.x, 16); ot.y += __shfl_xor(ot.y, 16); ot.z += __shfl_xor(ot.z, 16); ot.w += __shfl_xor(ot.w, 16);
+      ot.x += __shfl_xor(ot.x, 32); ot.y += __shfl_xor(ot.y, 32); ot.z += __shfl_xor(ot.z, 32); ot.w += __shfl_xor(ot.w, 32);
+    }
     if (!xv[b]) continue;
-    float* orow = PASS == 1 ? a.out + ((size_t)part * 2 * a.B + x_base + x[b]) * dk
-                            : a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x[b]] + part) * dk;
+    float* orow = a.out + ((size_t)part * 2 * a.B + x_base + x[b]) * dk;
 #pragma unroll
     for (int cb = 0; cb < NC; ++cb) {
       const int col = 16 * cb + 4 * g;                       // O^T rows 16cb + 4g + r of lane's column x
@@ -355,6 +351,14 @@ k_flash(FlashArgs a) {
         *reinterpret_cast<float4*>(orow + col) = o;
       }
     }
+    if (VT && g == 0 && 16 * NC < dk) {
+      float4 o = ot;
+      if (L2) {
+        const float4 xs = *reinterpret_cast<const float4*>(xrow[b] + 16 * NC);
+        o.x -= xs.x * ws; o.y -= xs.y * ws; o.z -= xs.z * ws; o.w -= xs.w * ws;
+      }
+      *reinterpret_cast<float4*>(orow + 16 * NC) = o;
+    }
   }
 }
 
@@ -364,7 +368,7 @@ k_flash(FlashArgs a) {
 // matching slice of the score rows go through LDS; only the second product runs on the matrix
 // cores.  Lane (g, m) takes T[e = 4g + r][j = m] of its 16-negative block, which is the
 // B-operand layout of O^T[c][j] += sum_e Q[e][c] W[e][j].
-template <int NK, int NC, int TY, int XB, int L2>
+template <int NK, int NC, int VT, int TY, int XB, int L2>
 __global__ void __launch_bounds__(256, (NK * XB <= 32 ? 3 : (NK * XB <= 64 ? 2 : 1)))
 k_flash_bwd(FlashArgs a) {
   typedef FlashGeom<NK> GM;
@@ -393,11 +397,13 @@ k_flash_bwd(FlashArgs a) {
   const int dk = a.dk;
 
   v4f oacc[XB][NC];
+  float4 otail[XB];                                       // last 4 output columns on the vector ALU (see k_flash)
   float wsum[XB];
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
 #pragma unroll
     for (int cb = 0; cb < NC; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+    otail[b] = make_float4(0.f, 0.f, 0.f, 0.f);
     wsum[b] = 0.f;
   }
 
@@ -496,6 +502,14 @@ k_flash_bwd(FlashArgs a) {
 #pragma unroll
           for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
         }
+        if (VT) {
+          const float4 yt = *reinterpret_cast<const float4*>(&tile[(yl + r) * PITCH + 16 * NC]);
+#pragma unroll
+          for (int b = 0; b < XB; ++b) {
+            otail[b].x += yt.x * w[b][r]; otail[b].y += yt.y * w[b][r];
+            otail[b].z += yt.z * w[b][r]; otail[b].w += yt.w * w[b][r];
+          }
+        }
       }
     }
   }
@@ -506,6 +520,11 @@ k_flash_bwd(FlashArgs a) {
     if (L2) {
       ws += __shfl_xor(ws, 16);
       ws += __shfl_xor(ws, 32);
+    }
+    float4 ot = otail[b];
+    if (VT) {
+      ot.x += __shfl_xor(ot.x, 16); ot.y += __shfl_xor(ot.y, 16); ot.z += __shfl_xor(ot.z, 16); ot.w += __shfl_xor(ot.w, 16);
+      ot.x += __shfl_xor(ot.x, 32); ot.y += __shfl_xor(ot.y, 32); ot.z += __shfl_xor(ot.z, 32); ot.w += __shfl_xor(ot.w, 32);
     }
     const int x = stripe * SR + (wave * XB + b) * 16 + m;
     if (x >= n_x) continue;
@@ -523,6 +542,14 @@ k_flash_bwd(FlashArgs a) {
         *reinterpret_cast<float4*>(orow + col) = o;
       }
     }
+    if (VT && g == 0 && 16 * NC < dk) {
+      float4 o = ot;
+      if (L2) {
+        const float4 xs = *reinterpret_cast<const float4*>(xrow + 16 * NC);
+        o.x -= xs.x * ws; o.y -= xs.y * ws; o.z -= xs.z * ws; o.w -= xs.w * ws;
+      }
+      *reinterpret_cast<float4*>(orow + 16 * NC) = o;
+    }
   }
 }
 
@@ -533,15 +560,13 @@ int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of th
 // Stationary rows per workgroup (64 per x-block of the instantiation that serves dk): pass 1 / 3 and pass 2.
 int mar_flash_stripe_rows(int dk, int pass) { return pass == 2 && dk / 4 <= 32 ? 128 : 64; }
 
-template <int NK, int NC, int TY, int XB, int BXB>
+template <int NK, int NC, int VT, int TY, int XB, int BXB>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
-#define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, TY, XB, P, L>), grid, dim3(256), 0, st, a)
+#define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, VT, TY, XB, P, L>), grid, dim3(256), 0, st, a)
   if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
   else if (pass == 2) {
-    if (a.T) {
-      if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, BXB, 1>), grid, dim3(256), 0, st, a);
-      else hipLaunchKernelGGL((k_flash_bwd<NK, NC, TY, BXB, 0>), grid, dim3(256), 0, st, a);
-    } else { if (l2) FL(2, 1); else FL(2, 0); }
+    if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, TY, BXB, 1>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, TY, BXB, 0>), grid, dim3(256), 0, st, a);
   }
   else { if (l2) FL(3, 1); else FL(3, 0); }
 #undef FL
@@ -553,10 +578,10 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const MarDims& d = c->dm;
   const MarLayout& L = c->L;
   FlashArgs a;
-  a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;
-  a.xx = pass == 2 ? L.kk : L.qq; a.yy = pass == 2 ? L.qq : L.kk;
+  a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;   // stationary / streamed matrix
+  a.xx = L.qq; a.yy = L.kk;
   a.ml = L.ml; a.pos = L.pos;
-  a.T = pass == 3 ? nullptr : L.T; a.tpitch = (d.N + 3) & ~3;
+  a.T = L.T; a.tpitch = (d.N + 3) & ~3;
   a.out = pass == 1 ? L.gQ : L.G;
   a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
@@ -570,9 +595,9 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
-  if (nk <= 13) return launch_sized<13, 4, 64, 1, 2>(a, pass, l2, grid, st);
-  if (nk <= 25) return launch_sized<25, 7, 64, 1, 2>(a, pass, l2, grid, st);
-  if (nk <= 32) return launch_sized<32, 8, 64, 1, 2>(a, pass, l2, grid, st);
-  if (nk <= 64) return launch_sized<64, 16, 32, 1, 1>(a, pass, l2, grid, st);
-  return launch_sized<100, 25, 32, 1, 1>(a, pass, l2, grid, st);
+  if (nk <= 13) return launch_sized<13, 3, 1, 64, 1, 2>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, 2>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, 2>(a, pass, l2, grid, st);
+  if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 1>(a, pass, l2, grid, st);
+  return launch_sized<100, 25, 0, 32, 1, 1>(a, pass, l2, grid, st);
 }
