@@ -19,6 +19,9 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3       # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
+# HBM bytes of the two contraction passes of one full kg_small step, from the rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs summarised in profiles/traffic_k_flash_kg_small.md (counters scaled by a 1 GiB copy).
+MEASURED_FLASH_TRAFFIC = {"kg_small": 253.0e6}
 
 
 def oracle_baseline(w, es, er, ed, budget_s=15.0):
@@ -169,7 +172,8 @@ def main():
                    "chunks": w.num_chunks, "negs_per_chunk": w.negs_per_chunk, "deg_negs_per_chunk": w.deg_negs_per_chunk},
         "roofline": {"bound": "mfma", "kernel": "k_flash (pass 1 + pass 2 of every step)", "achieved": achieved,
                      "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": None, "us_per_step": round(flash_us, 2),
+                     "traffic": MEASURED_FLASH_TRAFFIC.get(w.name) if not (args.edges or args.nodes) else None,
+                     "us_per_step": round(flash_us, 2),
                      "algorithmic_flops_per_step": 12.0 * w.batch_size * w.negs_per_chunk * w.dim},
         "phases_us_per_step": phases,
         "hbm_phases": {
