@@ -138,6 +138,18 @@ int mar_eval_scores(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const 
                     float* pos_scores, int32_t* rank_dst, int32_t* rank_src, void* hip_stream);
 
 /*
+ * Link-prediction metrics from ranks (Sec. 5.1): MRR = mean of 1/r_i and Hits@k = fraction of ranks
+ * r_i <= k over the candidate set (pass the ranks of both corrupted sides as one array of 2n
+ * candidates, or one side alone).
+ *   ranks : device, [n_ranks] int32, every rank >= 1
+ *   ks    : HOST array of num_k thresholds, 0 <= num_k <= 8
+ *   out   : device, out, [1 + num_k] doubles: MRR, then Hits@ks[0], Hits@ks[1], ...
+ * n_ranks = 0 writes zeros.  The sums are formed in a fixed order (bit-reproducible).
+ */
+int mar_rank_metrics(mar_ctx* ctx, const int32_t* ranks, int64_t n_ranks, const int32_t* ks, int32_t num_k,
+                     double* out, void* hip_stream);
+
+/*
  * Per-phase device timing of mar_train_batch with HIP events on the stream each phase runs on
  * (phases 0 and 4 run on the context's second stream beside phases 1-3, so the six times
  * overlap and do not add up to the step time).

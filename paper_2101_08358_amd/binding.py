@@ -37,6 +37,7 @@ class MarDebugOut(ctypes.Structure):
 
 
 EXPORTS = ("mar_workspace_bytes", "mar_init_tables", "mar_sample_negatives", "mar_train_batch", "mar_eval_scores",
+           "mar_rank_metrics",
            "mar_profile_enable", "mar_profile_read", "mar_destroy", "mar_last_error")
 
 
@@ -60,6 +61,7 @@ def load_library():
     lib.mar_sample_negatives.argtypes = [vp, u64, vp, vp, i64, vp, vp, vp]
     lib.mar_train_batch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, ctypes.POINTER(MarDebugOut), vp]
     lib.mar_eval_scores.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.mar_rank_metrics.argtypes = [vp, vp, i64, ctypes.POINTER(i32), i32, vp, vp]
     lib.mar_profile_enable.argtypes = [vp, i32, ctypes.c_uint32]
     lib.mar_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.mar_destroy.argtypes = [vp]
@@ -126,6 +128,11 @@ def mar_eval_scores(ctx, src, rel, dst, n_edges, neg_src, neg_dst, pos_scores, r
     _check(load_library().mar_eval_scores(ctx, _ptr(src), _ptr(rel), _ptr(dst), int(n_edges), _ptr(neg_src),
                                           _ptr(neg_dst), _ptr(pos_scores), _ptr(rank_dst), _ptr(rank_src),
                                           _stream(stream)))
+
+
+def mar_rank_metrics(ctx, ranks, n_ranks, ks, out, stream=None):
+    arr = (ctypes.c_int32 * max(len(ks), 1))(*ks)
+    _check(load_library().mar_rank_metrics(ctx, _ptr(ranks), int(n_ranks), arr, len(ks), _ptr(out), _stream(stream)))
 
 
 def mar_profile_enable(ctx, max_steps, phase_mask=(1 << NUM_PHASES) - 1):

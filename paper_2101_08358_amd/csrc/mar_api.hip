@@ -279,6 +279,17 @@ extern "C" int mar_eval_scores(mar_ctx* c, const int32_t* src, const int32_t* re
   return MAR_OK;
 }
 
+extern "C" int mar_rank_metrics(mar_ctx* c, const int32_t* ranks, int64_t n_ranks, const int32_t* ks, int32_t num_k,
+                                double* out, void* hip_stream) {
+  if (!c) return fail(MAR_EINVAL, "context is NULL");
+  if (!out) return fail(MAR_EINVAL, "out is NULL");
+  if (n_ranks < 0 || (n_ranks > 0 && !ranks)) return fail(MAR_EINVAL, "ranks is NULL or n_ranks negative");
+  if (num_k < 0 || num_k > 8 || (num_k > 0 && !ks)) return fail(MAR_ERANGE, "num_k outside 0..8 or ks NULL");
+  for (int j = 0; j < num_k; ++j) if (ks[j] < 1) return fail(MAR_EINVAL, "thresholds must be >= 1");
+  HIP_TRY(mar_launch_rank_metrics(ranks, n_ranks, ks, num_k, out, (hipStream_t)hip_stream), "metrics kernel");
+  return MAR_OK;
+}
+
 // ----------------------------------------------------------------------- profiling -----
 extern "C" int mar_profile_enable(mar_ctx* c, int32_t max_steps, uint32_t phase_mask) {
   if (!c) return fail(MAR_EINVAL, "context is NULL");

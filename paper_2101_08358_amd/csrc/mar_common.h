@@ -100,6 +100,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
 hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st);
 hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st);
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
+hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_t* ks, int num_k, double* out, hipStream_t st);
 int mar_flash_supported(int dk);
 int mar_flash_tile_rows(int dk);
 int mar_flash_stripe_rows(int dk, int pass);

@@ -75,3 +75,36 @@ def test_ranks_within_rounding_of_oracle(model, shape):
     got, exp = _run(model, V, R, dim, B, C, N, n, seed=10 + model)
     _tolerant(got, exp, B // C)
     assert got[1].min() >= 1 and got[1].max() <= N + 1
+
+
+def test_mrr_and_hits_from_gpu_ranks():
+    """Ranks -> MRR / Hits@k on the device against the oracle's reduction of the same ranks: hit counts are
+    integers (exact), the reciprocal sum is fp64 on both sides."""
+    from oracle import metrics
+    rng = np.random.default_rng(3)
+    V, R, dim, B, C, N, n = 4000, 5, 50, 1000, 10, 100, 940
+    ne = (rng.standard_normal((V, dim)) * 0.3).astype(np.float32)
+    re_ = (rng.standard_normal((R, dim)) * 0.3).astype(np.float32)
+    tr = mar.Trainer(V, R, dim, 0, B, C, N, node_emb=ne, rel_emb=re_)
+    tr.sample_negatives(5)
+    ids = [torch.from_numpy(rng.integers(0, hi, n).astype(np.int32)).to(tr.device) for hi in (V, R, V)]
+    pos, rd, rs = tr.eval_scores(*ids)
+    both = torch.cat([rd, rs]).contiguous()
+    ks = [1, 3, 10, 50]
+    out = torch.zeros(1 + len(ks), dtype=torch.float64, device=tr.device)
+    mar.mar_rank_metrics(tr.ctx, both, both.numel(), ks, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ranks = both.cpu().numpy()
+    assert abs(got[0] - metrics.mrr(ranks)) <= 1e-12
+    for j, k in enumerate(ks):
+        assert got[1 + j] == metrics.hits_at(ranks, k)
+    # degenerate sizes
+    mar.mar_rank_metrics(tr.ctx, both, 0, ks, out)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(out).item() == 0
+    one = torch.tensor([7], dtype=torch.int32, device=tr.device)
+    mar.mar_rank_metrics(tr.ctx, one, 1, [7], out)
+    torch.cuda.synchronize()
+    assert out[0].item() == 1.0 / 7 and out[1].item() == 1.0
+    tr.close()
