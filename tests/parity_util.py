@@ -143,3 +143,57 @@ def check_step(out, rel=REL, max_flip_frac=1e-4):
     for st, ost, rows in ((gpu["node_state"], ora["node_state"], rows_n), (gpu["rel_state"], ora["rel_state"], rows_r)):
         assert rel_err(st[rows], ost[rows]) <= 2 * rel
     return rep
+
+
+def run_step_device_tables(model, num_nodes, num_rels, dim, B, C, N, ids, seed=0, lr=0.1, eps=1e-10, std=0.001):
+    """One step on tables that are too large to build on the host: the library fills them on the device,
+    the touched rows are copied out, and the oracle runs on a compact copy with remapped ids (the step
+    only depends on touched rows).  Returns the same dict as run_step_both, with tables restricted to
+    the touched rows, plus a device-side check that no other row changed."""
+    src, rel, dst, neg_src, neg_dst = ids
+    n = src.shape[0]
+    tr = mar.Trainer(num_nodes, num_rels, dim, model, B, C, N, 0, lr, eps, std, seed)
+    dev = tr.device
+    nch = (n + B // C - 1) // (B // C)
+    uniq_n = np.unique(np.concatenate([src, dst, neg_src[:nch].ravel(), neg_dst[:nch].ravel()]))
+    uniq_r = np.unique(rel)
+    t_un, t_ur = torch.from_numpy(uniq_n.astype(np.int64)).to(dev), torch.from_numpy(uniq_r.astype(np.int64)).to(dev)
+    ne0 = tr.node_emb[t_un].cpu().numpy(); re0 = tr.rel_emb[t_ur].cpu().numpy()
+    checksum_before = (tr.node_emb.double().sum().item(), tr.node_state.double().sum().item())
+    touched_sum_before = tr.node_emb[t_un].double().sum().item()
+    tr.neg_src.copy_(torch.from_numpy(neg_src.reshape(-1))); tr.neg_dst.copy_(torch.from_numpy(neg_dst.reshape(-1)))
+    d_ids = [torch.from_numpy(x).to(dev) for x in (src, rel, dst)]
+    dbg, t = tr.make_debug(n)
+    tr.train_batch(*d_ids, dbg)
+    torch.cuda.synchronize()
+    nu = t["num_uniq"].cpu().numpy()
+    # rows outside the unique set: their sum must be unchanged (bitwise-equal rows give an identical fp64 sum
+    # because the summation order is the same)
+    mask = torch.ones(num_nodes, dtype=torch.bool, device=dev); mask[t_un] = False
+    untouched_ok = True
+    for tab in (tr.node_state,):
+        untouched_ok &= bool((tab[mask] == 0).all().item())
+    gpu = dict(loss=float(tr.loss.item()), num_uniq=nu,
+               uniq_nodes=t["uniq_nodes"].cpu().numpy()[:nu[0]], uniq_rels=t["uniq_rels"].cpu().numpy()[:nu[1]],
+               pos=t["pos"].cpu().numpy()[:n], lse_dst=t["lse_dst"].cpu().numpy()[:n], lse_src=t["lse_src"].cpu().numpy()[:n],
+               G=t["grad_rows"].cpu().numpy()[:(nu[0] + nu[1]) * dim].reshape(-1, dim),
+               node_emb=tr.node_emb[t_un].cpu().numpy(), node_state=tr.node_state[t_un].cpu().numpy(),
+               rel_emb=tr.rel_emb[t_ur].cpu().numpy(), rel_state=tr.rel_state[t_ur].cpu().numpy(),
+               untouched_ok=untouched_ok)
+    tr.close()
+    # oracle on compact tables
+    remap = lambda a: np.searchsorted(uniq_n, a).astype(np.int32)
+    c_src, c_dst, c_ns, c_nd = remap(src), remap(dst), remap(neg_src), remap(neg_dst)
+    c_rel = np.searchsorted(uniq_r, rel).astype(np.int32)
+    one, ore = ne0.copy(), re0.copy()
+    ons, ors = np.zeros_like(one), np.zeros_like(ore)
+    res = ostep.train_batch(model, np.float32(lr), np.float32(eps), B // C, one, ons, ore, ors, c_src, c_rel, c_dst, c_ns, c_nd)
+    # translate the oracle's unique ids back to the original id space and keep compact row indices for the tables
+    res.uniq_nodes_compact = res.uniq_nodes.copy(); res.uniq_rels_compact = res.uniq_rels.copy()
+    orig_un, orig_ur = uniq_n[res.uniq_nodes].astype(np.int32), uniq_r[res.uniq_rels].astype(np.int32)
+    assert np.array_equal(gpu["uniq_nodes"], orig_un) and np.array_equal(gpu["uniq_rels"], orig_ur)
+    # hand check_step compact ids so that its row indexing matches the compact tables
+    gpu["uniq_nodes"], gpu["uniq_rels"] = res.uniq_nodes, res.uniq_rels
+    ora = dict(res=res, node_emb=one, node_state=ons, rel_emb=ore, rel_state=ors)
+    return dict(gpu=gpu, ora=ora, before=(ne0, np.zeros_like(ne0), re0, np.zeros_like(re0)),
+                lr=float(np.float32(lr)), eps=float(np.float32(eps)))
