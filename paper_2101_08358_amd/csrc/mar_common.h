@@ -31,7 +31,7 @@ struct MarLayout {
   float*    lse;          // [2][batch] log-sum-exp per edge and side
   float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
   float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
-  float*    T;            // [2*chunks][S][N rounded up to 4] raw score block, pass 1 -> pass 2
+  float*    T;            // [2*chunks][S up to 64][N up to 64] raw score block, pass 1 -> pass 2
   float*    G;            // [n_occ][dk] one gradient row per occurrence, in row-sorted order
   float*    Gu;           // [u_max][dk] summed gradient per unique row
   float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders

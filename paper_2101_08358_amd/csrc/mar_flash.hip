@@ -37,13 +37,85 @@ struct FlashArgs {
   int32_t sy;          // workgroups sharing one stripe, each streaming `tps` tiles
   int32_t tps;
   int32_t sy_ml;       // parts pass 1 was split into
-  float* T;            // [2*nchunks][S][tpitch] raw scores of every (edge, negative) pair: written by pass 1,
-                       // read by the negatives' gradient pass (which then needs no score product)
-  int32_t tpitch;      // N rounded up to 4
+  float* T;            // [2*nchunks][trows][tpitch] raw scores of every (edge, negative) pair: written by
+                       // pass 1, read by the negatives' gradient pass (which then needs no score product)
+  int32_t tpitch;      // N rounded up to 64
+  int32_t trows;       // chunk size rounded up to 64
 };
 
 __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+
+// A operands of the second product O^T[c][x] += sum_y Y[y][c] W[y][x] for one streamed row y.
+// The 16 lanes m of a lane group supply the 16 output rows i of a matrix block; which output
+// COLUMN c a row i stands for is free, so blocks are grouped so that one lane's operands for
+// several blocks are consecutive floats of the row: a group of 4 blocks covers 64 columns with
+// block j taking c = base + 4 i + j (one 16-byte LDS read feeds 4 matrix instructions), a group
+// of 2 blocks 32 columns with c = base + 2 i + j, a single block c = base + i.
+template <int NC>
+__device__ __forceinline__ void load_orow(const float* __restrict__ yr, int m, float (&ya)[NC]) {
+  constexpr int NG4 = NC / 4, NG2 = (NC % 4) / 2, NG1 = NC % 2;
+#pragma unroll
+  for (int q = 0; q < NG4; ++q) {
+    const float4 v = *reinterpret_cast<const float4*>(yr + 64 * q + 4 * m);
+    ya[4 * q + 0] = v.x; ya[4 * q + 1] = v.y; ya[4 * q + 2] = v.z; ya[4 * q + 3] = v.w;
+  }
+  if (NG2) {
+    const float2 v = *reinterpret_cast<const float2*>(yr + 64 * NG4 + 2 * m);
+    ya[4 * NG4 + 0] = v.x; ya[4 * NG4 + 1] = v.y;
+  }
+  if (NG1) ya[NC - 1] = yr[64 * NG4 + 32 * NG2 + m];
+}
+
+// Writes the accumulators of one stationary row back in row order, undoing the column grouping of
+// load_orow: lane (g, .) register t of block cb holds output row i = 4g + t.  `sub` (TransE) is
+// subtracted as xs[c] * ws.
+template <int NC, bool SUB>
+__device__ __forceinline__ void store_orow(float* __restrict__ orow, const float* __restrict__ xs, float ws, int dk, int g,
+                                           const v4f (&o)[NC]) {
+  constexpr int NG4 = NC / 4, NG2 = (NC % 4) / 2, NG1 = NC % 2;
+#pragma unroll
+  for (int q = 0; q < NG4; ++q) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int col = 64 * q + 16 * g + 4 * t;
+      if (col < dk) {
+        float4 v = make_float4(o[4 * q][t], o[4 * q + 1][t], o[4 * q + 2][t], o[4 * q + 3][t]);
+        if (SUB) {
+          const float4 x = *reinterpret_cast<const float4*>(xs + col);
+          v.x -= x.x * ws; v.y -= x.y * ws; v.z -= x.z * ws; v.w -= x.w * ws;
+        }
+        *reinterpret_cast<float4*>(orow + col) = v;
+      }
+    }
+  }
+  if (NG2) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int col = 64 * NG4 + 8 * g + 2 * t;
+      if (col < dk) {
+        float2 v = make_float2(o[4 * NG4][t], o[4 * NG4 + 1][t]);
+        if (SUB) {
+          const float2 x = *reinterpret_cast<const float2*>(xs + col);
+          v.x -= x.x * ws; v.y -= x.y * ws;
+        }
+        *reinterpret_cast<float2*>(orow + col) = v;
+      }
+    }
+  }
+  if (NG1) {
+    const int col = 64 * NG4 + 32 * NG2 + 4 * g;
+    if (col < dk) {
+      float4 v = make_float4(o[NC - 1][0], o[NC - 1][1], o[NC - 1][2], o[NC - 1][3]);
+      if (SUB) {
+        const float4 x = *reinterpret_cast<const float4*>(xs + col);
+        v.x -= x.x * ws; v.y -= x.y * ws; v.z -= x.z * ws; v.w -= x.w * ws;
+      }
+      *reinterpret_cast<float4*>(orow + col) = v;
+    }
+  }
 }
 
 template <int NK>
@@ -61,8 +133,11 @@ struct FlashGeom {
 // fragments of the next block's score product are fetched before the current block's
 // second product is issued, and each row of the second product is fetched while the
 // previous row is being multiplied.
+#ifndef MAR_FLASH_WAVES_SMALL
+#define MAR_FLASH_WAVES_SMALL 2
+#endif
 template <int NK, int NC, int VT, int TY, int XB, int PASS, int L2>
-__global__ void __launch_bounds__(256, (NK * XB <= 32 ? 3 : (NK * XB <= 64 ? 2 : 1)))
+__global__ void __launch_bounds__(256, (NK * XB <= 32 ? MAR_FLASH_WAVES_SMALL : (NK * XB <= 64 ? 2 : 1)))
 k_flash(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
@@ -170,8 +245,9 @@ k_flash(FlashArgs a) {
     for (int j = 0; j < NT; ++j) q1[j] = tile[(yb * 16 + m) * PITCH + 16 * N16 + 4 * j + g];
   };
 
-  for (int t = t_begin; t < ntiles; ++t) {
-    __syncthreads();
+  // Moves the prefetched tile from the staging registers into LDS.  Called at the end of a tile's
+  // iteration (and once before the loop), between two barriers.
+  auto stage_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
       const int unit = threadIdx.x + 256 * u;
@@ -181,23 +257,28 @@ k_flash(FlashArgs a) {
     if (threadIdx.x < TY) {
       if (L2) auy[threadIdx.x] = st_auy;
     }
+  };
+  if (t_begin < ntiles) {
+    stage_tile();
     __syncthreads();
-    if (t + 1 < ntiles) load_tile(t + 1);
+  }
 
+  for (int t = t_begin; t < ntiles; ++t) {
+    const bool has_next = t + 1 < ntiles;
+    if (has_next) load_tile(t + 1);
     const int y0 = t * TY;
     const int nblk = min(TY / 16, (n_y - y0 + 15) / 16);
     load_head(0);
-#pragma unroll 1
-    for (int yb = 0; yb < nblk; ++yb) {
+    // One 16-row block of the tile.  For a full tile the blocks are unrolled so that the compiler can count
+    // the score stores issued after the next tile's prefetch loads and wait for the loads alone (loads and
+    // stores share one in-order counter; waiting for "everything" would stall on the stores' round trip).
+    auto process_block = [&](const int yb, const bool more) {
       const int yl = yb * 16 + 4 * g;                      // first of this lane's 4 streamed rows
       const float* yrow = &tile[(yb * 16 + m) * PITCH + 4 * g];
-      const float* ycol = &tile[yl * PITCH + m];
+      const float* ycol = &tile[yl * PITCH];
       // row 0 of the second product's A operand, fetched under the score product
-      float ya[NC];
-      if (PASS != 3) {
-#pragma unroll
-        for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[16 * cb];
-      }
+      float ya[NC > 0 ? NC : 1];
+      if (PASS != 3) load_orow<NC>(ycol, m, ya);
       // -- T[y][x]: lane (g, m), register r holds y = yb*16 + 4g + r, x = m
       v4f tacc[XB];
 #pragma unroll
@@ -240,10 +321,10 @@ k_flash(FlashArgs a) {
           }
         }
         if (PASS == 1) {
-          // keep the raw scores for the negatives' gradient pass: row = edge, 4 consecutive negatives
-          const int yc = y0 + yl;
-          if (xv[b] && yc < a.tpitch)
-            *reinterpret_cast<float4*>(a.T + ((size_t)cs * a.S + x[b]) * a.tpitch + yc) = make_float4(sc[0], sc[1], sc[2], sc[3]);
+          // keep the raw scores for the negatives' gradient pass: row = edge, 4 consecutive negatives.  The
+          // buffer is padded to whole stripes and tiles, so the store needs no bounds test (a conditional
+          // store would hide from the compiler how many stores follow the prefetch loads).
+          *reinterpret_cast<float4*>(a.T + ((size_t)cs * a.trows + x[b]) * a.tpitch + y0 + yl) = make_float4(sc[0], sc[1], sc[2], sc[3]);
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -281,7 +362,7 @@ k_flash(FlashArgs a) {
         }
       }
       // first fragments of the next block's score product, fetched under the second product
-      if (yb + 1 < nblk) load_head(yb + 1);
+      if (more) load_head(yb + 1);
       if (PASS != 3) {
         // -- O^T[c][x] += sum_y Y[y][c] W[y][x]: A = Y fragment (row c), B = W (lane x)
 #pragma unroll
@@ -289,10 +370,7 @@ k_flash(FlashArgs a) {
           float cur[NC];
 #pragma unroll
           for (int cb = 0; cb < NC; ++cb) cur[cb] = ya[cb];
-          if (r < 3) {
-#pragma unroll
-            for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[(r + 1) * PITCH + 16 * cb];
-          }
+          if (r < 3) load_orow<NC>(ycol + (r + 1) * PITCH, m, ya);
 #pragma unroll
           for (int cb = 0; cb < NC; ++cb) {
 #pragma unroll
@@ -308,6 +386,19 @@ k_flash(FlashArgs a) {
           }
         }
       }
+    };
+    if (nblk == TY / 16) {
+#pragma unroll
+      for (int yb = 0; yb < TY / 16; ++yb) process_block(yb, yb + 1 < TY / 16);
+      __syncthreads();                                     // every wave is done with this tile
+      if (has_next) stage_tile();
+      __syncthreads();
+    } else {
+#pragma unroll 1
+      for (int yb = 0; yb < nblk; ++yb) process_block(yb, yb + 1 < nblk);
+      __syncthreads();
+      if (has_next) stage_tile();
+      __syncthreads();
     }
   }
 
@@ -339,18 +430,7 @@ k_flash(FlashArgs a) {
     }
     if (!xv[b]) continue;
     float* orow = a.out + ((size_t)part * 2 * a.B + x_base + x[b]) * dk;
-#pragma unroll
-    for (int cb = 0; cb < NC; ++cb) {
-      const int col = 16 * cb + 4 * g;                       // O^T rows 16cb + 4g + r of lane's column x
-      if (col < dk) {
-        float4 o = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
-        if (L2) {
-          const float4 xs = *reinterpret_cast<const float4*>(xrow[b] + col);
-          o.x -= xs.x * ws; o.y -= xs.y * ws; o.z -= xs.z * ws; o.w -= xs.w * ws;
-        }
-        *reinterpret_cast<float4*>(orow + col) = o;
-      }
-    }
+    store_orow<NC, L2 != 0>(orow, xrow[b], ws, dk, g, oacc[b]);
     if (VT && g == 0 && 16 * NC < dk) {
       float4 o = ot;
       if (L2) {
@@ -429,7 +509,7 @@ k_flash_bwd(FlashArgs a) {
       const int row = unit / (SR / 4), j0 = stripe * SR + 4 * (unit % (SR / 4));
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (y0 + row < n_y && j0 < a.tpitch)
-        v = *reinterpret_cast<const float4*>(a.T + ((size_t)cs * a.S + y0 + row) * a.tpitch + j0);
+        v = *reinterpret_cast<const float4*>(a.T + ((size_t)cs * a.trows + y0 + row) * a.tpitch + j0);
       tstage[u] = v;
     }
     if (threadIdx.x < TY) {
@@ -468,10 +548,9 @@ k_flash_bwd(FlashArgs a) {
 #pragma unroll 1
     for (int yb = 0; yb < nblk; ++yb) {
       const int yl = yb * 16 + 4 * g;
-      const float* ycol = &tile[yl * PITCH + m];
+      const float* ycol = &tile[yl * PITCH];
       float ya[NC];
-#pragma unroll
-      for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[16 * cb];
+      load_orow<NC>(ycol, m, ya);
       float w[XB][4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -493,10 +572,7 @@ k_flash_bwd(FlashArgs a) {
         float cur[NC];
 #pragma unroll
         for (int cb = 0; cb < NC; ++cb) cur[cb] = ya[cb];
-        if (r < 3) {
-#pragma unroll
-          for (int cb = 0; cb < NC; ++cb) ya[cb] = ycol[(r + 1) * PITCH + 16 * cb];
-        }
+        if (r < 3) load_orow<NC>(ycol + (r + 1) * PITCH, m, ya);
 #pragma unroll
         for (int cb = 0; cb < NC; ++cb) {
 #pragma unroll
@@ -530,18 +606,7 @@ k_flash_bwd(FlashArgs a) {
     if (x >= n_x) continue;
     const float* xrow = a.X + (x_base + x) * dk;
     float* orow = a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] + part) * dk;
-#pragma unroll
-    for (int cb = 0; cb < NC; ++cb) {
-      const int col = 16 * cb + 4 * g;
-      if (col < dk) {
-        float4 o = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
-        if (L2) {
-          const float4 xs = *reinterpret_cast<const float4*>(xrow + col);
-          o.x -= xs.x * ws; o.y -= xs.y * ws; o.z -= xs.z * ws; o.w -= xs.w * ws;
-        }
-        *reinterpret_cast<float4*>(orow + col) = o;
-      }
-    }
+    store_orow<NC, L2 != 0>(orow, xrow, ws, dk, g, oacc[b]);
     if (VT && g == 0 && 16 * NC < dk) {
       float4 o = ot;
       if (L2) {
@@ -581,7 +646,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;   // stationary / streamed matrix
   a.xx = L.qq; a.yy = L.kk;
   a.ml = L.ml; a.pos = L.pos;
-  a.T = L.T; a.tpitch = (d.N + 3) & ~3;
+  a.T = L.T; a.tpitch = (d.N + 63) & ~63; a.trows = (d.S + 63) & ~63;
   a.out = pass == 1 ? L.gQ : L.G;
   a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
