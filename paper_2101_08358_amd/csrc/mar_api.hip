@@ -103,7 +103,7 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.seg_off = (uint32_t*)take((u1 + 1) * 4);
   l.inv = (int32_t*)take(n_occ * 4);
   l.slot = (int32_t*)take(n_occ * 4);
-  l.occ_pos = (int32_t*)take(n_occ * 4);
+  l.perm = (int32_t*)take(n_pos * 4);
   l.rank_sorted = (int32_t*)take(n_pos * 4);
   l.Q = (float*)take(2 * B * dk * 4);
   l.Km = (float*)take(2 * CN * dk * 4);
@@ -222,7 +222,7 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
     c->bitmap_dirty = 0;
   }
   // Two streams: the caller's carries the gather and the two contraction passes; the index build
-  // (needed first by pass 2) and the chain rule (needs pass 1 only) run beside them on `aux`.
+  // (needed only by the per-row reduce) and the chain rule (needs pass 1 only) run beside them on `aux`.
   hipStream_t ax = c->aux;
   hipEvent_t* ev = nullptr;
   if (c->prof_events && c->prof_steps < c->prof_max) ev = c->prof_events + (size_t)c->prof_steps * 2 * MAR_NUM_PHASES;
@@ -247,10 +247,10 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   HIP_TRY(mar_launch_chain(c, b, ax), "chain-rule kernel");
   MARK(4, 1, ax);
   HIP_TRY(hipEventRecord(c->ev_chain, ax), "join");
-  HIP_TRY(hipStreamWaitEvent(st, c->ev_index, 0), "join");
   MARK(3, 0, st);
   HIP_TRY(mar_launch_flash(c, b, 2, nullptr, nullptr, st), "negative-gradient kernel");
   MARK(3, 1, st);
+  HIP_TRY(hipStreamWaitEvent(st, c->ev_index, 0), "join");
   HIP_TRY(hipStreamWaitEvent(st, c->ev_chain, 0), "join");
   MARK(5, 0, st);
   HIP_TRY(mar_launch_reduce(c, b, loss_sum_out, dbg ? dbg->grad_rows : nullptr, st), "reduce/Adagrad kernels");

@@ -21,7 +21,7 @@ struct MarLayout {
   uint32_t* seg_off;      // exclusive scan of count: start of each row's segment
   int32_t*  inv;          // occurrence -> rank of its row among the unique rows
   int32_t*  slot;         // occurrence -> index inside its row's segment
-  int32_t*  occ_pos;      // occurrence -> position in row-sorted order
+  int32_t*  perm;         // position in row-sorted order -> gradient row
   int32_t*  rank_sorted;  // position -> rank
   float*    Q;            // [2][batch][dk] edge-side operands (side-major)
   float*    Km;           // [2][chunks][N][dk] gathered negative rows
@@ -32,7 +32,8 @@ struct MarLayout {
   float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
   float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
   float*    T;            // [2*chunks][S up to 64][N up to 64] raw score block, pass 1 -> pass 2
-  float*    G;            // [n_occ][dk] one gradient row per occurrence, in row-sorted order
+  float*    G;            // [3n + 2*cn*sy2][dk] gradient rows: occurrence k < 3n at row k, part i of negative
+                          // occurrence k at row 3n + (k - 3n)*sy2 + i
   float*    Gu;           // [u_max][dk] summed gradient per unique row
   float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders
   float*    loss_part;    // per-block partial loss sums

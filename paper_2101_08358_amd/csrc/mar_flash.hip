@@ -31,7 +31,6 @@ struct FlashArgs {
                        // written by pass 1, combined into the log-sum-exp by pass 2
   const float* pos;    // [B] positive scores (pass 3)
   float* out;          // pass 1: unnormalised gQ rows [sy][2][B][dk]; pass 2: gradient rows G
-  const int32_t* rowmap;  // pass 2: occ_pos of the negatives' occurrences (each owns sy consecutive rows)
   int32_t* rank_dst; int32_t* rank_src;   // pass 3
   int32_t n, B, C, N, S, cn, nchunks, dk, nstripes;
   int32_t sy;          // workgroups sharing one stripe, each streaming `tps` tiles
@@ -605,7 +604,9 @@ k_flash_bwd(FlashArgs a) {
     const int x = stripe * SR + (wave * XB + b) * 16 + m;
     if (x >= n_x) continue;
     const float* xrow = a.X + (x_base + x) * dk;
-    float* orow = a.out + ((size_t)a.rowmap[3 * (size_t)a.n + (side == MAR_SIDE_DST ? 0 : a.cn) + (size_t)c * a.N + x] + part) * dk;
+    // gradient row of part `part` of this negative's occurrence (occurrences: 3n edge-side ones, then the
+    // destination-replacing negatives, then the source-replacing ones)
+    float* orow = a.out + (3 * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x) * a.sy + part) * dk;
     store_orow<NC, L2 != 0>(orow, xrow, ws, dk, g, oacc[b]);
     if (VT && g == 0 && 16 * NC < dk) {
       float4 o = ot;
@@ -648,7 +649,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.ml = L.ml; a.pos = L.pos;
   a.T = L.T; a.tpitch = (d.N + 63) & ~63; a.trows = (d.S + 63) & ~63;
   a.out = pass == 1 ? L.gQ : L.G;
-  a.rowmap = L.occ_pos; a.rank_dst = rank_dst; a.rank_src = rank_src;
+  a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
   const int max_nx = pass == 2 ? d.N : (b.n < d.S ? b.n : d.S);
   const int sr = mar_flash_stripe_rows(d.dk, pass);

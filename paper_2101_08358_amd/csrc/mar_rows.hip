@@ -20,20 +20,25 @@ template <int GL> __device__ __forceinline__ float group_sum(float v) {
 }
 
 // -------------------------------------------------------------------- positions -----
-// Occurrence -> position in row-sorted order (a negative owns sy2 consecutive positions, one
-// per workgroup sharing its stripe in the second contraction pass); also clears the
-// occurrence's word of the touched-id map for the next step.
+// Row-sorted order of the gradient rows: position -> gradient row (a negative owns sy2
+// consecutive positions, one per workgroup sharing its stripe in the second contraction pass)
+// and position -> rank; also clears the occurrence's word of the touched-id map for the next step.
 __global__ void __launch_bounds__(256)
 k_positions(RowArgs a, int ipw_log2, const uint32_t* __restrict__ seg_off, const int32_t* __restrict__ inv,
-            const int32_t* __restrict__ slot, int32_t* __restrict__ occ_pos, int32_t* __restrict__ rank_sorted,
+            const int32_t* __restrict__ slot, int32_t* __restrict__ perm, int32_t* __restrict__ rank_sorted,
             uint32_t* __restrict__ bitmap) {
   const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (k >= a.n_occ) return;
   const int r = inv[k];
   const int p = (int)seg_off[r] + slot[k];
-  occ_pos[k] = p;
-  const int rows = k < 3 * (int64_t)a.n ? 1 : a.sy2;
-  for (int i = 0; i < rows; ++i) rank_sorted[p + i] = r;
+  // Gradient rows are written by their producers at fixed places (occurrence k < 3n: row k; the i-th
+  // part of negative occurrence k: row 3n + (k - 3n) * sy2 + i); perm lists them in row-sorted order.
+  const int64_t n3 = 3 * (int64_t)a.n;
+  if (k < n3) {
+    perm[p] = (int32_t)k; rank_sorted[p] = r;
+  } else {
+    for (int i = 0; i < a.sy2; ++i) { perm[p + i] = (int32_t)(n3 + (k - n3) * a.sy2 + i); rank_sorted[p + i] = r; }
+  }
   // unified id of the occurrence (same numbering as the index kernels)
   int64_t kk2 = k; uint32_t id;
   if (kk2 < a.n) id = a.src[kk2];
@@ -125,7 +130,7 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
 template <int GL>
 __global__ void __launch_bounds__(256, 8)
 k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, const float* __restrict__ pos,
-        float* __restrict__ lse, const int32_t* __restrict__ occ_pos, float* __restrict__ G, float* __restrict__ loss_part) {
+        float* __restrict__ lse, float* __restrict__ G, float* __restrict__ loss_part) {
   constexpr int GPB = 256 / GL;
   constexpr int MAXP = 8;
   __shared__ float lsum[GPB];
@@ -167,9 +172,9 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
     const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
     const float* r_row = a.rel_emb + (size_t)a.rel[e] * dim;
     const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
-    float* gs = G + (size_t)occ_pos[e] * dk;
-    float* gd = G + (size_t)occ_pos[a.n + e] * dk;
-    float* gr = G + (size_t)occ_pos[2 * (size_t)a.n + e] * dk;
+    float* gs = G + (size_t)e * dk;                              // gradient row of occurrence k is row k
+    float* gd = G + ((size_t)a.n + e) * dk;
+    float* gr = G + (2 * (size_t)a.n + e) * dk;
     if (a.model == MAR_MODEL_COMPLEX) {
       const int h = dim >> 1;
       for (int k = l; k < h; k += GL) {
@@ -222,6 +227,7 @@ struct ReduceArgs {
   float* Gu;                 // [unique rows][dk] summed gradient per unique row
   float* carry;              // [tasks][2][dk]
   const int32_t* rank_sorted;
+  const int32_t* perm;       // position in row-sorted order -> gradient row
   const uint32_t* seg_off;
   const int32_t* uniq;
   const int32_t* scalars;    // [0] = number of unique rows
@@ -231,8 +237,8 @@ struct ReduceArgs {
   float lr, eps;
 };
 
-// One wave per task of MAR_TASK_ROWS consecutive positions.  Rows of one segment (= one unique
-// table row) are summed; a segment that lies inside the task is finished here, one that
+// One wave per task of MAR_TASK_ROWS consecutive positions of the row-sorted order (the rows
+// themselves are gathered through perm).  Rows of one segment (= one unique table row) are summed; a segment that lies inside the task is finished here, one that
 // crosses the task's borders leaves a partial sum (slot 0: began earlier, slot 1: continues).
 // Rows are fetched BATCH at a time so that many loads are in flight per wave, and each lane
 // fetches its position's segment bounds up front so that no load depends on another.
@@ -246,6 +252,7 @@ __global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
   const int cnt = (int)(p1 - p0);
   const int nq = a.dk >> 2;
   const int my_rank = lane < cnt ? a.rank_sorted[p0 + lane] : -1;
+  const int my_row = lane < cnt ? a.perm[p0 + lane] : 0;
   const int64_t my_lo = lane < cnt ? (int64_t)a.seg_off[my_rank] : 0;
   const int64_t my_hi = lane < cnt ? (int64_t)a.seg_off[my_rank + 1] : 0;
   int cur = __shfl(my_rank, 0), cur_i = 0;
@@ -265,7 +272,7 @@ __global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
     float4 rows[BATCH][NV];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-      const float* row = a.G + (size_t)(p0 + i0 + j) * a.dk;
+      const float* row = a.G + (size_t)__shfl(my_row, (i0 + j) & 63) * a.dk;
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
         const int q = lane + 64 * v;
@@ -415,7 +422,7 @@ hipError_t mar_launch_positions(const mar_ctx* c, const MarBatch& b, hipStream_t
   const MarLayout& L = c->L;
   RowArgs a = row_args(c, b);
   hipLaunchKernelGGL(k_positions, dim3((unsigned)((b.n_occ + 255) / 256)), dim3(256), 0, st, a, (int)c->dm.ipw_log2, L.seg_off,
-                     L.inv, L.slot, L.occ_pos, L.rank_sorted, L.bitmap);
+                     L.inv, L.slot, L.perm, L.rank_sorted, L.bitmap);
   return hipGetLastError();
 }
 
@@ -437,7 +444,7 @@ hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st)
   RowArgs a = row_args(c, b);
   const int GL = lane_group(a.dk), gpb = 256 / GL;
   const dim3 grid((b.n + gpb - 1) / gpb), blk(256);
-#define CHAIN(GLV) hipLaunchKernelGGL(k_chain<GLV>, grid, blk, 0, st, a, L.gQ, L.ml, L.pos, L.lse, L.occ_pos, L.G, L.loss_part)
+#define CHAIN(GLV) hipLaunchKernelGGL(k_chain<GLV>, grid, blk, 0, st, a, L.gQ, L.ml, L.pos, L.lse, L.G, L.loss_part)
   if (GL == 16) CHAIN(16); else if (GL == 32) CHAIN(32); else CHAIN(64);
 #undef CHAIN
   return hipGetLastError();
@@ -448,7 +455,7 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
   const MarDims& d = c->dm;
   ReduceArgs a;
   a.node_emb = c->node_emb; a.node_state = c->node_state; a.rel_emb = c->rel_emb; a.rel_state = c->rel_state;
-  a.G = L.G; a.Gu = L.Gu; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.seg_off = L.seg_off; a.uniq = L.uniq;
+  a.G = L.G; a.Gu = L.Gu; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.perm = L.perm; a.seg_off = L.seg_off; a.uniq = L.uniq;
   a.scalars = L.scalars; a.dbg_grad = dbg_grad; a.n_rows = b.n_pos; a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk;
   a.lr = c->cfg.lr; a.eps = c->cfg.eps;
   const int64_t tasks = (b.n_pos + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
