@@ -21,7 +21,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3       # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
 # HBM bytes of the two contraction passes of one full kg_small step, from the rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs summarised in profiles/traffic_k_flash_kg_small.md (counters scaled by a 1 GiB copy).
-MEASURED_FLASH_TRAFFIC = {"kg_small": 253.0e6}
+MEASURED_FLASH_TRAFFIC = {"kg_small": 238.0e6}
 
 
 def oracle_baseline(w, es, er, ed, budget_s=15.0):

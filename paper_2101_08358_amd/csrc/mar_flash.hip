@@ -624,7 +624,10 @@ int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
 int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of the instantiation that serves dk
 
 // Stationary rows per workgroup (64 per x-block of the instantiation that serves dk): pass 1 / 3 and pass 2.
-int mar_flash_stripe_rows(int dk, int pass) { return pass == 2 && dk / 4 <= 32 ? 128 : 64; }
+#ifndef MAR_BWD_XB
+#define MAR_BWD_XB 2
+#endif
+int mar_flash_stripe_rows(int dk, int pass) { return pass == 2 && dk / 4 <= 32 ? 64 * MAR_BWD_XB : 64; }
 
 template <int NK, int NC, int VT, int TY, int XB, int BXB>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
@@ -661,9 +664,9 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
-  if (nk <= 13) return launch_sized<13, 3, 1, 64, 1, 2>(a, pass, l2, grid, st);
-  if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, 2>(a, pass, l2, grid, st);
-  if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, 2>(a, pass, l2, grid, st);
+  if (nk <= 13) return launch_sized<13, 3, 1, 64, 1, MAR_BWD_XB>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, MAR_BWD_XB>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, MAR_BWD_XB>(a, pass, l2, grid, st);
   if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 1>(a, pass, l2, grid, st);
   return launch_sized<100, 25, 0, 32, 1, 1>(a, pass, l2, grid, st);
 }
