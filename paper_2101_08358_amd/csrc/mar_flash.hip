@@ -38,7 +38,7 @@ struct FlashArgs {
   int32_t sy_ml;       // parts pass 1 was split into
   float* T;            // [2*nchunks][trows][tpitch] raw scores of every (edge, negative) pair: written by
                        // pass 1, read by the negatives' gradient pass (which then needs no score product)
-  int32_t tpitch;      // N rounded up to 64
+  int32_t tpitch;      // N rounded up to 128 (whole tiles of pass 1 and whole stripes of pass 2)
   int32_t trows;       // chunk size rounded up to 64
 };
 
@@ -213,22 +213,34 @@ k_flash(FlashArgs a) {
   const int ntiles_all = (n_y + TY - 1) / TY;
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);     // this part streams tiles [t_begin, ntiles); may be empty
+  // Per-thread staging slots: which row / float4 of a tile this thread moves.  Everything that does
+  // not depend on the tile is computed once here (the vector ALU does not run beside the matrix
+  // pipe on this chip, so index arithmetic in the tile loop costs matrix time).
   float4 stage[NU];
   float st_auy = 0.f;
+  int srow[NU], sgofs[NU], slofs[NU];                     // tile row, float offset in the tile (global), LDS offset
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    const int unit = threadIdx.x + 256 * u;
+    const int row = unit / NK, cu = unit % NK;
+    const bool ok = unit < TY * NK && 4 * cu < dk;
+    srow[u] = ok ? row : (1 << 30);                       // never below the rows left: loads zeros
+    sgofs[u] = row * dk + 4 * cu;
+    slofs[u] = unit < TY * NK ? row * PITCH + 4 * cu : -1;
+  }
   auto load_tile = [&](int t) {
     const int y0 = t * TY;
+    const int left = n_y - y0;                            // valid rows of this tile
+    const float* __restrict__ src = a.Y + (y_base + y0) * dk;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      const int unit = threadIdx.x + 256 * u;
-      const int row = unit / NK, cu = unit % NK;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (unit < TY * NK && y0 + row < n_y && 4 * cu < dk)
-        v = *reinterpret_cast<const float4*>(a.Y + (y_base + y0 + row) * dk + 4 * cu);
+      if (srow[u] < left) v = *reinterpret_cast<const float4*>(src + sgofs[u]);
       stage[u] = v;
     }
-    if (threadIdx.x < TY) {
+    if (L2 && threadIdx.x < TY) {
       const int yr = y0 + threadIdx.x;
-      if (L2) st_auy = yr < n_y ? a.yy[y_base + yr] : 0.f;
+      st_auy = yr < n_y ? a.yy[y_base + yr] : 0.f;
     }
   };
   if (t_begin < ntiles) load_tile(t_begin);
@@ -249,13 +261,9 @@ k_flash(FlashArgs a) {
   auto stage_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      const int unit = threadIdx.x + 256 * u;
-      const int row = unit / NK, cu = unit % NK;
-      if (unit < TY * NK) *reinterpret_cast<float4*>(&tile[row * PITCH + 4 * cu]) = stage[u];
+      if (slofs[u] >= 0) *reinterpret_cast<float4*>(&tile[slofs[u]]) = stage[u];
     }
-    if (threadIdx.x < TY) {
-      if (L2) auy[threadIdx.x] = st_auy;
-    }
+    if (L2 && threadIdx.x < TY) auy[threadIdx.x] = st_auy;
   };
   if (t_begin < ntiles) {
     stage_tile();
@@ -271,7 +279,7 @@ k_flash(FlashArgs a) {
     // One 16-row block of the tile.  For a full tile the blocks are unrolled so that the compiler can count
     // the score stores issued after the next tile's prefetch loads and wait for the loads alone (loads and
     // stores share one in-order counter; waiting for "everything" would stall on the stores' round trip).
-    auto process_block = [&](const int yb, const bool more) {
+    auto process_block = [&](const int yb, const bool more, const bool masked) {
       const int yl = yb * 16 + 4 * g;                      // first of this lane's 4 streamed rows
       const float* yrow = &tile[(yb * 16 + m) * PITCH + 4 * g];
       const float* ycol = &tile[yl * PITCH];
@@ -327,7 +335,7 @@ k_flash(FlashArgs a) {
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          if (y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
+          if (masked && y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
         }
         if (PASS == 3) {
 #pragma unroll
@@ -386,15 +394,15 @@ k_flash(FlashArgs a) {
         }
       }
     };
-    if (nblk == TY / 16) {
+    if (y0 + TY <= n_y) {                                  // full tile: no row masks, blocks unrolled
 #pragma unroll
-      for (int yb = 0; yb < TY / 16; ++yb) process_block(yb, yb + 1 < TY / 16);
+      for (int yb = 0; yb < TY / 16; ++yb) process_block(yb, yb + 1 < TY / 16, false);
       __syncthreads();                                     // every wave is done with this tile
       if (has_next) stage_tile();
       __syncthreads();
     } else {
 #pragma unroll 1
-      for (int yb = 0; yb < nblk; ++yb) process_block(yb, yb + 1 < nblk);
+      for (int yb = 0; yb < nblk; ++yb) process_block(yb, yb + 1 < nblk, true);
       __syncthreads();
       if (has_next) stage_tile();
       __syncthreads();
@@ -443,21 +451,20 @@ k_flash(FlashArgs a) {
 
 // Gradient w.r.t. the negatives' rows from stored scores: gK[j] = sum_e exp(T[e][j] - lse[e]) Q[e]
 // (TransE: weights divided by the distance, minus n_j times their sum).  A workgroup owns 64*XB
-// negatives (16*XB per wave) and streams the chunk's edges in tiles of TY: the Q rows and the
-// matching slice of the score rows go through LDS; only the second product runs on the matrix
-// cores.  Lane (g, m) takes T[e = 4g + r][j = m] of its 16-negative block, which is the
-// B-operand layout of O^T[c][j] += sum_e Q[e][c] W[e][j].
+// negatives (16*XB per wave) and streams the chunk's edges in tiles of TY: the Q rows go through
+// LDS, the scores straight from memory into registers -- lane (g, m) takes T[e = 4g + r][j = m]
+// of its 16-negative block, which is the B-operand layout of O^T[c][j] += sum_e Q[e][c] W[e][j] --
+// one tile ahead: as soon as a block's scores are consumed the same registers are refilled with
+// the next tile's.  Only the second product runs on the matrix cores.
 template <int NK, int NC, int VT, int TY, int XB, int L2>
-__global__ void __launch_bounds__(256, (NK * XB <= 32 ? 3 : (NK * XB <= 64 ? 2 : 1)))
+__global__ void __launch_bounds__(256, (NK * XB <= 64 ? 2 : 1))
 k_flash_bwd(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
   constexpr int SR = 64 * XB;                             // negatives per workgroup
-  constexpr int TP = SR + 4;                              // LDS pitch of the score slice: 4 mod 8
+  constexpr int NB = TY / 16;                             // 16-row blocks per tile
   constexpr int NU = (TY * NK + 255) / 256;              // float4 units of the Q tile staged per thread
-  constexpr int TU = TY * (SR / 4) / 256;                 // float4 units of the score slice per thread
   __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
-  __shared__ __attribute__((aligned(16))) float tt[TY * TP];
   __shared__ float aux[TY];                               // log-sum-exp of the streamed edges
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -489,29 +496,45 @@ k_flash_bwd(FlashArgs a) {
   const int ntiles_all = (n_y + TY - 1) / TY;
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);
-  float4 stage[NU], tstage[TU];
+
+  // staging slots of the Q tile (index arithmetic hoisted out of the tile loop)
+  float4 stage[NU];
   float st_aux = 0.f;
+  int srow[NU], sgofs[NU], slofs[NU];
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    const int unit = threadIdx.x + 256 * u;
+    const int row = unit / NK, cu = unit % NK;
+    const bool ok = unit < TY * NK && 4 * cu < dk;
+    srow[u] = ok ? row : (1 << 30);
+    sgofs[u] = row * dk + 4 * cu;
+    slofs[u] = unit < TY * NK ? row * PITCH + 4 * cu : -1;
+  }
+  // scores of the current tile: tr[yb][b][r] = T[e = y0 + 16 yb + 4g + r][j = stripe*SR + (wave*XB + b)*16 + m].
+  // The buffer is padded to whole tiles and stripes, so every address is valid; rows beyond the chunk
+  // carry lse = +inf and weigh nothing.
+  float tr[NB][XB][4];
+  const float* __restrict__ tcol = a.T + (size_t)cs * a.trows * a.tpitch + (size_t)(4 * g) * a.tpitch + stripe * SR + wave * XB * 16 + m;
+  auto load_scores = [&](int t, int yb) {
+    const float* __restrict__ p = tcol + (size_t)(t * TY + yb * 16) * a.tpitch;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int b = 0; b < XB; ++b) tr[yb][b][r] = p[(size_t)r * a.tpitch + 16 * b];
+    }
+  };
   auto load_tile = [&](int t) {
     const int y0 = t * TY;
+    const int left = n_y - y0;
+    const float* __restrict__ src = a.Y + (y_base + y0) * dk;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      const int unit = threadIdx.x + 256 * u;
-      const int row = unit / NK, cu = unit % NK;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (unit < TY * NK && y0 + row < n_y && 4 * cu < dk)
-        v = *reinterpret_cast<const float4*>(a.Y + (y_base + y0 + row) * dk + 4 * cu);
+      if (srow[u] < left) v = *reinterpret_cast<const float4*>(src + sgofs[u]);
       stage[u] = v;
     }
-#pragma unroll
-    for (int u = 0; u < TU; ++u) {
-      const int unit = threadIdx.x + 256 * u;
-      const int row = unit / (SR / 4), j0 = stripe * SR + 4 * (unit % (SR / 4));
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (y0 + row < n_y && j0 < a.tpitch)
-        v = *reinterpret_cast<const float4*>(a.T + ((size_t)cs * a.trows + y0 + row) * a.tpitch + j0);
-      tstage[u] = v;
-    }
     if (threadIdx.x < TY) {
+      // log-sum-exp of streamed row yr from the parts of pass 1
       const int yr = y0 + threadIdx.x;
       st_aux = __builtin_inff();
       if (yr < n_y) {
@@ -523,70 +546,77 @@ k_flash_bwd(FlashArgs a) {
       }
     }
   };
-  if (t_begin < ntiles) load_tile(t_begin);
-
-  for (int t = t_begin; t < ntiles; ++t) {
-    __syncthreads();
+  auto stage_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      const int unit = threadIdx.x + 256 * u;
-      const int row = unit / NK, cu = unit % NK;
-      if (unit < TY * NK) *reinterpret_cast<float4*>(&tile[row * PITCH + 4 * cu]) = stage[u];
-    }
-#pragma unroll
-    for (int u = 0; u < TU; ++u) {
-      const int unit = threadIdx.x + 256 * u;
-      *reinterpret_cast<float4*>(&tt[(unit / (SR / 4)) * TP + 4 * (unit % (SR / 4))]) = tstage[u];
+      if (slofs[u] >= 0) *reinterpret_cast<float4*>(&tile[slofs[u]]) = stage[u];
     }
     if (threadIdx.x < TY) aux[threadIdx.x] = st_aux;
+  };
+  if (t_begin < ntiles) {
+    load_tile(t_begin);
+#pragma unroll
+    for (int yb = 0; yb < NB; ++yb) load_scores(t_begin, yb);
+    stage_tile();
     __syncthreads();
-    if (t + 1 < ntiles) load_tile(t + 1);
+  }
 
+  for (int t = t_begin; t < ntiles; ++t) {
+    const bool has_next = t + 1 < ntiles;
+    if (has_next) load_tile(t + 1);
     const int y0 = t * TY;
-    const int nblk = min(TY / 16, (n_y - y0 + 15) / 16);
-#pragma unroll 1
-    for (int yb = 0; yb < nblk; ++yb) {
-      const int yl = yb * 16 + 4 * g;
-      const float* ycol = &tile[yl * PITCH];
-      float ya[NC];
-      load_orow<NC>(ycol, m, ya);
-      float w[XB][4];
+    const int nblk = min(NB, (n_y - y0 + 15) / 16);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float ls = aux[yl + r];
+    for (int yb = 0; yb < NB; ++yb) {
+      if (yb < nblk) {                                     // uniform over the workgroup
+        const int yl = yb * 16 + 4 * g;
+        const float* ycol = &tile[yl * PITCH];
+        float ya[NC];
+        load_orow<NC>(ycol, m, ya);
+        float w[XB][4];
 #pragma unroll
-        for (int b = 0; b < XB; ++b) {
-          const float sc = tt[(yl + r) * TP + (wave * XB + b) * 16 + m];
-          float v = __expf(sc - ls);                       // 0 for rows beyond the chunk (lse = +inf)
-          if (L2) v = sc < 0.f ? v / -sc : 0.f;            // score = -distance
-          w[b][r] = v;
-        }
-      }
-      if (L2) {
-#pragma unroll
-        for (int b = 0; b < XB; ++b) wsum[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float cur[NC];
-#pragma unroll
-        for (int cb = 0; cb < NC; ++cb) cur[cb] = ya[cb];
-        if (r < 3) load_orow<NC>(ycol + (r + 1) * PITCH, m, ya);
-#pragma unroll
-        for (int cb = 0; cb < NC; ++cb) {
-#pragma unroll
-          for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
-        }
-        if (VT) {
-          const float4 yt = *reinterpret_cast<const float4*>(&tile[(yl + r) * PITCH + 16 * NC]);
+        for (int r = 0; r < 4; ++r) {
+          const float ls = aux[yl + r];
 #pragma unroll
           for (int b = 0; b < XB; ++b) {
-            otail[b].x += yt.x * w[b][r]; otail[b].y += yt.y * w[b][r];
-            otail[b].z += yt.z * w[b][r]; otail[b].w += yt.w * w[b][r];
+            const float sc = tr[yb][b][r];
+            float v = __expf(sc - ls);                     // 0 for rows beyond the chunk (lse = +inf)
+            if (L2) v = sc < 0.f ? v / -sc : 0.f;          // score = -distance
+            w[b][r] = v;
           }
         }
+        if (has_next) load_scores(t + 1, yb);              // refill the registers just consumed
+        if (L2) {
+#pragma unroll
+          for (int b = 0; b < XB; ++b) wsum[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float cur[NC];
+#pragma unroll
+          for (int cb = 0; cb < NC; ++cb) cur[cb] = ya[cb];
+          if (r < 3) load_orow<NC>(ycol + (r + 1) * PITCH, m, ya);
+#pragma unroll
+          for (int cb = 0; cb < NC; ++cb) {
+#pragma unroll
+            for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
+          }
+          if (VT) {
+            const float4 yt = *reinterpret_cast<const float4*>(&tile[(yl + r) * PITCH + 16 * NC]);
+#pragma unroll
+            for (int b = 0; b < XB; ++b) {
+              otail[b].x += yt.x * w[b][r]; otail[b].y += yt.y * w[b][r];
+              otail[b].z += yt.z * w[b][r]; otail[b].w += yt.w * w[b][r];
+            }
+          }
+        }
+      } else if (has_next) {
+        load_scores(t + 1, yb);
       }
     }
+    __syncthreads();                                       // every wave is done with this tile
+    if (has_next) stage_tile();
+    __syncthreads();
   }
 
 #pragma unroll
@@ -650,7 +680,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;   // stationary / streamed matrix
   a.xx = L.qq; a.yy = L.kk;
   a.ml = L.ml; a.pos = L.pos;
-  a.T = L.T; a.tpitch = (d.N + 63) & ~63; a.trows = (d.S + 63) & ~63;
+  a.T = L.T; a.tpitch = (d.N + 127) & ~127; a.trows = (d.S + 63) & ~63;
   a.out = pass == 1 ? L.gQ : L.G;
   a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
