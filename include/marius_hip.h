@@ -150,6 +150,28 @@ int mar_rank_metrics(mar_ctx* ctx, const int32_t* ranks, int64_t n_ranks, const 
                      double* out, void* hip_stream);
 
 /*
+ * Edge-bucket ordering for out-of-memory training (Sec. 4.1).  Host-only: all pointers are HOST memory.
+ *   mar_beta_buffer_sequence  : Alg. 3.  Writes the sequence of partition buffers, row r = the c partition
+ *                               ids in the buffer at step r; successive rows differ by one swapped
+ *                               partition.  buffers == NULL only reports the number of rows.
+ *   mar_beta_edge_bucket_order: Alg. 3 + Alg. 4.  Writes all p*p edge buckets (i, j) as pairs[2k], pairs[2k+1]
+ *                               in processing order: every bucket the first time both partitions share the
+ *                               buffer; shuffle != 0 permutes the buckets of one buffer (Fisher-Yates from
+ *                               the back, j = mulhi64(x, k+1), x = words 0,1 of Philox4x32-10 with key =
+ *                               seed and counter (k, buffer index, 0, 0x40000000)).
+ *   mar_buffer_simulate       : Alg. 2 without the training: replays an order through a buffer of c
+ *                               partitions that evicts the partition needed furthest in the future and
+ *                               reports the number of partition loads (swaps = loads - c, the first fill
+ *                               of the buffer is not a swap).
+ *   mar_swap_lower_bound      : Eq. 2.     mar_beta_swap_count: Eq. 3.   (-1 unless 2 <= c <= p)
+ */
+int mar_beta_buffer_sequence(int32_t p, int32_t c, int32_t* buffers, int64_t capacity_rows, int64_t* num_rows);
+int mar_beta_edge_bucket_order(int32_t p, int32_t c, int32_t shuffle, uint64_t seed, int32_t* pairs);
+int mar_buffer_simulate(int32_t p, int32_t c, const int32_t* pairs, int64_t n_pairs, int64_t* loads);
+int64_t mar_swap_lower_bound(int32_t p, int32_t c);
+int64_t mar_beta_swap_count(int32_t p, int32_t c);
+
+/*
  * Per-phase device timing of mar_train_batch with HIP events on the stream each phase runs on
  * (phases 0 and 4 run on the context's second stream beside phases 1-3, so the six times
  * overlap and do not add up to the step time).

@@ -37,7 +37,8 @@ class MarDebugOut(ctypes.Structure):
 
 
 EXPORTS = ("mar_workspace_bytes", "mar_init_tables", "mar_sample_negatives", "mar_train_batch", "mar_eval_scores",
-           "mar_rank_metrics",
+           "mar_rank_metrics", "mar_beta_buffer_sequence", "mar_beta_edge_bucket_order", "mar_buffer_simulate",
+           "mar_swap_lower_bound", "mar_beta_swap_count",
            "mar_profile_enable", "mar_profile_read", "mar_destroy", "mar_last_error")
 
 
@@ -62,13 +63,20 @@ def load_library():
     lib.mar_train_batch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, ctypes.POINTER(MarDebugOut), vp]
     lib.mar_eval_scores.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.mar_rank_metrics.argtypes = [vp, vp, i64, ctypes.POINTER(i32), i32, vp, vp]
+    lib.mar_beta_buffer_sequence.argtypes = [i32, i32, vp, i64, ctypes.POINTER(i64)]
+    lib.mar_beta_edge_bucket_order.argtypes = [i32, i32, i32, u64, vp]
+    lib.mar_buffer_simulate.argtypes = [i32, i32, vp, i64, ctypes.POINTER(i64)]
+    lib.mar_swap_lower_bound.argtypes = [i32, i32]
+    lib.mar_beta_swap_count.argtypes = [i32, i32]
     lib.mar_profile_enable.argtypes = [vp, i32, ctypes.c_uint32]
     lib.mar_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.mar_destroy.argtypes = [vp]
     lib.mar_last_error.argtypes = [vp]
     lib.mar_last_error.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name != "mar_last_error":
+        if name in ("mar_swap_lower_bound", "mar_beta_swap_count"):
+            getattr(lib, name).restype = ctypes.c_int64
+        elif name != "mar_last_error":
             getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -133,6 +141,41 @@ def mar_eval_scores(ctx, src, rel, dst, n_edges, neg_src, neg_dst, pos_scores, r
 def mar_rank_metrics(ctx, ranks, n_ranks, ks, out, stream=None):
     arr = (ctypes.c_int32 * max(len(ks), 1))(*ks)
     _check(load_library().mar_rank_metrics(ctx, _ptr(ranks), int(n_ranks), arr, len(ks), _ptr(out), _stream(stream)))
+
+
+def mar_swap_lower_bound(p, c):
+    return int(load_library().mar_swap_lower_bound(p, c))
+
+
+def mar_beta_swap_count(p, c):
+    return int(load_library().mar_beta_swap_count(p, c))
+
+
+def mar_beta_buffer_sequence(p, c):
+    """Returns the buffer sequence as a numpy int32 array [rows, c] (host memory)."""
+    import numpy as np
+    rows = ctypes.c_int64(0)
+    _check(load_library().mar_beta_buffer_sequence(p, c, None, 0, ctypes.byref(rows)))
+    out = np.empty((rows.value, c), dtype=np.int32)
+    _check(load_library().mar_beta_buffer_sequence(p, c, out.ctypes.data, rows.value, ctypes.byref(rows)))
+    return out
+
+
+def mar_beta_edge_bucket_order(p, c, shuffle=False, seed=0):
+    """Returns the edge-bucket order as a numpy int32 array [p*p, 2] (host memory)."""
+    import numpy as np
+    out = np.empty((p * p, 2), dtype=np.int32)
+    _check(load_library().mar_beta_edge_bucket_order(p, c, 1 if shuffle else 0, int(seed), out.ctypes.data))
+    return out
+
+
+def mar_buffer_simulate(p, c, pairs):
+    """Partition loads of replaying `pairs` ([n, 2] int32, host) through a buffer of c partitions."""
+    import numpy as np
+    arr = np.ascontiguousarray(pairs, dtype=np.int32)
+    loads = ctypes.c_int64(0)
+    _check(load_library().mar_buffer_simulate(p, c, arr.ctypes.data, arr.shape[0], ctypes.byref(loads)))
+    return loads.value
 
 
 def mar_profile_enable(ctx, max_steps, phase_mask=(1 << NUM_PHASES) - 1):
