@@ -118,7 +118,6 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.Gu = (float*)take(u1 * dk * 4);
   l.carry = (float*)take(tasks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);
-  l.rank_tmp = (int32_t*)take(2 * B * 4);
   if (L) *L = l;
   return off;
 }

@@ -13,8 +13,9 @@
 // Workspace carve-up (device pointers).
 struct MarLayout {
   int32_t*  scalars;      // [16]: 0 = unique rows (nodes + relations), 1 = unique nodes
-  uint32_t* bitmap;       // one bit per unified id (node id, or num_nodes + relation id)
-  uint32_t* word_prefix;  // set bits before each bitmap word
+  uint32_t* bitmap;       // touched-id map over unified ids (node id, or num_nodes + relation id): one bit or
+                          // one byte per id, see ipw_log2
+  uint32_t* word_prefix;  // marked ids before each word of the map
   uint32_t* bsum;         // scan scratch (block sums)
   int32_t*  uniq;         // ascending unified ids of the touched rows
   uint32_t* count;        // occurrences per unique row (u_max + 1, last stays 0)
@@ -31,13 +32,12 @@ struct MarLayout {
   float*    lse;          // [2][batch] log-sum-exp per edge and side
   float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
   float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
-  float*    T;            // [2*chunks][S up to 64][N up to 64] raw score block, pass 1 -> pass 2
+  float*    T;            // [2*chunks][S rounded up to 64][N rounded up to 128] raw score block, pass 1 -> pass 2
   float*    G;            // [3n + 2*cn*sy2][dk] gradient rows: occurrence k < 3n at row k, part i of negative
                           // occurrence k at row 3n + (k - 3n)*sy2 + i
   float*    Gu;           // [u_max][dk] summed gradient per unique row
   float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders
   float*    loss_part;    // per-block partial loss sums
-  int32_t*  rank_tmp;     // [2][batch] scratch ranks when the caller passes none
 };
 
 struct MarDims {

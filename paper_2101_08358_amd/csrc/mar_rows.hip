@@ -1,7 +1,7 @@
 // Row-wise (bandwidth-bound) kernels of the training step (gfx950): gather of the batch's
 // rows into dense contraction operands, the chain rule from operand gradients back to the
-// source / relation / destination rows, and the per-row gradient reduction fused with the
-// sparse Adagrad scatter.
+// source / relation / destination rows, the per-row gradient reduction over the row-sorted
+// order, and the sparse Adagrad scatter.
 #include "mar_common.h"
 
 struct RowArgs {
@@ -49,22 +49,21 @@ k_positions(RowArgs a, int ipw_log2, const uint32_t* __restrict__ seg_off, const
 }
 
 // ---------------------------------------------------------------------- gather -----
-// Section B: one lane group per edge builds the two edge-side operands
+// Edge blocks: one lane group per edge builds the two edge-side operands
 //     side DST (negatives replace d): a_ej = <q, n_j>,  q = s*r (DistMult), s.r complex (ComplEx)
 //     side SRC (negatives replace s): b_ej = <q, m_j>,  q = r*d,            conj(r).d
 //   for TransE the scores are -|q - n_j| with q = s + r and q = d - r; also the positive score.
-// Section C: one lane group per negative copies its row into the dense per-chunk matrix.
+// Negative blocks: one lane group per negative copies its row into the dense per-chunk matrix.
 template <int GL>
 __global__ void __launch_bounds__(256)
 k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float* __restrict__ qq,
        float* __restrict__ kk, float* __restrict__ pos, float* __restrict__ pos_user) {
   const int blk = blockIdx.x;
-  constexpr int nbA = 0;
   constexpr int GPB = 256 / GL;                  // lane groups per block
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
   const int dim = a.dim, dk = a.dk;
-  if (blk < nbA + nbB) {
-    const int e = (blk - nbA) * GPB + grp;
+  if (blk < nbB) {
+    const int e = blk * GPB + grp;
     if (e >= a.n) return;
     const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
     const float* r_row = a.rel_emb + (size_t)a.rel[e] * dim;
@@ -101,7 +100,7 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
     return;
   }
   {
-    const int rr = (blk - nbA - nbB) * GPB + grp;          // row among 2*cn negatives
+    const int rr = (blk - nbB) * GPB + grp;                // row among 2*cn negatives
     if (rr >= 2 * a.cn) return;
     const int side = rr >= a.cn ? MAR_SIDE_DST : MAR_SIDE_SRC;
     const int cj = rr - (side == MAR_SIDE_DST ? a.cn : 0);  // chunk*N + j
