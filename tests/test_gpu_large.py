@@ -64,3 +64,41 @@ def test_social_shape_batch_on_a_41m_row_table(model):
     out = run_step_device_tables(model, V, R, dim, B, C, N, ids, seed=5)
     assert out["gpu"]["untouched_ok"]
     print(check_step(out, max_flip_frac=1e-3), flush=True)
+
+
+def test_large_kg_shape_with_degree_negatives_on_86m_rows():
+    """Geometry of the large-KG workload: 86.1 M nodes, 14,824 relations, ComplEx d = 100 (69 GB of tables and
+    accumulators), 50,000 edges, 50 chunks x 1,000 negatives of which 500 are drawn by degree through the
+    library's sampler from a power-law edge list (bit-exact against the oracle's sampler), then one step."""
+    import paper_2101_08358_amd as mar
+    w = synth.get_workload("kg_large")
+    E = 4_000_000
+    src, rel, dst = synth.make_graph(w.num_nodes, w.num_rels, E, w.node_zipf, w.rel_zipf, seed=1, device="cuda:0")
+    es, er, ed = src.cpu().numpy(), rel.cpu().numpy(), dst.cpu().numpy()
+    # negatives from the library's sampler on a small context that shares nothing but the configuration
+    tr = mar.Trainer(w.num_nodes, 1, 1, 0, w.batch_size, w.num_chunks, w.negs_per_chunk, w.deg_negs_per_chunk, seed=9)
+    tr.sample_negatives(123, src, dst)
+    torch.cuda.synchronize()
+    ns = tr.neg_src.cpu().numpy().reshape(w.num_chunks, w.negs_per_chunk)
+    nd = tr.neg_dst.cpu().numpy().reshape(w.num_chunks, w.negs_per_chunk)
+    tr.close()
+    del tr
+    torch.cuda.empty_cache()
+    ons, ond = sampling.sample_negatives(9, 123, w.num_nodes, es, ed, w.num_chunks, w.negs_per_chunk, w.deg_negs_per_chunk)
+    assert np.array_equal(ns, ons) and np.array_equal(nd, ond)
+    b = w.batch_size
+    out = run_step_device_tables(w.model, w.num_nodes, w.num_rels, w.dim, b, w.num_chunks, w.negs_per_chunk,
+                                 (es[:b].copy(), er[:b].copy(), ed[:b].copy(), ns, nd), seed=2)
+    assert out["gpu"]["untouched_ok"]
+    print(check_step(out, max_flip_frac=1e-3), flush=True)
+
+
+def test_wide_workload_full_size_160gb():
+    """The wide-embedding workload at full size: 50 M nodes x 400 floats (80 GB of embeddings + 80 GB of
+    accumulators), 100,000 edges, 100 chunks x 1,000 negatives."""
+    w = synth.get_workload("wide")
+    rng = np.random.default_rng(21)
+    ids = _hot_ids(rng, w.num_nodes, w.num_rels, w.batch_size, w.num_chunks, w.negs_per_chunk, 0.1)
+    out = run_step_device_tables(w.model, w.num_nodes, w.num_rels, w.dim, w.batch_size, w.num_chunks, w.negs_per_chunk, ids, seed=4)
+    assert out["gpu"]["untouched_ok"]
+    print(check_step(out, max_flip_frac=1e-3), flush=True)
