@@ -155,7 +155,7 @@ def main():
     scatter_bytes = n_occ * dk * 4 + U * w.dim * 16                                 # gradient rows read + theta/state r+w
     phases = {name: round(per_step(ms) * 1e3, 2) for name, ms in zip(mar.binding.PHASE_NAMES, phase_ms)}
     out = {
-        "metric": "training edges/sec per MI355X",
+        "metric": "training edges/sec per MI355X; achieved HBM GB/s + MFMA util vs peak",
         "value": edges / elapsed,
         "unit": "edges/s",
         "n_gpus": 1,
