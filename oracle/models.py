@@ -7,6 +7,8 @@
   ``dim`` floats stores the real parts first, then the imaginary parts.
 * TransE: only cited in Sec. 2.1 ("linear score functions").  Reading taken:
   f = -||s + r - d||_2 (not squared); the derivative at distance 0 is taken as 0.
+* Dot: f = theta_s . theta_d, "a dot product between the node embeddings of an edge" (Sec. 5.1,
+  "Embedding Models"); it has no relation parameters.
 
 ``neg_block`` / ``neg_block_backward`` evaluate one chunk's positives against the
 chunk's shared negative set: a[e, j] = f(s_e, r_e, n_j) when the negatives replace
@@ -19,6 +21,7 @@ import numpy as np
 DISTMULT = 0
 COMPLEX = 1
 TRANSE = 2
+DOT = 3
 
 SIDE_SRC = 0   # negatives replace the source
 SIDE_DST = 1   # negatives replace the destination
@@ -44,6 +47,8 @@ def score(model, s, r, d):
         return np.sum(_cplx(s) * _cplx(r) * np.conj(_cplx(d)), axis=-1).real
     if model == TRANSE:
         return -np.sqrt(np.sum((s + r - d) ** 2, axis=-1))
+    if model == DOT:
+        return np.sum(s * d + 0.0 * r, axis=-1)
     raise ValueError("unknown model %r" % (model,))
 
 
@@ -65,6 +70,8 @@ def score_grads(model, s, r, d):
         dist = np.sqrt(np.sum(diff ** 2, axis=-1, keepdims=True))
         unit = np.divide(diff, dist, out=np.zeros_like(diff), where=dist > 0)
         return -unit, -unit, unit
+    if model == DOT:
+        return d + 0.0 * r, 0.0 * (s + r + d), s + 0.0 * r
     raise ValueError("unknown model %r" % (model,))
 
 
@@ -74,6 +81,8 @@ def neg_block(model, side, S, R, D, Neg):
     if model == DISTMULT:
         q = S * R if side == SIDE_DST else R * D
         return q @ Neg.T
+    if model == DOT:
+        return (S if side == SIDE_DST else D) @ Neg.T
     if model == COMPLEX:
         if side == SIDE_DST:
             return ((_cplx(S) * _cplx(R)) @ np.conj(_cplx(Neg)).T).real
@@ -101,6 +110,10 @@ def neg_block_backward(model, side, S, R, D, Neg, P):
             return gq * R, gq * S, zero, P.T @ (S * R)
         gq = P @ Neg                          # d/d(r*d)
         return zero, gq * D, gq * R, P.T @ (R * D)
+    if model == DOT:
+        if side == SIDE_DST:
+            return P @ Neg, zero, zero, P.T @ S
+        return zero, zero, P @ Neg, P.T @ D
     if model == COMPLEX:
         sc, rc, dc, nc = _cplx(S), _cplx(R), _cplx(D), _cplx(Neg)
         if side == SIDE_DST:

@@ -57,7 +57,8 @@ def train_batch(model, lr, eps, chunk_size, node_emb, node_state, rel_emb, rel_s
     neg_dst = np.asarray(neg_dst, dtype=np.int64)[:nchunks]
 
     uniq_nodes = np.unique(np.concatenate([src, dst, neg_src.ravel(), neg_dst.ravel()]))
-    uniq_rels = np.unique(rel)
+    # Dot has no relation parameters: no relation row is touched
+    uniq_rels = np.unique(rel) if model != models.DOT else np.zeros(0, dtype=np.int64)
     G_nodes = np.zeros((uniq_nodes.shape[0], dim), dtype=np.float64)
     G_rels = np.zeros((uniq_rels.shape[0], dim), dtype=np.float64)
     node_row = lambda ids: np.searchsorted(uniq_nodes, ids)
@@ -75,7 +76,8 @@ def train_batch(model, lr, eps, chunk_size, node_emb, node_state, rel_emb, rel_s
         pos[lo:hi] = models.score(model, S, R, D)
         fs, fr, fd = models.score_grads(model, S, R, D)
         np.add.at(G_nodes, node_row(s_id), -2.0 * fs)
-        np.add.at(G_rels, rel_row(r_id), -2.0 * fr)
+        if model != models.DOT:
+            np.add.at(G_rels, rel_row(r_id), -2.0 * fr)
         np.add.at(G_nodes, node_row(d_id), -2.0 * fd)
 
         # one log-sum-exp term per corrupted side
@@ -87,7 +89,8 @@ def train_batch(model, lr, eps, chunk_size, node_emb, node_state, rel_emb, rel_s
             P = np.exp(A - lse[:, None])                       # d lse_e / d A[e, j]
             gS, gR, gD, gNeg = models.neg_block_backward(model, side, S, R, D, Neg, P)
             np.add.at(G_nodes, node_row(s_id), gS)
-            np.add.at(G_rels, rel_row(r_id), gR)
+            if model != models.DOT:
+                np.add.at(G_rels, rel_row(r_id), gR)
             np.add.at(G_nodes, node_row(d_id), gD)
             np.add.at(G_nodes, node_row(neg_ids), gNeg)
 

@@ -4,9 +4,9 @@ import numpy as np
 import pytest
 
 from oracle import models
-from oracle.models import DISTMULT, COMPLEX, TRANSE, SIDE_SRC, SIDE_DST
+from oracle.models import DISTMULT, COMPLEX, TRANSE, DOT, SIDE_SRC, SIDE_DST
 
-ALL = (DISTMULT, COMPLEX, TRANSE)
+ALL = (DISTMULT, COMPLEX, TRANSE, DOT)
 
 
 def rows(rng, *shape):
@@ -22,6 +22,16 @@ def test_distmult_closed_forms():
     assert np.allclose(models.score(DISTMULT, s, np.ones_like(r), d), np.sum(s * d, axis=1))   # r = 1 -> Dot
     # the printed form theta_s^T diag(theta_r) theta_d
     assert np.isclose(f[3], s[3] @ np.diag(r[3]) @ d[3])
+
+
+def test_dot_closed_forms():
+    rng = np.random.default_rng(9)
+    s, r, d = rows(rng, 7, 6), rows(rng, 7, 6), rows(rng, 7, 6)
+    f = models.score(DOT, s, r, d)
+    assert np.allclose(f, np.einsum("ek,ek->e", s, d), rtol=1e-13)
+    assert np.allclose(f, models.score(DISTMULT, s, np.ones_like(r), d), rtol=1e-13)       # DistMult with r = 1
+    assert np.array_equal(f, models.score(DOT, s, 5 * r, d))                               # no relation parameters
+    assert np.all(models.score_grads(DOT, s, r, d)[1] == 0)
 
 
 def test_complex_closed_forms():

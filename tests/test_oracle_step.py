@@ -9,9 +9,9 @@ import torch
 from scipy.special import logsumexp
 
 from oracle import models, step
-from oracle.models import DISTMULT, COMPLEX, TRANSE
+from oracle.models import DISTMULT, COMPLEX, TRANSE, DOT
 
-ALL = (DISTMULT, COMPLEX, TRANSE)
+ALL = (DISTMULT, COMPLEX, TRANSE, DOT)
 
 
 def tiny(seed, V=12, Rn=3, dim=6, n=7, S=4, N=3, scale=0.7):
@@ -82,6 +82,8 @@ def _torch_loss(model, ne, re_, t):
             h = s.shape[-1] // 2
             sr, si, rr, ri, dr, di = s[..., :h], s[..., h:], r[..., :h], r[..., h:], d[..., :h], d[..., h:]
             return (sr * rr * dr + si * rr * di + sr * ri * di - si * ri * dr).sum(-1)
+        if model == DOT:
+            return (s * d).sum(-1) + 0.0 * r.sum(-1)
         return -torch.linalg.vector_norm(s + r - d, dim=-1)
     L = 0.0
     n = len(t["src"])
