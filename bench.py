@@ -168,7 +168,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "num_nodes": w.num_nodes, "num_rels": w.num_rels, "num_edges": w.num_edges,
-                   "score": ["DistMult", "ComplEx", "TransE"][w.model], "dim": w.dim, "batch": w.batch_size,
+                   "score": ["DistMult", "ComplEx", "TransE", "Dot"][w.model], "dim": w.dim, "batch": w.batch_size,
                    "chunks": w.num_chunks, "negs_per_chunk": w.negs_per_chunk, "deg_negs_per_chunk": w.deg_negs_per_chunk},
         "roofline": {"bound": "mfma", "kernel": "k_flash (pass 1 + pass 2 of every step)", "achieved": achieved,
                      "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,

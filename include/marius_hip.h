@@ -44,6 +44,8 @@ extern "C" {
 #define MAR_MODEL_DISTMULT 0   /* theta_s^T diag(theta_r) theta_d, as printed in Sec. 2.1             */
 #define MAR_MODEL_COMPLEX  1   /* Re sum_k s_k r_k conj(d_k); row = [re(0..dim/2) | im(0..dim/2)]      */
 #define MAR_MODEL_TRANSE   2   /* -|| s + r - d ||_2                                                   */
+#define MAR_MODEL_DOT      3   /* theta_s . theta_d (Sec. 5.1, "Embedding Models"): no relation parameters; */
+                               /* rel ids are ignored (may be NULL) and relation rows are never touched  */
 
 #define MAR_MAX_DIM 400        /* largest supported row width in floats                              */
 

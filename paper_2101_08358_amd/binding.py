@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("MARIUS_HIP_LIB") or os.path.join(_HERE, "libmarius_hip.so")
 _lib = None
 
-MODEL_DISTMULT, MODEL_COMPLEX, MODEL_TRANSE = 0, 1, 2
+MODEL_DISTMULT, MODEL_COMPLEX, MODEL_TRANSE, MODEL_DOT = 0, 1, 2, 3
 NUM_PHASES = 6
 PHASE_NAMES = ("index", "gather", "score_softmax_gq", "neg_grad", "chain_rule", "reduce_adagrad")
 

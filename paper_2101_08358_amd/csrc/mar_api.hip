@@ -36,7 +36,7 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   if (cfg->num_nodes < 1 || cfg->num_rels < 1) return fail(MAR_EINVAL, "num_nodes and num_rels must be >= 1");
   if (cfg->num_nodes + (int64_t)cfg->num_rels >= ((int64_t)1 << 31))
     return fail(MAR_ERANGE, "num_nodes + num_rels must be below 2^31");
-  if (cfg->model < MAR_MODEL_DISTMULT || cfg->model > MAR_MODEL_TRANSE) return fail(MAR_EINVAL, "unknown model %d", cfg->model);
+  if (cfg->model < MAR_MODEL_DISTMULT || cfg->model > MAR_MODEL_DOT) return fail(MAR_EINVAL, "unknown model %d", cfg->model);
   if (cfg->dim < 1 || cfg->dim > MAR_MAX_DIM) return fail(MAR_ERANGE, "dim %d outside 1..%d", cfg->dim, MAR_MAX_DIM);
   if (cfg->model == MAR_MODEL_COMPLEX && (cfg->dim & 1)) return fail(MAR_EINVAL, "ComplEx needs an even dim");
   if (cfg->batch_size < 1 || cfg->num_chunks < 1 || cfg->negs_per_chunk < 1)
@@ -46,12 +46,13 @@ static int check_config(const mar_config* cfg, MarDims* d) {
     return fail(MAR_EINVAL, "deg_negs_per_chunk outside 0..negs_per_chunk");
   if (!(cfg->lr > 0.f) || !(cfg->eps >= 0.f)) return fail(MAR_EINVAL, "lr must be > 0 and eps >= 0");
   const int64_t cn = (int64_t)cfg->num_chunks * cfg->negs_per_chunk;
-  const int64_t n_occ = 3 * (int64_t)cfg->batch_size + 2 * cn;
-  if (n_occ >= ((int64_t)1 << 30)) return fail(MAR_ERANGE, "batch too large: 3*batch_size + 2*chunks*negatives must be below 2^30");
+  const int roles = cfg->model == MAR_MODEL_DOT ? 2 : 3;
+  const int64_t n_occ = roles * (int64_t)cfg->batch_size + 2 * cn;
+  if (3 * (int64_t)cfg->batch_size + 2 * cn >= ((int64_t)1 << 30)) return fail(MAR_ERANGE, "batch too large: 3*batch_size + 2*chunks*negatives must be below 2^30");
   d->dim = cfg->dim;
   d->dk = (cfg->dim + 3) & ~3;
   d->B = cfg->batch_size; d->C = cfg->num_chunks; d->S = cfg->batch_size / cfg->num_chunks;
-  d->N = cfg->negs_per_chunk; d->Ndeg = cfg->deg_negs_per_chunk;
+  d->N = cfg->negs_per_chunk; d->Ndeg = cfg->deg_negs_per_chunk; d->roles = roles;
   d->num_nodes = cfg->num_nodes; d->num_rels = cfg->num_rels;
   d->n_occ_max = n_occ;
   const int64_t ids = cfg->num_nodes + cfg->num_rels;
@@ -79,7 +80,7 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   };
   split(1, d->S, d->N, &d->sy1, &d->tps1);
   split(2, d->N, d->S, &d->sy2, &d->tps2);
-  d->n_pos_max = 3 * (int64_t)cfg->batch_size + 2 * cn * d->sy2;
+  d->n_pos_max = roles * (int64_t)cfg->batch_size + 2 * cn * d->sy2;
   return MAR_OK;
 }
 
@@ -194,13 +195,13 @@ static int make_batch(const mar_ctx* c, const int32_t* src, const int32_t* rel, 
                       const int32_t* neg_src, const int32_t* neg_dst, MarBatch* b) {
   if (!c) return fail(MAR_EINVAL, "context is NULL");
   if (n < 0 || n > c->dm.B) return fail(MAR_ERANGE, "n_edges %d outside 0..batch_size %d", n, c->dm.B);
-  if (n > 0 && (!src || !rel || !dst || !neg_src || !neg_dst)) return fail(MAR_EINVAL, "an id array is NULL");
+  if (n > 0 && (!src || (!rel && c->dm.roles == 3) || !dst || !neg_src || !neg_dst)) return fail(MAR_EINVAL, "an id array is NULL");
   b->src = src; b->rel = rel; b->dst = dst; b->neg_src = neg_src; b->neg_dst = neg_dst;
   b->n = n;
   b->nchunks = (n + c->dm.S - 1) / c->dm.S;
   b->cn = b->nchunks * c->dm.N;
-  b->n_occ = 3 * (int64_t)n + 2 * (int64_t)b->cn;
-  b->n_pos = 3 * (int64_t)n + 2 * (int64_t)b->cn * c->dm.sy2;
+  b->n_occ = c->dm.roles * (int64_t)n + 2 * (int64_t)b->cn;
+  b->n_pos = c->dm.roles * (int64_t)n + 2 * (int64_t)b->cn * c->dm.sy2;
   return MAR_OK;
 }
 

@@ -33,8 +33,8 @@ struct MarLayout {
   float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
   float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
   float*    T;            // [2*chunks][S rounded up to 64][N rounded up to 128] raw score block, pass 1 -> pass 2
-  float*    G;            // [3n + 2*cn*sy2][dk] gradient rows: occurrence k < 3n at row k, part i of negative
-                          // occurrence k at row 3n + (k - 3n)*sy2 + i
+  float*    G;            // [roles*n + 2*cn*sy2][dk] gradient rows: edge-side occurrence k < roles*n at row k, part i
+                          // of negative occurrence k at row roles*n + (k - roles*n)*sy2 + i
   float*    Gu;           // [u_max][dk] summed gradient per unique row
   float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders
   float*    loss_part;    // per-block partial loss sums
@@ -43,9 +43,10 @@ struct MarLayout {
 struct MarDims {
   int32_t dim, dk;                 // row width and its multiple-of-4 padding
   int32_t B, C, S, N, Ndeg;
+  int32_t roles;                   // edge-side occurrences per edge: source, destination and (unless Dot) relation
   int64_t num_nodes; int32_t num_rels;
-  int64_t n_occ_max;               // 3B + 2CN
-  int64_t n_pos_max;               // 3B + 2CN*sy2: gradient rows per step
+  int64_t n_occ_max;               // roles*B + 2CN
+  int64_t n_pos_max;               // roles*B + 2CN*sy2: gradient rows per step
   int32_t sy1, sy2;                // how many workgroups share the streamed rows of one stripe (pass 1 / 2)
   int32_t tps1, tps2;              // streamed tiles per workgroup
   int32_t ty;                      // rows per streamed tile
@@ -89,8 +90,8 @@ struct MarBatch {
   int32_t n;        // edges
   int32_t nchunks;  // ceil(n / S)
   int32_t cn;       // nchunks * N
-  int64_t n_occ;    // 3n + 2cn
-  int64_t n_pos;    // 3n + 2cn*sy2 gradient rows
+  int64_t n_occ;    // roles*n + 2cn
+  int64_t n_pos;    // roles*n + 2cn*sy2 gradient rows
 };
 
 hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st);

@@ -36,6 +36,7 @@ struct FlashArgs {
   int32_t sy;          // workgroups sharing one stripe, each streaming `tps` tiles
   int32_t tps;
   int32_t sy_ml;       // parts pass 1 was split into
+  int32_t roles;       // edge-side occurrences per edge (3, or 2 for Dot)
   float* T;            // [2*nchunks][trows][tpitch] raw scores of every (edge, negative) pair: written by
                        // pass 1, read by the negatives' gradient pass (which then needs no score product)
   int32_t tpitch;      // N rounded up to 128 (whole tiles of pass 1 and whole stripes of pass 2)
@@ -634,9 +635,9 @@ k_flash_bwd(FlashArgs a) {
     const int x = stripe * SR + (wave * XB + b) * 16 + m;
     if (x >= n_x) continue;
     const float* xrow = a.X + (x_base + x) * dk;
-    // gradient row of part `part` of this negative's occurrence (occurrences: 3n edge-side ones, then the
+    // gradient row of part `part` of this negative's occurrence (occurrences: roles*n edge-side ones, then the
     // destination-replacing negatives, then the source-replacing ones)
-    float* orow = a.out + (3 * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x) * a.sy + part) * dk;
+    float* orow = a.out + (a.roles * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x) * a.sy + part) * dk;
     store_orow<NC, L2 != 0>(orow, xrow, ws, dk, g, oacc[b]);
     if (VT && g == 0 && 16 * NC < dk) {
       float4 o = ot;
@@ -690,7 +691,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const int ncs = 2 * b.nchunks;
   a.sy = pass == 1 ? d.sy1 : (pass == 2 ? d.sy2 : 1);
   a.tps = pass == 1 ? d.tps1 : (pass == 2 ? d.tps2 : (1 << 30));
-  a.sy_ml = d.sy1;
+  a.sy_ml = d.sy1; a.roles = d.roles;
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;

@@ -86,21 +86,23 @@ __global__ void __launch_bounds__(256) k_fill_u32(uint32_t* __restrict__ p, int6
 }
 
 // ------------------------------------------------------------ occurrence numbering -----
-// Occurrence k of a batch with n edges and cn = chunks*N negatives per side:
-//   [0,n) source of edge k | [n,2n) destination | [2n,3n) relation |
-//   [3n,3n+cn) destination-replacing negatives | [3n+cn,3n+2cn) source-replacing negatives
+// Occurrence k of a batch with n edges and cn = chunks*N negatives per side (roles = 3, or 2 for
+// the relation-free Dot score, which has no relation occurrences):
+//   [0,n) source of edge k | [n,2n) destination | [2n,3n) relation (roles = 3 only) |
+//   [roles*n, +cn) destination-replacing negatives | then cn source-replacing negatives
 struct OccArgs {
   const int32_t *src, *rel, *dst, *neg_src, *neg_dst;
   int32_t n, cn;
   int32_t num_nodes;
+  int32_t roles;
 };
 
 __device__ __forceinline__ int32_t occ_unified_id(const OccArgs& a, int64_t k) {
   const int64_t n = a.n;
   if (k < n) return a.src[k];
   if (k < 2 * n) return a.dst[k - n];
-  if (k < 3 * n) return a.num_nodes + a.rel[k - 2 * n];
-  k -= 3 * n;
+  if (k < a.roles * n) return a.num_nodes + a.rel[k - 2 * n];
+  k -= a.roles * n;
   if (k < a.cn) return a.neg_dst[k];
   return a.neg_src[k - a.cn];
 }
@@ -307,7 +309,7 @@ k_count(OccArgs a, int64_t n_occ, int neg_mult, int L, const uint32_t* __restric
   __shared__ BlockAgg tab;
   const int64_t stride = (int64_t)gridDim.x * AGG_THREADS;
   const int64_t rounds = (n_occ + stride - 1) / stride;          // same trip count for every thread
-  const int64_t n_pos_occ = 3 * (int64_t)a.n;
+  const int64_t n_pos_occ = a.roles * (int64_t)a.n;
   for (int64_t it = 0; it < rounds; ++it) {
     agg_clear(tab);
     __syncthreads();
@@ -432,7 +434,7 @@ hipError_t mar_launch_sample(const mar_ctx* c, uint64_t step, const int32_t* es,
 hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
   const MarDims& d = c->dm;
   const MarLayout& L = c->L;
-  OccArgs a{b.src, b.rel, b.dst, b.neg_src, b.neg_dst, b.n, b.cn, (int32_t)d.num_nodes};
+  OccArgs a{b.src, b.rel, b.dst, b.neg_src, b.neg_dst, b.n, b.cn, (int32_t)d.num_nodes, d.roles};
   const int64_t n_count = d.u_max + 1;
   const int64_t work = b.n_occ > n_count ? b.n_occ : n_count;
   hipLaunchKernelGGL(k_mark, dim3(grid_for(work, AGG_THREADS, 2048)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.ipw_log2,

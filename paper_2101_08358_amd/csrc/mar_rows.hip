@@ -11,6 +11,7 @@ struct RowArgs {
   int64_t n_occ;
   int32_t num_nodes;
   int32_t sy1, sy2;      // parts per stripe in the two contraction passes
+  int32_t roles;         // 3, or 2 for the relation-free Dot score
 };
 
 template <int GL> __device__ __forceinline__ float group_sum(float v) {
@@ -31,9 +32,10 @@ k_positions(RowArgs a, int ipw_log2, const uint32_t* __restrict__ seg_off, const
   if (k >= a.n_occ) return;
   const int r = inv[k];
   const int p = (int)seg_off[r] + slot[k];
-  // Gradient rows are written by their producers at fixed places (occurrence k < 3n: row k; the i-th
-  // part of negative occurrence k: row 3n + (k - 3n) * sy2 + i); perm lists them in row-sorted order.
-  const int64_t n3 = 3 * (int64_t)a.n;
+  // Gradient rows are written by their producers at fixed places (edge-side occurrence k < roles*n: row k;
+  // the i-th part of negative occurrence k: row roles*n + (k - roles*n) * sy2 + i); perm lists them in
+  // row-sorted order.
+  const int64_t n3 = a.roles * (int64_t)a.n;
   if (k < n3) {
     perm[p] = (int32_t)k; rank_sorted[p] = r;
   } else {
@@ -43,8 +45,8 @@ k_positions(RowArgs a, int ipw_log2, const uint32_t* __restrict__ seg_off, const
   int64_t kk2 = k; uint32_t id;
   if (kk2 < a.n) id = a.src[kk2];
   else if (kk2 < 2 * (int64_t)a.n) id = a.dst[kk2 - a.n];
-  else if (kk2 < 3 * (int64_t)a.n) id = a.num_nodes + a.rel[kk2 - 2 * (int64_t)a.n];
-  else { kk2 -= 3 * (int64_t)a.n; id = kk2 < a.cn ? a.neg_dst[kk2] : a.neg_src[kk2 - a.cn]; }
+  else if (kk2 < n3) id = a.num_nodes + a.rel[kk2 - 2 * (int64_t)a.n];
+  else { kk2 -= n3; id = kk2 < a.cn ? a.neg_dst[kk2] : a.neg_src[kk2 - a.cn]; }
   bitmap[id >> ipw_log2] = 0u;
 }
 
@@ -66,7 +68,7 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
     const int e = blk * GPB + grp;
     if (e >= a.n) return;
     const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
-    const float* r_row = a.rel_emb + (size_t)a.rel[e] * dim;
+    const float* r_row = a.rel_emb + (size_t)(a.model == MAR_MODEL_DOT ? 0 : a.rel[e]) * dim;     // unused by Dot
     const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
     float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
     float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
@@ -85,6 +87,7 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
         const float s = s_row[k], r = r_row[k], d = d_row[k];
         float u, w;
         if (a.model == MAR_MODEL_DISTMULT) { u = s * r; w = r * d; acc += u * d; }
+        else if (a.model == MAR_MODEL_DOT) { u = s; w = d; acc += s * d; }
         else { u = s + r; w = d - r; const float df = u - d; acc += df * df; nd += u * u; ns += w * w; }
         qd[k] = u; qs[k] = w;
       }
@@ -169,7 +172,7 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
       return v;
     };
     const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
-    const float* r_row = a.rel_emb + (size_t)a.rel[e] * dim;
+    const float* r_row = a.rel_emb + (size_t)(a.model == MAR_MODEL_DOT ? 0 : a.rel[e]) * dim;
     const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
     float* gs = G + (size_t)e * dk;                              // gradient row of occurrence k is row k
     float* gd = G + ((size_t)a.n + e) * dk;
@@ -189,6 +192,11 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
         gr[k]     = sr * ure + si * uim + wre * dr + wim * di - 2.f * (sr * dr + si * di);
         gr[h + k] = sr * uim - si * ure + wre * di - wim * dr - 2.f * (sr * di - si * dr);
       }
+    } else if (a.model == MAR_MODEL_DOT) {
+      for (int k = l; k < dim; k += GL) {
+        gs[k] = merged(gu0, fu, k) - 2.f * d_row[k];
+        gd[k] = merged(gw0, fw, k) - 2.f * s_row[k];
+      }
     } else if (a.model == MAR_MODEL_DISTMULT) {
       for (int k = l; k < dim; k += GL) {
         const float s = s_row[k], r = r_row[k], d = d_row[k], u = merged(gu0, fu, k), w = merged(gw0, fw, k);
@@ -207,7 +215,7 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
         gd[k] = w - dl;
       }
     }
-    for (int k = dim + l; k < dk; k += GL) { gs[k] = 0.f; gd[k] = 0.f; gr[k] = 0.f; }
+    for (int k = dim + l; k < dk; k += GL) { gs[k] = 0.f; gd[k] = 0.f; if (a.roles == 3) gr[k] = 0.f; }
     le = -2.f * pos[e] + lse[(size_t)MAR_SIDE_DST * a.B + e] + lse[(size_t)MAR_SIDE_SRC * a.B + e];
   }
   if (l == 0) lsum[grp] = le;
@@ -411,7 +419,7 @@ static RowArgs row_args(const mar_ctx* c, const MarBatch& b) {
   a.src = b.src; a.rel = b.rel; a.dst = b.dst; a.neg_src = b.neg_src; a.neg_dst = b.neg_dst;
   a.n = b.n; a.cn = b.cn; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.dim = d.dim; a.dk = d.dk; a.model = c->cfg.model;
   a.n_occ = b.n_occ; a.num_nodes = (int32_t)d.num_nodes;
-  a.sy1 = d.sy1; a.sy2 = d.sy2;
+  a.sy1 = d.sy1; a.sy2 = d.sy2; a.roles = d.roles;
   return a;
 }
 

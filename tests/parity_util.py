@@ -116,6 +116,8 @@ def check_step(out, rel=REL, max_flip_frac=1e-4):
     worst = 0.0
     for tab, otab, st0, rows, g_gpu, g_or in ((gpu["node_emb"], ora["node_emb"], ns0, rows_n, Gg[:un], res.G_nodes),
                                               (gpu["rel_emb"], ora["rel_emb"], rs0, rows_r, Gg[un:], res.G_rels)):
+        if rows.size == 0:                       # e.g. the Dot score touches no relation row
+            continue
         bad = np.sign(g_gpu) != np.sign(g_or)
         flips += int(bad.sum()); total += bad.size
         rowmax = np.max(np.abs(g_or), axis=1, keepdims=True) + 1e-300

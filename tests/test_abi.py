@@ -52,7 +52,7 @@ def test_workspace_bytes_scales_and_validates(lib):
     big = mar.mar_workspace_bytes(_cfg(batch_size=1000, negs_per_chunk=200))
     assert 0 < small < big
     assert small % 256 == 0
-    for bad, code in ((dict(dim=0), -2), (dict(dim=401), -2), (dict(model=3), -1), (dict(model=1, dim=51), -1),
+    for bad, code in ((dict(dim=0), -2), (dict(dim=401), -2), (dict(model=4), -1), (dict(model=1, dim=51), -1),
                       (dict(batch_size=101), -2), (dict(num_chunks=0), -1), (dict(deg_negs_per_chunk=21), -1),
                       (dict(num_nodes=(1 << 31) - 2), -2), (dict(lr=0.0), -1), (dict(num_rels=0), -1)):
         with pytest.raises(mar.MarError) as e:

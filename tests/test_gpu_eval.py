@@ -31,7 +31,7 @@ def _run(model, V, R, dim, B, C, N, n, seed, std=0.3, integer=False):
     return got, exp
 
 
-@pytest.mark.parametrize("model", (0, 1, 2))
+@pytest.mark.parametrize("model", (0, 1, 2, 3))
 def test_ranks_exact_on_integer_embeddings(model):
     """Small-integer embeddings make every score's decisive quantity exact in fp32 and fp64 (the sum for
     DistMult / ComplEx, the squared distance for TransE, whose square root is monotone), ties included (a
@@ -68,7 +68,7 @@ def _tolerant(got, exp, S):
     assert decided >= 0.5 * 2 * n
 
 
-@pytest.mark.parametrize("model", (0, 1, 2))
+@pytest.mark.parametrize("model", (0, 1, 2, 3))
 @pytest.mark.parametrize("shape", ((5000, 9, 100, 2000, 2, 1000, 1700), (300, 2, 50, 100, 10, 100, 100)))
 def test_ranks_within_rounding_of_oracle(model, shape):
     V, R, dim, B, C, N, n = shape

@@ -7,10 +7,10 @@ from parity_util import run_step_both, check_step
 
 pytestmark = pytest.mark.gpu
 
-DISTMULT, COMPLEX, TRANSE = 0, 1, 2
+DISTMULT, COMPLEX, TRANSE, DOT = 0, 1, 2, 3
 
 
-@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE))
+@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE, DOT))
 @pytest.mark.parametrize("shape", (
     # (V, R, dim, B, C, N, n_edges)
     (500, 7, 50, 1000, 10, 100, 1000),        # config-1 geometry on a small graph (heavy row reuse)
@@ -25,14 +25,14 @@ def test_one_step_matches_oracle(model, shape):
     print(rep, flush=True)
 
 
-@pytest.mark.parametrize("model,dim", ((DISTMULT, 400), (COMPLEX, 200), (TRANSE, 36), (DISTMULT, 17), (COMPLEX, 128)))
+@pytest.mark.parametrize("model,dim", ((DISTMULT, 400), (COMPLEX, 200), (TRANSE, 36), (DISTMULT, 17), (COMPLEX, 128), (DOT, 100)))
 def test_one_step_other_widths(model, dim):
     print("case", model, dim, flush=True)
     out = run_step_both(model, 4000, 11, dim, 512, 4, 200, 512, seed=7 + dim)
     print(check_step(out), flush=True)
 
 
-@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE))
+@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE, DOT))
 def test_one_step_from_warm_state(model):
     """With accumulators of the size of G^2 the update is smooth in G: every element is compared."""
     from oracle import step as ostep
@@ -45,7 +45,8 @@ def test_one_step_from_warm_state(model):
            rng.integers(0, V, (C, N)).astype(np.int32))
     dry = ostep.train_batch(model, 0.1, 1e-10, B // C, tabs[0].copy(), np.zeros_like(tabs[0]), tabs[1].copy(),
                             np.zeros_like(tabs[1]), *ids, apply_update=False)
-    gn, gr = np.max(np.abs(dry.G_nodes)), np.max(np.abs(dry.G_rels))
+    gn = np.max(np.abs(dry.G_nodes))
+    gr = np.max(np.abs(dry.G_rels)) if dry.G_rels.size else 1.0      # Dot touches no relation row
     ns = ((rng.random((V, dim)) + 0.5) * gn * gn).astype(np.float32)
     rs = ((rng.random((R, dim)) + 0.5) * gr * gr).astype(np.float32)
     out = run_step_both(model, V, R, dim, B, C, N, B, seed=11, node_state=ns, rel_state=rs, ids=ids, tables=tabs)
@@ -53,6 +54,8 @@ def test_one_step_from_warm_state(model):
     gpu, ora = out["gpu"], out["ora"]
     for k in ("node_emb", "rel_emb", "node_state", "rel_state"):
         assert np.max(np.abs(gpu[k].astype(np.float64) - ora[k])) / np.max(np.abs(ora[k])) <= 1e-4, k
+    if model == DOT:
+        assert np.array_equal(gpu["rel_emb"], tabs[1]) and np.array_equal(gpu["rel_state"], rs)   # relations untouched
     print(rep, flush=True)
 
 
