@@ -211,6 +211,9 @@ class Trainer:
         def table(rows, given):
             if given is None:
                 return torch.empty((rows, dim), **f32)
+            if torch.is_tensor(given) and given.device == self.device and given.dtype == torch.float32 \
+                    and given.is_contiguous() and tuple(given.shape) == (rows, dim):
+                return given                                    # adopt the caller's device tensor in place
             return torch.as_tensor(given, dtype=torch.float32).to(self.device).contiguous().clone()
 
         self.node_emb = table(num_nodes, node_emb)

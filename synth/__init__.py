@@ -6,4 +6,4 @@ available offline; these generators produce stand-ins with the same sizes,
 degree skew and relation mix.
 """
 from .configs import CONFIGS, Workload, get_workload      # noqa: F401
-from .graphs import make_graph, zipf_ids                  # noqa: F401
+from .graphs import make_graph, make_tables, zipf_ids     # noqa: F401

@@ -48,3 +48,13 @@ def make_graph(num_nodes, num_rels, num_edges, node_zipf, rel_zipf, seed=0, devi
         else:
             rel[lo:hi] = zipf_ids(m, num_rels, rel_zipf, rel_perm, gen, device).to(torch.int32)
     return src, rel, dst
+
+
+def make_tables(num_nodes, num_rels, dim, std, seed=0, device="cpu"):
+    """Seeded N(0, std^2) node and relation tables (fp32) on ``device``: plain input data for runs whose
+    tables are too large to build on the host."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed) + 0x7AB1E5)
+    node = torch.randn((num_nodes, dim), generator=gen, device=device, dtype=torch.float32).mul_(std)
+    rel = torch.randn((num_rels, dim), generator=gen, device=device, dtype=torch.float32).mul_(std)
+    return node, rel

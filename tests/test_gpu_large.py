@@ -88,7 +88,7 @@ def test_large_kg_shape_with_degree_negatives_on_86m_rows():
     assert np.array_equal(ns, ons) and np.array_equal(nd, ond)
     b = w.batch_size
     out = run_step_device_tables(w.model, w.num_nodes, w.num_rels, w.dim, b, w.num_chunks, w.negs_per_chunk,
-                                 (es[:b].copy(), er[:b].copy(), ed[:b].copy(), ns, nd), seed=2)
+                                 (es[:b].copy(), er[:b].copy(), ed[:b].copy(), ons, ond), seed=2)
     assert out["gpu"]["untouched_ok"]
     print(check_step(out, max_flip_frac=1e-3), flush=True)
 
