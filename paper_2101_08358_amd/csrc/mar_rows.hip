@@ -316,12 +316,22 @@ __global__ void __launch_bounds__(256)
 k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, float* __restrict__ loss_out) {
   __shared__ float4 part[4][64 * NV];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (blockIdx.x == 0 && threadIdx.x < 64 && loss_out) {
-    float t = 0.f;
-    for (int i = lane; i < n_loss_part; i += 64) t += loss_part[i];
+  if (blockIdx.x == 0 && loss_out) {                        // uniform over the workgroup
+    // thread t adds terms t, t + 256, ... (four independent running sums so that loads overlap), then
+    // lanes, then the four waves in order: a fixed summation tree
+    __shared__ float wsum4[4];
+    float t4[4] = {0.f, 0.f, 0.f, 0.f};
+    int i = threadIdx.x;
+    for (; i + 768 < n_loss_part; i += 1024) {
+      t4[0] += loss_part[i]; t4[1] += loss_part[i + 256]; t4[2] += loss_part[i + 512]; t4[3] += loss_part[i + 768];
+    }
+    for (; i < n_loss_part; i += 256) t4[0] += loss_part[i];
+    float t = (t4[0] + t4[1]) + (t4[2] + t4[3]);
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) t += __shfl_xor(t, o);
-    if (lane == 0) *loss_out = t;
+    if (lane == 0) wsum4[wave] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) *loss_out = (wsum4[0] + wsum4[1]) + (wsum4[2] + wsum4[3]);
   }
   const int64_t task = blockIdx.x;
   const int64_t p0 = task * MAR_TASK_ROWS;
@@ -339,7 +349,7 @@ k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, floa
     acc[v] = (wave == 0 && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)task * 2 + 1) * a.dk + 4 * q)
                                    : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  constexpr int FB = 8;
+  constexpr int FB = 8;                                     // partial rows in flight per wave
   for (int64_t t = task + 1 + wave; t <= last_task; t += 4 * FB) {
     float4 rows[FB][NV];
 #pragma unroll
