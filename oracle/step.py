@@ -142,3 +142,27 @@ def eval_scores(model, chunk_size, node_emb, rel_emb, src, rel, dst, neg_src, ne
     if return_blocks:
         return pos, rank_dst, rank_src, blocks
     return pos, rank_dst, rank_src
+
+
+def filtered_ranks(model, node_emb, rel_emb, src, rel, dst, true_edges):
+    """Filtered link-prediction ranks (Sec. 5.1): every node is a candidate for the corrupted endpoint;
+    candidates that make another TRUE edge (a false negative) are left out; rank = 1 + number of remaining
+    candidates scoring strictly higher than the edge itself.  ``true_edges`` is an iterable of (s, r, d).
+    Returns (rank_dst, rank_src).  Plain loops over edges: for small graphs only."""
+    true_set = set((int(a), int(b), int(c)) for a, b, c in true_edges)
+    ne = node_emb.astype(np.float64)
+    re_ = rel_emb.astype(np.float64)
+    V = ne.shape[0]
+    n = len(src)
+    rank_dst = np.empty(n, dtype=np.int32)
+    rank_src = np.empty(n, dtype=np.int32)
+    for e in range(n):
+        s, r, d = int(src[e]), int(rel[e]), int(dst[e])
+        pos = float(models.score(model, ne[s], re_[r], ne[d]))
+        a = models.score(model, ne[s][None, :], re_[r][None, :], ne)            # all destinations
+        keep = np.array([(c == d) or ((s, r, c) not in true_set) for c in range(V)])
+        rank_dst[e] = 1 + int(np.sum((a > pos) & keep))
+        b = models.score(model, ne, re_[r][None, :], ne[d][None, :])            # all sources
+        keep = np.array([(c == s) or ((c, r, d) not in true_set) for c in range(V)])
+        rank_src[e] = 1 + int(np.sum((b > pos) & keep))
+    return rank_dst, rank_src

@@ -262,3 +262,32 @@ def test_training_reduces_the_loss():
     t = tiny(80, V=60, Rn=3, dim=8, n=40, S=10, N=8, scale=0.1)
     losses = [run(DISTMULT, t).loss_sum for _ in range(15)]
     assert losses[-1] < losses[0] - 1.0
+
+
+def test_filtered_ranks_properties_and_brute_force():
+    rng = np.random.default_rng(5)
+    V, Rn, dim = 15, 2, 4
+    ne = rng.integers(-3, 4, (V, dim)).astype(np.float32)            # exact arithmetic, ties included
+    re_ = rng.integers(-3, 4, (Rn, dim)).astype(np.float32)
+    edges = [(int(rng.integers(V)), int(rng.integers(Rn)), int(rng.integers(V))) for _ in range(40)]
+    src, rel, dst = (np.array(x) for x in zip(*edges[:12]))
+    fd, fs = step.filtered_ranks(DISTMULT, ne, re_, src, rel, dst, edges)
+    # unfiltered ranks against all nodes: every node once as a negative
+    allnodes = np.arange(V)[None, :]
+    _, ud, us = step.eval_scores(DISTMULT, 12, ne, re_, src, rel, dst, allnodes, allnodes)
+    assert np.all(fd <= ud) and np.all(fs <= us) and np.all(fd >= 1) and np.all(fs >= 1)
+    # with no other true edges nothing is filtered
+    fd0, fs0 = step.filtered_ranks(DISTMULT, ne, re_, src, rel, dst, list(zip(src, rel, dst)))
+    ok = [e for e in range(12) if sum(1 for t in zip(src, rel, dst) if t[0] == src[e] and t[1] == rel[e]) == 1]
+    assert all(fd0[e] == ud[e] for e in ok)
+    # brute force for one edge, one candidate at a time
+    e = 3
+    s, r, d = edges[e]
+    f = lambda a, b, c: float(models.score(DISTMULT, ne[a].astype(float), re_[b].astype(float), ne[c].astype(float)))
+    cnt = sum(1 for c in range(V) if (c == d or (s, r, c) not in set(edges)) and f(s, r, c) > f(s, r, d))
+    assert fd[e] == 1 + cnt
+    # filtering a candidate that outranks the edge lowers the rank by exactly one
+    better = [c for c in range(V) if c != d and (s, r, c) not in set(edges) and f(s, r, c) > f(s, r, d)]
+    if better:
+        fd2, _ = step.filtered_ranks(DISTMULT, ne, re_, src[e:e + 1], rel[e:e + 1], dst[e:e + 1], edges + [(s, r, better[0])])
+        assert fd2[0] == fd[e] - 1
