@@ -140,6 +140,25 @@ int mar_eval_scores(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const 
                     float* pos_scores, int32_t* rank_dst, int32_t* rank_src, void* hip_stream);
 
 /*
+ * Filtered ranks (Sec. 5.1: "false negatives ... will not be used in filtered evaluation").  Call after
+ * mar_eval_scores on a context whose negatives are ALL nodes, each exactly once (num_chunks chunks that
+ * all carry 0..num_nodes-1).  For edge i the caller lists the OTHER true destinations of (src[i], rel[i], .)
+ * in dst_ids[dst_off[i] .. dst_off[i+1]) and the other true sources of (., rel[i], dst[i]) in src_ids
+ * likewise; every listed candidate that scores strictly higher than the edge itself is taken out of the rank:
+ *     rank_dst[i] -= #{k : f(s, r, dst_ids[k]) > f(s, r, d)},   rank_src[i] likewise.
+ * Scores are evaluated per candidate on the vector ALU in the same operation order as the positive score
+ * (a candidate equal to the edge's own endpoint never counts); the ranks from mar_eval_scores come from the
+ * matrix cores, so a candidate within rounding of the positive can be counted on one side and not the other.
+ *   dst_off, src_off : device, [n_edges + 1] int64, non-decreasing, off[0] = 0
+ *   dst_ids, src_ids : device, node ids
+ *   pos_scores       : device, [n_edges], as written by mar_eval_scores
+ *   rank_dst, rank_src : device, in/out
+ */
+int mar_eval_filter(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const int32_t* dst, int32_t n_edges,
+                    const int64_t* dst_off, const int32_t* dst_ids, const int64_t* src_off, const int32_t* src_ids,
+                    const float* pos_scores, int32_t* rank_dst, int32_t* rank_src, void* hip_stream);
+
+/*
  * Link-prediction metrics from ranks (Sec. 5.1): MRR = mean of 1/r_i and Hits@k = fraction of ranks
  * r_i <= k over the candidate set (pass the ranks of both corrupted sides as one array of 2n
  * candidates, or one side alone).

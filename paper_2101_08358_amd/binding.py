@@ -37,7 +37,7 @@ class MarDebugOut(ctypes.Structure):
 
 
 EXPORTS = ("mar_workspace_bytes", "mar_init_tables", "mar_sample_negatives", "mar_train_batch", "mar_eval_scores",
-           "mar_rank_metrics", "mar_beta_buffer_sequence", "mar_beta_edge_bucket_order", "mar_buffer_simulate",
+           "mar_eval_filter", "mar_rank_metrics", "mar_beta_buffer_sequence", "mar_beta_edge_bucket_order", "mar_buffer_simulate",
            "mar_swap_lower_bound", "mar_beta_swap_count",
            "mar_profile_enable", "mar_profile_read", "mar_destroy", "mar_last_error")
 
@@ -62,6 +62,7 @@ def load_library():
     lib.mar_sample_negatives.argtypes = [vp, u64, vp, vp, i64, vp, vp, vp]
     lib.mar_train_batch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, ctypes.POINTER(MarDebugOut), vp]
     lib.mar_eval_scores.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.mar_eval_filter.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.mar_rank_metrics.argtypes = [vp, vp, i64, ctypes.POINTER(i32), i32, vp, vp]
     lib.mar_beta_buffer_sequence.argtypes = [i32, i32, vp, i64, ctypes.POINTER(i64)]
     lib.mar_beta_edge_bucket_order.argtypes = [i32, i32, i32, u64, vp]
@@ -135,6 +136,13 @@ def mar_train_batch(ctx, src, rel, dst, n_edges, neg_src, neg_dst, loss_sum_out=
 def mar_eval_scores(ctx, src, rel, dst, n_edges, neg_src, neg_dst, pos_scores, rank_dst, rank_src, stream=None):
     _check(load_library().mar_eval_scores(ctx, _ptr(src), _ptr(rel), _ptr(dst), int(n_edges), _ptr(neg_src),
                                           _ptr(neg_dst), _ptr(pos_scores), _ptr(rank_dst), _ptr(rank_src),
+                                          _stream(stream)))
+
+
+def mar_eval_filter(ctx, src, rel, dst, n_edges, dst_off, dst_ids, src_off, src_ids, pos_scores, rank_dst, rank_src,
+                    stream=None):
+    _check(load_library().mar_eval_filter(ctx, _ptr(src), _ptr(rel), _ptr(dst), int(n_edges), _ptr(dst_off), _ptr(dst_ids),
+                                          _ptr(src_off), _ptr(src_ids), _ptr(pos_scores), _ptr(rank_dst), _ptr(rank_src),
                                           _stream(stream)))
 
 

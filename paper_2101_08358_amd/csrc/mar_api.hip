@@ -281,6 +281,23 @@ extern "C" int mar_eval_scores(mar_ctx* c, const int32_t* src, const int32_t* re
   return MAR_OK;
 }
 
+extern "C" int mar_eval_filter(mar_ctx* c, const int32_t* src, const int32_t* rel, const int32_t* dst, int32_t n_edges,
+                               const int64_t* dst_off, const int32_t* dst_ids, const int64_t* src_off,
+                               const int32_t* src_ids, const float* pos_scores, int32_t* rank_dst, int32_t* rank_src,
+                               void* hip_stream) {
+  if (!c) return fail(MAR_EINVAL, "context is NULL");
+  if (n_edges < 0 || n_edges > c->dm.B) return fail(MAR_ERANGE, "n_edges %d outside 0..batch_size %d", n_edges, c->dm.B);
+  if (n_edges == 0) return MAR_OK;
+  if (!src || (!rel && c->dm.roles == 3) || !dst) return fail(MAR_EINVAL, "an id array is NULL");
+  if (!dst_off || !src_off || !pos_scores || !rank_dst || !rank_src) return fail(MAR_EINVAL, "an argument is NULL");
+  MarBatch b;
+  b.src = src; b.rel = rel; b.dst = dst; b.neg_src = nullptr; b.neg_dst = nullptr;
+  b.n = n_edges; b.nchunks = 0; b.cn = 0; b.n_occ = 0; b.n_pos = 0;
+  HIP_TRY(mar_launch_filter(c, b, dst_off, dst_ids, src_off, src_ids, pos_scores, rank_dst, rank_src, (hipStream_t)hip_stream),
+          "filter kernel");
+  return MAR_OK;
+}
+
 extern "C" int mar_rank_metrics(mar_ctx* c, const int32_t* ranks, int64_t n_ranks, const int32_t* ks, int32_t num_k,
                                 double* out, void* hip_stream) {
   if (!c) return fail(MAR_EINVAL, "context is NULL");

@@ -100,6 +100,9 @@ hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, 
 hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32_t* rank_dst, int32_t* rank_src,
                             hipStream_t st);
 hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st);
+hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t* dst_off, const int32_t* dst_ids,
+                             const int64_t* src_off, const int32_t* src_ids, const float* pos, int32_t* rank_dst,
+                             int32_t* rank_src, hipStream_t st);
 hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st);
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
 hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_t* ks, int num_k, double* out, hipStream_t st);

@@ -227,6 +227,61 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
   }
 }
 
+// ------------------------------------------------------------ filtered evaluation -----
+// Score f(s, r, d) of one triple by one lane group, in the operation order of the positive score above.
+template <int GL>
+__device__ __forceinline__ float group_score(int model, int dim, const float* __restrict__ s_row,
+                                             const float* __restrict__ r_row, const float* __restrict__ d_row, int l) {
+  float acc = 0.f;
+  if (model == MAR_MODEL_COMPLEX) {
+    const int h = dim >> 1;
+    for (int k = l; k < h; k += GL) {
+      const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
+      const float ure = sr * rr - si * ri, uim = sr * ri + si * rr;
+      acc += ure * dr + uim * di;
+    }
+  } else {
+    for (int k = l; k < dim; k += GL) {
+      const float s = s_row[k], r = r_row[k], d = d_row[k];
+      if (model == MAR_MODEL_DISTMULT) { const float u = s * r; acc += u * d; }
+      else if (model == MAR_MODEL_DOT) acc += s * d;
+      else { const float u = s + r; const float df = u - d; acc += df * df; }
+    }
+  }
+  acc = group_sum<GL>(acc);
+  return model == MAR_MODEL_TRANSE ? -sqrtf(acc) : acc;
+}
+
+// One lane group per (edge, corrupted side): takes the listed true candidates that outscore the edge
+// out of its rank.
+template <int GL>
+__global__ void __launch_bounds__(256)
+k_filter(RowArgs a, const int64_t* __restrict__ dst_off, const int32_t* __restrict__ dst_ids,
+         const int64_t* __restrict__ src_off, const int32_t* __restrict__ src_ids, const float* __restrict__ pos,
+         int32_t* __restrict__ rank_dst, int32_t* __restrict__ rank_src) {
+  constexpr int GPB = 256 / GL;
+  const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
+  const int idx = blockIdx.x * GPB + grp;
+  if (idx >= 2 * a.n) return;
+  const int side = idx >= a.n ? MAR_SIDE_DST : MAR_SIDE_SRC;
+  const int e = side == MAR_SIDE_DST ? idx - a.n : idx;
+  const int dim = a.dim;
+  const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
+  const float* r_row = a.rel_emb + (size_t)(a.model == MAR_MODEL_DOT ? 0 : a.rel[e]) * dim;
+  const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
+  const float p = pos[e];
+  const int64_t* off = side == MAR_SIDE_DST ? dst_off : src_off;
+  const int32_t* ids = side == MAR_SIDE_DST ? dst_ids : src_ids;
+  int better = 0;
+  for (int64_t k = off[e]; k < off[e + 1]; ++k) {
+    const float* c_row = a.node_emb + (size_t)ids[k] * dim;
+    const float f = side == MAR_SIDE_DST ? group_score<GL>(a.model, dim, s_row, r_row, c_row, l)
+                                         : group_score<GL>(a.model, dim, c_row, r_row, d_row, l);
+    better += f > p ? 1 : 0;
+  }
+  if (l == 0 && better) (side == MAR_SIDE_DST ? rank_dst : rank_src)[e] -= better;
+}
+
 // ------------------------------------------------- per-row reduce + Adagrad scatter -----
 struct ReduceArgs {
   float *node_emb, *node_state, *rel_emb, *rel_state;
@@ -453,6 +508,18 @@ hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, 
 #define PREP(GLV) hipLaunchKernelGGL(k_prep<GLV>, grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
   if (GL == 16) PREP(16); else if (GL == 32) PREP(32); else PREP(64);
 #undef PREP
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t* dst_off, const int32_t* dst_ids,
+                             const int64_t* src_off, const int32_t* src_ids, const float* pos, int32_t* rank_dst,
+                             int32_t* rank_src, hipStream_t st) {
+  RowArgs a = row_args(c, b);
+  const int GL = lane_group(a.dk), gpb = 256 / GL;
+  const dim3 grid((2 * b.n + gpb - 1) / gpb), blk(256);
+#define FILT(GLV) hipLaunchKernelGGL(k_filter<GLV>, grid, blk, 0, st, a, dst_off, dst_ids, src_off, src_ids, pos, rank_dst, rank_src)
+  if (GL == 16) FILT(16); else if (GL == 32) FILT(32); else FILT(64);
+#undef FILT
   return hipGetLastError();
 }
 

@@ -108,3 +108,39 @@ def test_mrr_and_hits_from_gpu_ranks():
     torch.cuda.synchronize()
     assert out[0].item() == 1.0 / 7 and out[1].item() == 1.0
     tr.close()
+
+
+@pytest.mark.parametrize("model", (0, 1, 2, 3))
+def test_filtered_ranks_against_oracle(model):
+    """All nodes as negatives, then the other true edges filtered out; small-integer embeddings make every
+    comparison exact, so the ranks must equal the oracle's."""
+    rng = np.random.default_rng(40 + model)
+    V, R, dim, n = 120, 3, 24, 90
+    ne = rng.integers(-2, 3, (V, dim)).astype(np.float32)
+    re_ = rng.integers(-2, 3, (R, dim)).astype(np.float32)
+    true_edges = [(int(rng.integers(V)), int(rng.integers(R)), int(rng.integers(V))) for _ in range(1500)]
+    true_edges = sorted(set(true_edges))
+    src, rel, dst = (np.array(x, dtype=np.int32) for x in zip(*true_edges[:n]))
+    # per eval edge: the other true destinations of (s, r, .) and the other true sources of (., r, d)
+    by_sr, by_rd = {}, {}
+    for s_, r_, d_ in true_edges:
+        by_sr.setdefault((s_, r_), []).append(d_)
+        by_rd.setdefault((r_, d_), []).append(s_)
+    dlist = [[c for c in by_sr[(s_, r_)] if c != d_] for s_, r_, d_ in zip(src, rel, dst)]
+    slist = [[c for c in by_rd[(r_, d_)] if c != s_] for s_, r_, d_ in zip(src, rel, dst)]
+    csr = lambda ls: (np.concatenate([[0], np.cumsum([len(x) for x in ls])]).astype(np.int64),
+                      np.array([c for x in ls for c in x] or [0], dtype=np.int32))
+    (doff, dids), (soff, sids) = csr(dlist), csr(slist)
+    assert doff[-1] > 0 and soff[-1] > 0
+    # one chunk whose negatives are all nodes
+    tr = mar.Trainer(V, R, dim, model, n, 1, V, node_emb=ne, rel_emb=re_)
+    allnodes = torch.arange(V, dtype=torch.int32, device=tr.device)
+    tr.neg_src.copy_(allnodes); tr.neg_dst.copy_(allnodes)
+    d_ids = [torch.from_numpy(x).to(tr.device) for x in (src, rel, dst)]
+    pos, rd, rs = tr.eval_scores(*d_ids)
+    dev = lambda x: torch.from_numpy(x).to(tr.device)
+    mar.mar_eval_filter(tr.ctx, d_ids[0], d_ids[1], d_ids[2], n, dev(doff), dev(dids), dev(soff), dev(sids), pos, rd, rs)
+    torch.cuda.synchronize()
+    ed, es = ostep.filtered_ranks(model, ne, re_, src, rel, dst, true_edges)
+    assert np.array_equal(rd.cpu().numpy(), ed) and np.array_equal(rs.cpu().numpy(), es)
+    tr.close()
