@@ -214,20 +214,25 @@ k_flash(FlashArgs a) {
   const int ntiles_all = (n_y + TY - 1) / TY;
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);     // this part streams tiles [t_begin, ntiles); may be empty
-  // Per-thread staging slots: which row / float4 of a tile this thread moves.  Everything that does
-  // not depend on the tile is computed once here (the vector ALU does not run beside the matrix
-  // pipe on this chip, so index arithmetic in the tile loop costs matrix time).
+  // Per-thread staging slots: which row / float4 of a tile this thread moves.  For narrow rows everything
+  // that does not depend on the tile is computed once here (the vector ALU does not run beside the matrix
+  // pipe on this chip, so index arithmetic in the tile loop costs matrix time); wide rows have many slots
+  // and no registers to spare, so they recompute the slot (a division by a constant) where it is used.
+  constexpr bool HOIST = NK <= 32;
+  constexpr int NH = HOIST ? NU : 1;
   float4 stage[NU];
   float st_auy = 0.f;
-  int srow[NU], sgofs[NU], slofs[NU];                     // tile row, float offset in the tile (global), LDS offset
-#pragma unroll
-  for (int u = 0; u < NU; ++u) {
+  int srow[NH], sgofs[NH], slofs[NH];                     // tile row, float offset in the tile (global), LDS offset
+  auto slot_of = [&](int u, int& row, int& gofs, int& lofs) {
     const int unit = threadIdx.x + 256 * u;
-    const int row = unit / NK, cu = unit % NK;
-    const bool ok = unit < TY * NK && 4 * cu < dk;
-    srow[u] = ok ? row : (1 << 30);                       // never below the rows left: loads zeros
-    sgofs[u] = row * dk + 4 * cu;
-    slofs[u] = unit < TY * NK ? row * PITCH + 4 * cu : -1;
+    const int r = unit / NK, cu = unit % NK;
+    row = (unit < TY * NK && 4 * cu < dk) ? r : (1 << 30);   // invalid slots: never below the rows left, load zeros
+    gofs = r * dk + 4 * cu;
+    lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+  };
+  if (HOIST) {
+#pragma unroll
+    for (int u = 0; u < NU; ++u) slot_of(u, srow[u], sgofs[u], slofs[u]);
   }
   auto load_tile = [&](int t) {
     const int y0 = t * TY;
@@ -235,8 +240,10 @@ k_flash(FlashArgs a) {
     const float* __restrict__ src = a.Y + (y_base + y0) * dk;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
+      int row, gofs, lofs;
+      if (HOIST) { row = srow[u]; gofs = sgofs[u]; } else slot_of(u, row, gofs, lofs);
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (srow[u] < left) v = *reinterpret_cast<const float4*>(src + sgofs[u]);
+      if (row < left) v = *reinterpret_cast<const float4*>(src + gofs);
       stage[u] = v;
     }
     if (L2 && threadIdx.x < TY) {
@@ -262,7 +269,9 @@ k_flash(FlashArgs a) {
   auto stage_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      if (slofs[u] >= 0) *reinterpret_cast<float4*>(&tile[slofs[u]]) = stage[u];
+      int row, gofs, lofs;
+      if (HOIST) lofs = slofs[u]; else slot_of(u, row, gofs, lofs);
+      if (lofs >= 0) *reinterpret_cast<float4*>(&tile[lofs]) = stage[u];
     }
     if (L2 && threadIdx.x < TY) auy[threadIdx.x] = st_auy;
   };
@@ -395,7 +404,8 @@ k_flash(FlashArgs a) {
         }
       }
     };
-    if (y0 + TY <= n_y) {                                  // full tile: no row masks, blocks unrolled
+    const bool full = y0 + TY <= n_y;                      // full tile: no row masks
+    if (NK <= 32 && full) {                                // narrow rows: blocks unrolled (wide rows lack the registers)
 #pragma unroll
       for (int yb = 0; yb < TY / 16; ++yb) process_block(yb, yb + 1 < TY / 16, false);
       __syncthreads();                                     // every wave is done with this tile
@@ -403,7 +413,7 @@ k_flash(FlashArgs a) {
       __syncthreads();
     } else {
 #pragma unroll 1
-      for (int yb = 0; yb < nblk; ++yb) process_block(yb, yb + 1 < nblk, true);
+      for (int yb = 0; yb < nblk; ++yb) process_block(yb, yb + 1 < nblk, !full);
       __syncthreads();
       if (has_next) stage_tile();
       __syncthreads();
@@ -498,18 +508,22 @@ k_flash_bwd(FlashArgs a) {
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);
 
-  // staging slots of the Q tile (index arithmetic hoisted out of the tile loop)
+  // staging slots of the Q tile (index arithmetic hoisted out of the tile loop for narrow rows, see k_flash)
+  constexpr bool HOIST = NK <= 32;
+  constexpr int NH = HOIST ? NU : 1;
   float4 stage[NU];
   float st_aux = 0.f;
-  int srow[NU], sgofs[NU], slofs[NU];
-#pragma unroll
-  for (int u = 0; u < NU; ++u) {
+  int srow[NH], sgofs[NH], slofs[NH];
+  auto slot_of = [&](int u, int& row, int& gofs, int& lofs) {
     const int unit = threadIdx.x + 256 * u;
-    const int row = unit / NK, cu = unit % NK;
-    const bool ok = unit < TY * NK && 4 * cu < dk;
-    srow[u] = ok ? row : (1 << 30);
-    sgofs[u] = row * dk + 4 * cu;
-    slofs[u] = unit < TY * NK ? row * PITCH + 4 * cu : -1;
+    const int r = unit / NK, cu = unit % NK;
+    row = (unit < TY * NK && 4 * cu < dk) ? r : (1 << 30);
+    gofs = r * dk + 4 * cu;
+    lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+  };
+  if (HOIST) {
+#pragma unroll
+    for (int u = 0; u < NU; ++u) slot_of(u, srow[u], sgofs[u], slofs[u]);
   }
   // scores of the current tile: tr[yb][b][r] = T[e = y0 + 16 yb + 4g + r][j = stripe*SR + (wave*XB + b)*16 + m].
   // The buffer is padded to whole tiles and stripes, so every address is valid; rows beyond the chunk
@@ -530,8 +544,10 @@ k_flash_bwd(FlashArgs a) {
     const float* __restrict__ src = a.Y + (y_base + y0) * dk;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
+      int row, gofs, lofs;
+      if (HOIST) { row = srow[u]; gofs = sgofs[u]; } else slot_of(u, row, gofs, lofs);
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (srow[u] < left) v = *reinterpret_cast<const float4*>(src + sgofs[u]);
+      if (row < left) v = *reinterpret_cast<const float4*>(src + gofs);
       stage[u] = v;
     }
     if (threadIdx.x < TY) {
@@ -550,7 +566,9 @@ k_flash_bwd(FlashArgs a) {
   auto stage_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      if (slofs[u] >= 0) *reinterpret_cast<float4*>(&tile[slofs[u]]) = stage[u];
+      int row, gofs, lofs;
+      if (HOIST) lofs = slofs[u]; else slot_of(u, row, gofs, lofs);
+      if (lofs >= 0) *reinterpret_cast<float4*>(&tile[lofs]) = stage[u];
     }
     if (threadIdx.x < TY) aux[threadIdx.x] = st_aux;
   };
