@@ -56,7 +56,8 @@ k_positions(RowArgs a, int ipw_log2, const uint32_t* __restrict__ seg_off, const
 //     side SRC (negatives replace s): b_ej = <q, m_j>,  q = r*d,            conj(r).d
 //   for TransE the scores are -|q - n_j| with q = s + r and q = d - r; also the positive score.
 // Negative blocks: one lane group per negative copies its row into the dense per-chunk matrix.
-template <int GL>
+// VEC: dim is a multiple of 4, rows are moved as float4 (float2 pairs for the two halves of a ComplEx row).
+template <int GL, bool VEC>
 __global__ void __launch_bounds__(256)
 k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float* __restrict__ qq,
        float* __restrict__ kk, float* __restrict__ pos, float* __restrict__ pos_user) {
@@ -73,7 +74,43 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
     float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
     float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
     float acc = 0.f, nd = 0.f, ns = 0.f;
-    if (a.model == MAR_MODEL_COMPLEX) {
+    if (VEC && a.model == MAR_MODEL_COMPLEX) {
+      const int h = dim >> 1;
+      for (int k = 2 * l; k < h; k += 2 * GL) {
+        const float2 sr = *reinterpret_cast<const float2*>(s_row + k), si = *reinterpret_cast<const float2*>(s_row + h + k);
+        const float2 rr = *reinterpret_cast<const float2*>(r_row + k), ri = *reinterpret_cast<const float2*>(r_row + h + k);
+        const float2 dr = *reinterpret_cast<const float2*>(d_row + k), di = *reinterpret_cast<const float2*>(d_row + h + k);
+        const float2 ure = make_float2(sr.x * rr.x - si.x * ri.x, sr.y * rr.y - si.y * ri.y);
+        const float2 uim = make_float2(sr.x * ri.x + si.x * rr.x, sr.y * ri.y + si.y * rr.y);
+        const float2 wre = make_float2(rr.x * dr.x + ri.x * di.x, rr.y * dr.y + ri.y * di.y);
+        const float2 wim = make_float2(rr.x * di.x - ri.x * dr.x, rr.y * di.y - ri.y * dr.y);
+        acc += (ure.x * dr.x + uim.x * di.x) + (ure.y * dr.y + uim.y * di.y);
+        *reinterpret_cast<float2*>(qd + k) = ure; *reinterpret_cast<float2*>(qd + h + k) = uim;
+        *reinterpret_cast<float2*>(qs + k) = wre; *reinterpret_cast<float2*>(qs + h + k) = wim;
+      }
+    } else if (VEC) {
+      for (int k = 4 * l; k < dim; k += 4 * GL) {
+        const float4 s = *reinterpret_cast<const float4*>(s_row + k), d = *reinterpret_cast<const float4*>(d_row + k);
+        float4 r = make_float4(0.f, 0.f, 0.f, 0.f), u, w;
+        if (a.model != MAR_MODEL_DOT) r = *reinterpret_cast<const float4*>(r_row + k);
+        if (a.model == MAR_MODEL_DISTMULT) {
+          u = make_float4(s.x * r.x, s.y * r.y, s.z * r.z, s.w * r.w);
+          w = make_float4(r.x * d.x, r.y * d.y, r.z * d.z, r.w * d.w);
+          acc += (u.x * d.x + u.y * d.y) + (u.z * d.z + u.w * d.w);
+        } else if (a.model == MAR_MODEL_DOT) {
+          u = s; w = d;
+          acc += (s.x * d.x + s.y * d.y) + (s.z * d.z + s.w * d.w);
+        } else {
+          u = make_float4(s.x + r.x, s.y + r.y, s.z + r.z, s.w + r.w);
+          w = make_float4(d.x - r.x, d.y - r.y, d.z - r.z, d.w - r.w);
+          const float4 df = make_float4(u.x - d.x, u.y - d.y, u.z - d.z, u.w - d.w);
+          acc += (df.x * df.x + df.y * df.y) + (df.z * df.z + df.w * df.w);
+          nd += (u.x * u.x + u.y * u.y) + (u.z * u.z + u.w * u.w);
+          ns += (w.x * w.x + w.y * w.y) + (w.z * w.z + w.w * w.w);
+        }
+        *reinterpret_cast<float4*>(qd + k) = u; *reinterpret_cast<float4*>(qs + k) = w;
+      }
+    } else if (a.model == MAR_MODEL_COMPLEX) {
       const int h = dim >> 1;
       for (int k = l; k < h; k += GL) {
         const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
@@ -112,10 +149,18 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
     const size_t krow = (size_t)side * a.C * a.N + cj;
     float* out = Km + krow * dk;
     float nn = 0.f;
-    for (int k = l; k < dk; k += GL) {
-      const float v = k < dim ? row[k] : 0.f;
-      nn += v * v;
-      out[k] = v;
+    if (VEC) {
+      for (int k = 4 * l; k < dim; k += 4 * GL) {
+        const float4 v = *reinterpret_cast<const float4*>(row + k);
+        nn += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+        *reinterpret_cast<float4*>(out + k) = v;
+      }
+    } else {
+      for (int k = l; k < dk; k += GL) {
+        const float v = k < dim ? row[k] : 0.f;
+        nn += v * v;
+        out[k] = v;
+      }
     }
     if (a.model == MAR_MODEL_TRANSE) {
       nn = group_sum<GL>(nn);
@@ -505,8 +550,9 @@ hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, 
   const int nbB = (b.n + gpb - 1) / gpb;
   const int nbC = (2 * b.cn + gpb - 1) / gpb;
   const dim3 grid(nbB + nbC), blk(256);
-#define PREP(GLV) hipLaunchKernelGGL(k_prep<GLV>, grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
-  if (GL == 16) PREP(16); else if (GL == 32) PREP(32); else PREP(64);
+#define PREP(GLV, V) hipLaunchKernelGGL((k_prep<GLV, V>), grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
+  if (a.dim % 4 == 0) { if (GL == 16) PREP(16, true); else if (GL == 32) PREP(32, true); else PREP(64, true); }
+  else { if (GL == 16) PREP(16, false); else if (GL == 32) PREP(32, false); else PREP(64, false); }
 #undef PREP
   return hipGetLastError();
 }
