@@ -27,3 +27,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_library():
+    """Tests load the in-tree shared library; it is built here only if it is not there yet."""
+    from paper_2101_08358_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2101_08358_amd import build
+        build.build()
+    yield
