@@ -274,11 +274,37 @@ k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, c
 
 // ------------------------------------------------------------ filtered evaluation -----
 // Score f(s, r, d) of one triple by one lane group, in the operation order of the positive score above.
-template <int GL>
+template <int GL, bool VEC>
 __device__ __forceinline__ float group_score(int model, int dim, const float* __restrict__ s_row,
                                              const float* __restrict__ r_row, const float* __restrict__ d_row, int l) {
   float acc = 0.f;
-  if (model == MAR_MODEL_COMPLEX) {
+  if (VEC && model == MAR_MODEL_COMPLEX) {
+    const int h = dim >> 1;
+    for (int k = 2 * l; k < h; k += 2 * GL) {
+      const float2 sr = *reinterpret_cast<const float2*>(s_row + k), si = *reinterpret_cast<const float2*>(s_row + h + k);
+      const float2 rr = *reinterpret_cast<const float2*>(r_row + k), ri = *reinterpret_cast<const float2*>(r_row + h + k);
+      const float2 dr = *reinterpret_cast<const float2*>(d_row + k), di = *reinterpret_cast<const float2*>(d_row + h + k);
+      const float2 ure = make_float2(sr.x * rr.x - si.x * ri.x, sr.y * rr.y - si.y * ri.y);
+      const float2 uim = make_float2(sr.x * ri.x + si.x * rr.x, sr.y * ri.y + si.y * rr.y);
+      acc += (ure.x * dr.x + uim.x * di.x) + (ure.y * dr.y + uim.y * di.y);
+    }
+  } else if (VEC) {
+    for (int k = 4 * l; k < dim; k += 4 * GL) {
+      const float4 s = *reinterpret_cast<const float4*>(s_row + k), d = *reinterpret_cast<const float4*>(d_row + k);
+      float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (model != MAR_MODEL_DOT) r = *reinterpret_cast<const float4*>(r_row + k);
+      if (model == MAR_MODEL_DISTMULT) {
+        const float4 u = make_float4(s.x * r.x, s.y * r.y, s.z * r.z, s.w * r.w);
+        acc += (u.x * d.x + u.y * d.y) + (u.z * d.z + u.w * d.w);
+      } else if (model == MAR_MODEL_DOT) {
+        acc += (s.x * d.x + s.y * d.y) + (s.z * d.z + s.w * d.w);
+      } else {
+        const float4 u = make_float4(s.x + r.x, s.y + r.y, s.z + r.z, s.w + r.w);
+        const float4 df = make_float4(u.x - d.x, u.y - d.y, u.z - d.z, u.w - d.w);
+        acc += (df.x * df.x + df.y * df.y) + (df.z * df.z + df.w * df.w);
+      }
+    }
+  } else if (model == MAR_MODEL_COMPLEX) {
     const int h = dim >> 1;
     for (int k = l; k < h; k += GL) {
       const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
@@ -299,7 +325,7 @@ __device__ __forceinline__ float group_score(int model, int dim, const float* __
 
 // One lane group per (edge, corrupted side): takes the listed true candidates that outscore the edge
 // out of its rank.
-template <int GL>
+template <int GL, bool VEC>
 __global__ void __launch_bounds__(256)
 k_filter(RowArgs a, const int64_t* __restrict__ dst_off, const int32_t* __restrict__ dst_ids,
          const int64_t* __restrict__ src_off, const int32_t* __restrict__ src_ids, const float* __restrict__ pos,
@@ -320,8 +346,8 @@ k_filter(RowArgs a, const int64_t* __restrict__ dst_off, const int32_t* __restri
   int better = 0;
   for (int64_t k = off[e]; k < off[e + 1]; ++k) {
     const float* c_row = a.node_emb + (size_t)ids[k] * dim;
-    const float f = side == MAR_SIDE_DST ? group_score<GL>(a.model, dim, s_row, r_row, c_row, l)
-                                         : group_score<GL>(a.model, dim, c_row, r_row, d_row, l);
+    const float f = side == MAR_SIDE_DST ? group_score<GL, VEC>(a.model, dim, s_row, r_row, c_row, l)
+                                         : group_score<GL, VEC>(a.model, dim, c_row, r_row, d_row, l);
     better += f > p ? 1 : 0;
   }
   if (l == 0 && better) (side == MAR_SIDE_DST ? rank_dst : rank_src)[e] -= better;
@@ -563,8 +589,9 @@ hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t*
   RowArgs a = row_args(c, b);
   const int GL = lane_group(a.dk), gpb = 256 / GL;
   const dim3 grid((2 * b.n + gpb - 1) / gpb), blk(256);
-#define FILT(GLV) hipLaunchKernelGGL(k_filter<GLV>, grid, blk, 0, st, a, dst_off, dst_ids, src_off, src_ids, pos, rank_dst, rank_src)
-  if (GL == 16) FILT(16); else if (GL == 32) FILT(32); else FILT(64);
+#define FILT(GLV, V) hipLaunchKernelGGL((k_filter<GLV, V>), grid, blk, 0, st, a, dst_off, dst_ids, src_off, src_ids, pos, rank_dst, rank_src)
+  if (a.dim % 4 == 0) { if (GL == 16) FILT(16, true); else if (GL == 32) FILT(32, true); else FILT(64, true); }
+  else { if (GL == 16) FILT(16, false); else if (GL == 32) FILT(32, false); else FILT(64, false); }
 #undef FILT
   return hipGetLastError();
 }
