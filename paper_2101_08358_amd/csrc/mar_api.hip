@@ -62,7 +62,6 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   if (!mar_flash_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the contraction kernels", d->dk);
   // Small batches give too few (chunk-side, 64-row stripe) workgroups to fill 256 CUs: let several
   // workgroups share a stripe, each streaming a slice of the other matrix.
-  d->ty = mar_flash_tile_rows(d->dk);
   long target1 = 640, target2 = 640;
   if (const char* e = getenv("MAR_FLASH_TARGET_WGS")) { const long v = atol(e); if (v > 0) target1 = target2 = v; }
   if (const char* e = getenv("MAR_FLASH_TARGET_WGS2")) { const long v = atol(e); if (v > 0) target2 = v; }
@@ -70,7 +69,8 @@ static int check_config(const mar_config* cfg, MarDims* d) {
     const long target = pass == 1 ? target1 : target2;
     const int sr = mar_flash_stripe_rows(d->dk, pass);
     const long wgs = 2L * d->C * ((n_x + sr - 1) / sr);
-    const int ntiles = (n_y + d->ty - 1) / d->ty;
+    const int ty = mar_flash_tile_rows(d->dk, pass);
+    const int ntiles = (n_y + ty - 1) / ty;
     long want = (target + wgs - 1) / wgs;
     if (want > 8) want = 8;
     if (want > ntiles) want = ntiles;

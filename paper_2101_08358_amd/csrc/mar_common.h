@@ -49,7 +49,6 @@ struct MarDims {
   int64_t n_pos_max;               // roles*B + 2CN*sy2: gradient rows per step
   int32_t sy1, sy2;                // how many workgroups share the streamed rows of one stripe (pass 1 / 2)
   int32_t tps1, tps2;              // streamed tiles per workgroup
-  int32_t ty;                      // rows per streamed tile
   int64_t u_max;                   // min(num_nodes + num_rels, n_occ_max)
   int64_t nwords;                  // words of the touched-id map
   int32_t ipw_log2;                // ids per word: 5 = one bit per id (atomic marks), 2 = one byte per id (plain stores)
@@ -107,5 +106,5 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
 hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_t* ks, int num_k, double* out, hipStream_t st);
 int mar_flash_supported(int dk);
-int mar_flash_tile_rows(int dk);
+int mar_flash_tile_rows(int dk, int pass);
 int mar_flash_stripe_rows(int dk, int pass);

@@ -468,7 +468,7 @@ k_flash(FlashArgs a) {
 // one tile ahead: as soon as a block's scores are consumed the same registers are refilled with
 // the next tile's.  Only the second product runs on the matrix cores.
 template <int NK, int NC, int VT, int TY, int XB, int L2>
-__global__ void __launch_bounds__(256, (NK * XB <= 64 ? 2 : 1))
+__global__ void __launch_bounds__(256, 2)
 k_flash_bwd(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
@@ -670,7 +670,9 @@ k_flash_bwd(FlashArgs a) {
 
 // ------------------------------------------------------------------- launchers -----
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
-int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of the instantiation that serves dk
+// Streamed rows per tile of the instantiation that serves dk: pass 1 / 3, and pass 2 (whose widest
+// instantiation takes 16-row tiles so that two workgroups fit in a CU's registers).
+int mar_flash_tile_rows(int dk, int pass) { return dk / 4 <= 32 ? 64 : (pass == 2 && dk / 4 > 64 ? 16 : 32); }
 
 // Stationary rows per workgroup (64 per x-block of the instantiation that serves dk): pass 1 / 3 and pass 2.
 #ifndef MAR_BWD_XB
@@ -678,13 +680,13 @@ int mar_flash_tile_rows(int dk) { return dk / 4 <= 32 ? 64 : 32; }   // TY of th
 #endif
 int mar_flash_stripe_rows(int dk, int pass) { return pass == 2 && dk / 4 <= 32 ? 64 * MAR_BWD_XB : 64; }
 
-template <int NK, int NC, int VT, int TY, int XB, int BXB>
+template <int NK, int NC, int VT, int TY, int XB, int BXB, int BTY>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
 #define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, VT, TY, XB, P, L>), grid, dim3(256), 0, st, a)
   if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
   else if (pass == 2) {
-    if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, TY, BXB, 1>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, TY, BXB, 0>), grid, dim3(256), 0, st, a);
+    if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, BTY, BXB, 1>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, BTY, BXB, 0>), grid, dim3(256), 0, st, a);
   }
   else { if (l2) FL(3, 1); else FL(3, 0); }
 #undef FL
@@ -713,9 +715,9 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
-  if (nk <= 13) return launch_sized<13, 3, 1, 64, 1, MAR_BWD_XB>(a, pass, l2, grid, st);
-  if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, MAR_BWD_XB>(a, pass, l2, grid, st);
-  if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, MAR_BWD_XB>(a, pass, l2, grid, st);
-  if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 1>(a, pass, l2, grid, st);
-  return launch_sized<100, 25, 0, 32, 1, 1>(a, pass, l2, grid, st);
+  if (nk <= 13) return launch_sized<13, 3, 1, 64, 1, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
+  if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 1, 32>(a, pass, l2, grid, st);
+  return launch_sized<100, 25, 0, 32, 1, 1, 16>(a, pass, l2, grid, st);
 }
