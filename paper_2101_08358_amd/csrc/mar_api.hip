@@ -31,6 +31,8 @@ static int hip_fail(hipError_t e, const char* what) {
 }
 
 // ------------------------------------------------------------------ configuration -----
+#define MAR_FLASH_TARGET_WGS 640
+
 static int check_config(const mar_config* cfg, MarDims* d) {
   if (!cfg) return fail(MAR_EINVAL, "config is NULL");
   if (cfg->num_nodes < 1 || cfg->num_rels < 1) return fail(MAR_EINVAL, "num_nodes and num_rels must be >= 1");
@@ -61,12 +63,11 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   d->nwords = (ids + (1 << d->ipw_log2) - 1) >> d->ipw_log2;
   if (!mar_flash_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the contraction kernels", d->dk);
   // Small batches give too few (chunk-side, 64-row stripe) workgroups to fill 256 CUs: let several
-  // workgroups share a stripe, each streaming a slice of the other matrix.
-  long target1 = 640, target2 = 640;
-  if (const char* e = getenv("MAR_FLASH_TARGET_WGS")) { const long v = atol(e); if (v > 0) target1 = target2 = v; }
-  if (const char* e = getenv("MAR_FLASH_TARGET_WGS2")) { const long v = atol(e); if (v > 0) target2 = v; }
+  // workgroups share a stripe, each streaming a slice of the other matrix, until a pass has at least
+  // MAR_FLASH_TARGET_WGS workgroups (measured best for a 10,000-edge batch; the 50,000-edge shapes have
+  // enough stripes and are not split).
   auto split = [&](int pass, int n_x, int n_y, int32_t* sy, int32_t* tps) {
-    const long target = pass == 1 ? target1 : target2;
+    const long target = MAR_FLASH_TARGET_WGS;
     const int sr = mar_flash_stripe_rows(d->dk, pass);
     const long wgs = 2L * d->C * ((n_x + sr - 1) / sr);
     const int ty = mar_flash_tile_rows(d->dk, pass);
@@ -81,6 +82,11 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   split(1, d->S, d->N, &d->sy1, &d->tps1);
   split(2, d->N, d->S, &d->sy2, &d->tps2);
   d->n_pos_max = roles * (int64_t)cfg->batch_size + 2 * cn * d->sy2;
+  // Sort keys are ranks below u_max: as few passes as digits of at most MAR_SORT_MAX_BITS bits allow.
+  int nbits = 1;
+  while (((int64_t)1 << nbits) < d->u_max) ++nbits;
+  d->sort_passes = (nbits + MAR_SORT_MAX_BITS - 1) / MAR_SORT_MAX_BITS;
+  d->sort_bits = (nbits + d->sort_passes - 1) / d->sort_passes;
   return MAR_OK;
 }
 
@@ -92,22 +98,27 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
     off += (bytes + 255) & ~(size_t)255;
     return p;
   };
-  const size_t n_occ = (size_t)d.n_occ_max, n_pos = (size_t)d.n_pos_max, u1 = (size_t)d.u_max + 1;
+  const size_t n_pos = (size_t)d.n_pos_max, u1 = (size_t)d.u_max + 1;
   const size_t B = d.B, CN = (size_t)d.C * d.N, dk = d.dk;
   const size_t scan_elems = (size_t)d.nwords > u1 ? (size_t)d.nwords : u1;
-  const size_t tasks = (n_pos + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
+  const size_t blocks = (n_pos + MAR_REDUCE_BLOCK - 1) / MAR_REDUCE_BLOCK;
+  const size_t tiles = (n_pos + MAR_SORT_TILE - 1) / MAR_SORT_TILE;
   MarLayout l;
   l.scalars = (int32_t*)take(16 * 4);
   l.bitmap = (uint32_t*)take((size_t)d.nwords * 4);
   l.word_prefix = (uint32_t*)take((size_t)d.nwords * 4);
   l.bsum = (uint32_t*)take((scan_elems / 4096 + 2) * 4);
   l.uniq = (int32_t*)take(u1 * 4);
-  l.count = (uint32_t*)take(u1 * 4);
   l.seg_off = (uint32_t*)take((u1 + 1) * 4);
-  l.inv = (int32_t*)take(n_occ * 4);
-  l.slot = (int32_t*)take(n_occ * 4);
+  l.keys0 = (uint32_t*)take(n_pos * 4);
+  for (int i = 0; i < 2; ++i) {
+    l.kbuf[i] = (uint32_t*)take(d.sort_passes > i + 1 ? n_pos * 4 : 0);
+    l.vbuf[i] = (int32_t*)take(d.sort_passes > i + 1 ? n_pos * 4 : 0);
+  }
+  l.hist = (uint32_t*)take((tiles << d.sort_bits) * 4);
   l.perm = (int32_t*)take(n_pos * 4);
   l.rank_sorted = (int32_t*)take(n_pos * 4);
+  l.owners = (int32_t*)take(blocks * 4);
   l.Q = (float*)take(2 * B * dk * 4);
   l.Km = (float*)take(2 * CN * dk * 4);
   l.qq = (float*)take(2 * B * 4);
@@ -118,8 +129,7 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.ml = (float*)take((size_t)d.sy1 * 2 * B * 2 * 4);
   l.T = (float*)take(2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)((d.N + 127) & ~127) * 4);
   l.G = (float*)take(n_pos * dk * 4);
-  l.Gu = (float*)take(u1 * dk * 4);
-  l.carry = (float*)take(tasks * 2 * dk * 4);
+  l.carry = (float*)take(blocks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);
   if (L) *L = l;
   return off;
@@ -233,7 +243,6 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   HIP_TRY(hipStreamWaitEvent(ax, c->ev_fork, 0), "fork");
   MARK(0, 0, ax);
   HIP_TRY(mar_launch_index(c, b, ax), "index kernels");
-  HIP_TRY(mar_launch_positions(c, b, ax), "position kernel");
   if (dbg) HIP_TRY(mar_launch_debug_copy(c, b, dbg, ax), "debug copy");
   MARK(0, 1, ax);
   HIP_TRY(hipEventRecord(c->ev_index, ax), "join");

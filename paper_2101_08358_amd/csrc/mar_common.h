@@ -12,18 +12,20 @@
 
 // Workspace carve-up (device pointers).
 struct MarLayout {
-  int32_t*  scalars;      // [16]: 0 = unique rows (nodes + relations), 1 = unique nodes
+  int32_t*  scalars;      // [16]: 0 = unique rows (nodes + relations), 1 = unique nodes, 2 = number of entries in `owners`
   uint32_t* bitmap;       // touched-id map over unified ids (node id, or num_nodes + relation id): one bit or
                           // one byte per id, see ipw_log2
   uint32_t* word_prefix;  // marked ids before each word of the map
   uint32_t* bsum;         // scan scratch (block sums)
   int32_t*  uniq;         // ascending unified ids of the touched rows
-  uint32_t* count;        // occurrences per unique row (u_max + 1, last stays 0)
-  uint32_t* seg_off;      // exclusive scan of count: start of each row's segment
-  int32_t*  inv;          // occurrence -> rank of its row among the unique rows
-  int32_t*  slot;         // occurrence -> index inside its row's segment
+  uint32_t* seg_off;      // [unique rows + 1] first position of each row's segment in the row-sorted order
+  uint32_t* keys0;        // [n_pos] gradient row -> rank of its table row among the unique rows (sort keys)
+  uint32_t* kbuf[2];      // [n_pos] each: keys between two passes of the radix sort
+  int32_t*  vbuf[2];      // [n_pos] each: gradient row numbers between two passes
+  uint32_t* hist;         // [sort tiles][bins] digit counts of the current pass
   int32_t*  perm;         // position in row-sorted order -> gradient row
   int32_t*  rank_sorted;  // position -> rank
+  int32_t*  owners;       // [reduce blocks] workgroups of the reduce in which a segment begins that continues into later ones
   float*    Q;            // [2][batch][dk] edge-side operands (side-major)
   float*    Km;           // [2][chunks][N][dk] gathered negative rows
   float*    qq;           // [2][batch] squared norms of Q rows (TransE)
@@ -35,8 +37,7 @@ struct MarLayout {
   float*    T;            // [2*chunks][S rounded up to 64][N rounded up to 128] raw score block, pass 1 -> pass 2
   float*    G;            // [roles*n + 2*cn*sy2][dk] gradient rows: edge-side occurrence k < roles*n at row k, part i
                           // of negative occurrence k at row roles*n + (k - roles*n)*sy2 + i
-  float*    Gu;           // [u_max][dk] summed gradient per unique row
-  float*    carry;        // [tasks][2][dk] partial sums of segments that cross task borders
+  float*    carry;        // [reduce blocks][2][dk] partial sums of segments that cross workgroup borders
   float*    loss_part;    // per-block partial loss sums
 };
 
@@ -52,6 +53,7 @@ struct MarDims {
   int64_t u_max;                   // min(num_nodes + num_rels, n_occ_max)
   int64_t nwords;                  // words of the touched-id map
   int32_t ipw_log2;                // ids per word: 5 = one bit per id (atomic marks), 2 = one byte per id (plain stores)
+  int32_t sort_passes, sort_bits;  // radix sort of the gradient rows by rank: passes, bits per pass
 };
 
 #define MAR_MAX_PROFILE_STEPS 4096
@@ -74,8 +76,15 @@ struct mar_ctx {
 
 void mar_set_error(const char* fmt, ...);
 
-// Sizes of the reduce kernel's work split.
-#define MAR_TASK_ROWS 64           // occurrence rows per wave task
+// Radix sort of the gradient rows: elements per workgroup tile and the widest digit.
+#define MAR_SORT_TILE 4096
+#define MAR_SORT_MAX_BITS 10
+
+// Positions of the row-sorted order per workgroup of the reduce.
+#define MAR_REDUCE_BLOCK 256
+
+// Lanes that move one table row as float4s.
+static inline int mar_lane_group(int dk) { return dk <= 64 ? 16 : (dk <= 128 ? 32 : 64); }
 
 // ---- launchers (each returns a hipError_t from the launch) --------------------------
 hipError_t mar_launch_init(const mar_ctx* c, int fill, hipStream_t st);
@@ -94,7 +103,6 @@ struct MarBatch {
 };
 
 hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st);
-hipError_t mar_launch_positions(const mar_ctx* c, const MarBatch& b, hipStream_t st);
 hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, hipStream_t st);
 hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32_t* rank_dst, int32_t* rank_src,
                             hipStream_t st);

@@ -3,9 +3,10 @@
 //
 // The unique set comes from a bitmap over "unified ids" (a node id, or num_nodes + relation
 // id): mark bits, pop-count scan -> rank of every touched row and the ascending id list.
-// Occurrences are then counted per rank and an exclusive scan gives each row a contiguous
-// segment of positions; gradient rows are later written straight into that order so the
-// per-row reduction streams contiguous memory.
+// The gradient rows (one per occurrence of a row in the batch) are then put in row-sorted order by
+// a stable radix sort on the rank, so that every table row owns a contiguous segment of positions
+// whose order -- the occurrence order -- is the same in every run: the per-row sums that follow
+// are bit-reproducible.
 #include "mar_common.h"
 
 // ---------------------------------------------------------------- Philox4x32-10 -----
@@ -141,13 +142,12 @@ __device__ __forceinline__ uint32_t agg_insert(BlockAgg& t, int key, uint32_t mu
   return atomicAdd(&t.cnt[h], mult);
 }
 
-// Marks the touched-id map and zeroes the per-rank counters for this step.
+// Marks the touched-id map.
 __global__ void __launch_bounds__(AGG_THREADS)
-k_mark(OccArgs a, int64_t n_occ, int L, uint32_t* __restrict__ bitmap, uint32_t* __restrict__ count, int64_t n_count) {
+k_mark(OccArgs a, int64_t n_occ, int L, uint32_t* __restrict__ bitmap) {
   __shared__ BlockAgg tab;
   const int64_t stride = (int64_t)gridDim.x * AGG_THREADS;
   const int64_t t0 = (int64_t)blockIdx.x * AGG_THREADS + threadIdx.x;
-  for (int64_t i = t0; i < n_count; i += stride) count[i] = 0u;
   if (L == 2) {
     unsigned char* bytes = reinterpret_cast<unsigned char*>(bitmap);
     for (int64_t k = t0; k < n_occ; k += stride) bytes[(uint32_t)occ_unified_id(a, k)] = 1;
@@ -297,39 +297,155 @@ static hipError_t scan_u32(const uint32_t* in, int64_t n, int L, uint32_t* out, 
   return hipGetLastError();
 }
 
-// -------------------------------------------------------- rank + slot per occurrence -----
-// Rank of every occurrence's row and its slot inside the row's segment.  Equal ranks inside a
-// block are grouped in LDS and issue one global atomic together (a hot row is hit by a large
-// share of the occurrences).  An occurrence of a negative takes neg_mult consecutive slots (one
-// gradient row per workgroup that shares its stripe).
-__global__ void __launch_bounds__(AGG_THREADS)
-k_count(OccArgs a, int64_t n_occ, int neg_mult, int L, const uint32_t* __restrict__ bitmap,
-        const uint32_t* __restrict__ word_prefix, uint32_t* __restrict__ count, int32_t* __restrict__ inv,
-        int32_t* __restrict__ slot) {
-  __shared__ BlockAgg tab;
-  const int64_t stride = (int64_t)gridDim.x * AGG_THREADS;
-  const int64_t rounds = (n_occ + stride - 1) / stride;          // same trip count for every thread
-  const int64_t n_pos_occ = a.roles * (int64_t)a.n;
-  for (int64_t it = 0; it < rounds; ++it) {
-    agg_clear(tab);
-    __syncthreads();
-    const int64_t k = it * stride + (int64_t)blockIdx.x * AGG_THREADS + threadIdx.x;
-    const bool active = k < n_occ;
-    int rank = 0, h = 0;
-    uint32_t local = 0;
-    if (active) {
-      const uint32_t id = (uint32_t)occ_unified_id(a, k);
-      const uint32_t w = id >> L;
-      rank = (int)(word_prefix[w] + __popc(bitmap[w] & ((1u << map_bitpos(id, L)) - 1u)));
-      local = agg_insert(tab, rank, k < n_pos_occ ? 1u : (uint32_t)neg_mult, &h);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < AGG_SLOTS; i += AGG_THREADS)
-      if (tab.key[i] >= 0) tab.base[i] = atomicAdd(&count[tab.key[i]], tab.cnt[i]);
-    __syncthreads();
-    if (active) { inv[k] = rank; slot[k] = (int32_t)(tab.base[h] + local); }
-    __syncthreads();
+// ------------------------------------------------ row-sorted order of the gradient rows -----
+// Gradient row gr belongs to occurrence k = gr (edge side, gr < roles*n) or to part (gr - roles*n) % sy2
+// of negative occurrence roles*n + (gr - roles*n) / sy2; its sort key is the rank of the occurrence's
+// table row among the unique rows.  A least-significant-digit radix sort with digits of `bits` bits puts
+// the gradient rows in key order; every pass is stable, so equal keys stay in gradient-row order.
+// One pass = k_sort_hist (digit counts per tile of MAR_SORT_TILE elements) + k_sort_scatter (each tile
+// derives its digits' global offsets from the counts of all tiles and scatters its elements).
+
+// Lanes of the wave that hold the same digit as this lane (valid lanes only).
+__device__ __forceinline__ uint64_t match_digit(uint32_t digit, int bits, bool valid) {
+  uint64_t mask = __ballot(valid);
+  for (int b = 0; b < bits; ++b) {
+    const bool bit = (digit >> b) & 1u;
+    const uint64_t bal = __ballot(bit);
+    mask &= bit ? bal : ~bal;
   }
+  return mask;
+}
+
+// FIRST: computes the keys from the touched-id map and its prefix sums and stores them.
+template <int FIRST>
+__global__ void __launch_bounds__(256)
+k_sort_hist(OccArgs a, int64_t n_pos, int sy2, int L, const uint32_t* __restrict__ bitmap,
+            const uint32_t* __restrict__ word_prefix, const uint32_t* __restrict__ keys_in,
+            uint32_t* __restrict__ keys_out, int shift, int bits, uint32_t* __restrict__ hist) {
+  __shared__ uint32_t h[1 << MAR_SORT_MAX_BITS];
+  const int bins = 1 << bits;
+  const int lane = threadIdx.x & 63;
+  for (int i = threadIdx.x; i < bins; i += 256) h[i] = 0u;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * MAR_SORT_TILE;
+  const int64_t n3 = a.roles * (int64_t)a.n;
+#pragma unroll 4
+  for (int j = 0; j < MAR_SORT_TILE / 256; ++j) {
+    const int64_t gr = base + j * 256 + threadIdx.x;
+    const bool valid = gr < n_pos;
+    uint32_t key = 0u;
+    if (valid) {
+      if (FIRST) {
+        const int64_t k = gr < n3 ? gr : n3 + (gr - n3) / sy2;
+        const uint32_t id = (uint32_t)occ_unified_id(a, k);
+        const uint32_t w = id >> L;
+        key = word_prefix[w] + __popc(bitmap[w] & ((1u << map_bitpos(id, L)) - 1u));
+        keys_out[gr] = key;
+      } else {
+        key = keys_in[gr];
+      }
+    }
+    // one LDS atomic per distinct digit of the wave (a hot row fills whole waves with one key)
+    const uint32_t digit = (key >> shift) & (uint32_t)(bins - 1);
+    const uint64_t same = match_digit(digit, bits, valid);
+    if (valid && (same & ((1ull << lane) - 1ull)) == 0ull) atomicAdd(&h[digit], (uint32_t)__popcll(same));
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < bins; i += 256) hist[(size_t)blockIdx.x * bins + i] = h[i];
+}
+
+// Scatters the tile's elements to their places in digit order.  Global place of an element =
+// (elements with a smaller digit anywhere) + (same digit in earlier tiles) + (same digit earlier in this
+// tile).  Inside the tile wave w owns a contiguous quarter and walks it 64 consecutive elements at a time,
+// so "earlier in this tile" = same digit in earlier waves + earlier rounds of this wave + lower lanes.
+// vals_in == NULL: the values are the element indices (first pass).
+__global__ void __launch_bounds__(256)
+k_sort_scatter(const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
+               uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out, const uint32_t* __restrict__ hist,
+               int64_t n, int shift, int bits, int ntiles) {
+  constexpr int ITEMS = MAR_SORT_TILE / 256;
+  __shared__ uint32_t wcnt[4][1 << MAR_SORT_MAX_BITS];      // per wave: elements per digit, then their exclusive prefix over waves
+  __shared__ uint32_t gbase[1 << MAR_SORT_MAX_BITS];        // global place of the tile's first element of each digit
+  const int bins = 1 << bits;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < 4 * bins; i += 256) wcnt[i / bins][i % bins] = 0u;
+
+  // keys of this wave's quarter, round r = 64 consecutive elements
+  const int64_t q0 = (int64_t)blockIdx.x * MAR_SORT_TILE + (int64_t)wave * (MAR_SORT_TILE / 4) + lane;
+  uint32_t key[ITEMS];
+#pragma unroll
+  for (int r = 0; r < ITEMS; ++r) key[r] = q0 + 64 * r < n ? keys_in[q0 + 64 * r] : 0u;
+
+  // digit offsets: thread t owns digits [t*per, (t+1)*per)
+  const int per = (bins + 255) / 256;
+  uint32_t before[4] = {0u, 0u, 0u, 0u}, total[4] = {0u, 0u, 0u, 0u};
+  const int d0 = threadIdx.x * per;
+  for (int b = 0; b < ntiles; ++b) {
+    const uint32_t* hrow = hist + (size_t)b * bins;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j < per && d0 + j < bins) {
+        const uint32_t v = hrow[d0 + j];
+        total[j] += v;
+        if (b < (int)blockIdx.x) before[j] += v;
+      }
+    }
+  }
+  uint32_t tot_all;
+  uint32_t run = block_exclusive_scan<256>((total[0] + total[1]) + (total[2] + total[3]), &tot_all);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (j < per && d0 + j < bins) { gbase[d0 + j] = run + before[j]; run += total[j]; }
+  }
+  __syncthreads();                                          // counters cleared, gbase written
+
+  uint32_t loc[ITEMS];
+#pragma unroll
+  for (int r = 0; r < ITEMS; ++r) {
+    const bool valid = q0 + 64 * r < n;
+    const uint32_t digit = (key[r] >> shift) & (uint32_t)(bins - 1);
+    const uint64_t same = match_digit(digit, bits, valid);
+    const uint32_t lower = (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+    loc[r] = 0u;
+    if (valid) {
+      // every lane of a group reads the wave's counter before the group's first lane advances it: one wave
+      // executes both accesses in program order
+      const uint32_t old = wcnt[wave][digit];
+      loc[r] = old + lower;
+      if (lower == 0u) wcnt[wave][digit] = old + (uint32_t)__popcll(same);
+    }
+  }
+  __syncthreads();
+  for (int d = threadIdx.x; d < bins; d += 256) {
+    const uint32_t c0 = wcnt[0][d], c1 = wcnt[1][d], c2 = wcnt[2][d];
+    wcnt[0][d] = 0u; wcnt[1][d] = c0; wcnt[2][d] = c0 + c1; wcnt[3][d] = c0 + c1 + c2;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < ITEMS; ++r) {
+    const int64_t idx = q0 + 64 * r;
+    if (idx < n) {
+      const uint32_t digit = (key[r] >> shift) & (uint32_t)(bins - 1);
+      const uint32_t p = gbase[digit] + wcnt[wave][digit] + loc[r];
+      keys_out[p] = key[r];
+      vals_out[p] = vals_in ? vals_in[idx] : (int32_t)idx;
+    }
+  }
+}
+
+// Segment starts of the row-sorted order (every unique row has at least one position), the end sentinel,
+// the reset of the owner list's counter, and the reset of the touched-id map for the next step.
+__global__ void __launch_bounds__(256)
+k_segments(OccArgs a, int64_t n_occ, int64_t n_pos, int L, const int32_t* __restrict__ rank_sorted,
+           uint32_t* __restrict__ seg_off, uint32_t* __restrict__ bitmap, int32_t* __restrict__ scalars) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i == 0) scalars[2] = 0;
+  if (i < n_pos) {
+    const int r = rank_sorted[i];
+    if (i == 0 || rank_sorted[i - 1] != r) seg_off[r] = (uint32_t)i;
+    if (i == n_pos - 1) seg_off[r + 1] = (uint32_t)n_pos;
+  }
+  if (i < n_occ) bitmap[(uint32_t)occ_unified_id(a, i) >> L] = 0u;
 }
 
 // Copies the unique id lists into the caller's debug buffers.
@@ -435,15 +551,33 @@ hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st)
   const MarDims& d = c->dm;
   const MarLayout& L = c->L;
   OccArgs a{b.src, b.rel, b.dst, b.neg_src, b.neg_dst, b.n, b.cn, (int32_t)d.num_nodes, d.roles};
-  const int64_t n_count = d.u_max + 1;
-  const int64_t work = b.n_occ > n_count ? b.n_occ : n_count;
-  hipLaunchKernelGGL(k_mark, dim3(grid_for(work, AGG_THREADS, 2048)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.ipw_log2,
-                     L.bitmap, L.count, n_count);
+  hipLaunchKernelGGL(k_mark, dim3(grid_for(b.n_occ, AGG_THREADS, 2048)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.ipw_log2,
+                     L.bitmap);
   hipError_t e = scan_u32<1>(L.bitmap, d.nwords, d.ipw_log2, L.word_prefix, L.bsum, L.uniq, L.scalars, d.num_nodes, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_count, dim3(grid_for(b.n_occ, AGG_THREADS, 2048)), dim3(AGG_THREADS), 0, st, a, b.n_occ, (int)d.sy2,
-                     (int)d.ipw_log2, L.bitmap, L.word_prefix, L.count, L.inv, L.slot);
-  return scan_u32<0>(L.count, n_count, 5, L.seg_off, L.bsum, nullptr, nullptr, -1, st);
+  // stable radix sort of the gradient rows by rank; the last pass writes rank_sorted / perm
+  const int ntiles = (int)((b.n_pos + MAR_SORT_TILE - 1) / MAR_SORT_TILE);
+  const uint32_t* kin = L.keys0;
+  const int32_t* vin = nullptr;
+  for (int p = 0; p < d.sort_passes; ++p) {
+    const bool last = p == d.sort_passes - 1;
+    uint32_t* kout = last ? (uint32_t*)L.rank_sorted : L.kbuf[p & 1];
+    int32_t* vout = last ? L.perm : L.vbuf[p & 1];
+    const int shift = p * d.sort_bits;
+    if (p == 0)
+      hipLaunchKernelGGL(k_sort_hist<1>, dim3(ntiles), dim3(256), 0, st, a, b.n_pos, (int)d.sy2, (int)d.ipw_log2, L.bitmap,
+                         L.word_prefix, nullptr, L.keys0, shift, (int)d.sort_bits, L.hist);
+    else
+      hipLaunchKernelGGL(k_sort_hist<0>, dim3(ntiles), dim3(256), 0, st, a, b.n_pos, (int)d.sy2, (int)d.ipw_log2, L.bitmap,
+                         L.word_prefix, kin, nullptr, shift, (int)d.sort_bits, L.hist);
+    hipLaunchKernelGGL(k_sort_scatter, dim3(ntiles), dim3(256), 0, st, kin, vin, kout, vout, L.hist, b.n_pos, shift,
+                       (int)d.sort_bits, ntiles);
+    kin = kout; vin = vout;
+  }
+  const int64_t work = b.n_pos > b.n_occ ? b.n_pos : b.n_occ;
+  hipLaunchKernelGGL(k_segments, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, st, a, b.n_occ, b.n_pos, (int)d.ipw_log2,
+                     L.rank_sorted, L.seg_off, L.bitmap, L.scalars);
+  return hipGetLastError();
 }
 
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st) {

@@ -20,36 +20,6 @@ template <int GL> __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
-// -------------------------------------------------------------------- positions -----
-// Row-sorted order of the gradient rows: position -> gradient row (a negative owns sy2
-// consecutive positions, one per workgroup sharing its stripe in the second contraction pass)
-// and position -> rank; also clears the occurrence's word of the touched-id map for the next step.
-__global__ void __launch_bounds__(256)
-k_positions(RowArgs a, int ipw_log2, const uint32_t* __restrict__ seg_off, const int32_t* __restrict__ inv,
-            const int32_t* __restrict__ slot, int32_t* __restrict__ perm, int32_t* __restrict__ rank_sorted,
-            uint32_t* __restrict__ bitmap) {
-  const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (k >= a.n_occ) return;
-  const int r = inv[k];
-  const int p = (int)seg_off[r] + slot[k];
-  // Gradient rows are written by their producers at fixed places (edge-side occurrence k < roles*n: row k;
-  // the i-th part of negative occurrence k: row roles*n + (k - roles*n) * sy2 + i); perm lists them in
-  // row-sorted order.
-  const int64_t n3 = a.roles * (int64_t)a.n;
-  if (k < n3) {
-    perm[p] = (int32_t)k; rank_sorted[p] = r;
-  } else {
-    for (int i = 0; i < a.sy2; ++i) { perm[p + i] = (int32_t)(n3 + (k - n3) * a.sy2 + i); rank_sorted[p + i] = r; }
-  }
-  // unified id of the occurrence (same numbering as the index kernels)
-  int64_t kk2 = k; uint32_t id;
-  if (kk2 < a.n) id = a.src[kk2];
-  else if (kk2 < 2 * (int64_t)a.n) id = a.dst[kk2 - a.n];
-  else if (kk2 < n3) id = a.num_nodes + a.rel[kk2 - 2 * (int64_t)a.n];
-  else { kk2 -= n3; id = kk2 < a.cn ? a.neg_dst[kk2] : a.neg_src[kk2 - a.cn]; }
-  bitmap[id >> ipw_log2] = 0u;
-}
-
 // ---------------------------------------------------------------------- gather -----
 // Edge blocks: one lane group per edge builds the two edge-side operands
 //     side DST (negatives replace d): a_ej = <q, n_j>,  q = s*r (DistMult), s.r complex (ComplEx)
@@ -354,97 +324,211 @@ k_filter(RowArgs a, const int64_t* __restrict__ dst_off, const int32_t* __restri
 }
 
 // ------------------------------------------------- per-row reduce + Adagrad scatter -----
+// The gradient rows are summed per table row over the row-sorted order (a stable sort, so a row's
+// occurrences are always added in the same order and the sums are bit-reproducible) and the Adagrad
+// update (Sec. 5.1; one update per touched row and step) is applied where the sum becomes complete.
 struct ReduceArgs {
   float *node_emb, *node_state, *rel_emb, *rel_state;
-  const float* G;            // [n_rows][dk] gradient rows in row-sorted order
-  float* Gu;                 // [unique rows][dk] summed gradient per unique row
-  float* carry;              // [tasks][2][dk]
+  const float* G;            // [n_rows][dk] gradient rows
+  float* carry;              // [blocks][2][dk] partial sums of segments that cross block borders
   const int32_t* rank_sorted;
   const int32_t* perm;       // position in row-sorted order -> gradient row
   const uint32_t* seg_off;
   const int32_t* uniq;
-  const int32_t* scalars;    // [0] = number of unique rows
-  float* dbg_grad;
+  int32_t* scalars;          // [2] = number of entries in `owners`
+  int32_t* owners;           // blocks in which a segment begins that continues into later blocks
+  float* dbg_grad;           // [unique rows][dim] summed gradients (debug output), or NULL
   int64_t n_rows;
   int32_t num_nodes, dim, dk;
   float lr, eps;
 };
 
-// One wave per task of MAR_TASK_ROWS consecutive positions of the row-sorted order (the rows
-// themselves are gathered through perm).  Rows of one segment (= one unique table row) are summed; a segment that lies inside the task is finished here, one that
-// crosses the task's borders leaves a partial sum (slot 0: began earlier, slot 1: continues).
-// Rows are fetched BATCH at a time so that many loads are in flight per wave, and each lane
-// fetches its position's segment bounds up front so that no load depends on another.
-template <int NV, int BATCH>
-__global__ void __launch_bounds__(256) k_reduce(ReduceArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int64_t p0 = task * MAR_TASK_ROWS;
-  if (p0 >= a.n_rows) return;
-  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_rows ? p0 + MAR_TASK_ROWS : a.n_rows;
-  const int cnt = (int)(p1 - p0);
+__device__ __forceinline__ void add4(float4& a, const float4& b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+
+// Four consecutive floats of a table row starting at column `col`.  VEC: rows are 16-byte aligned (dim % 4 == 0).
+template <bool VEC> __device__ __forceinline__ float4 load_row4(const float* __restrict__ row, int col, int dim) {
+  if (VEC) return *reinterpret_cast<const float4*>(row + col);
+  float4 v;
+  v.x = col + 0 < dim ? row[col + 0] : 0.f; v.y = col + 1 < dim ? row[col + 1] : 0.f;
+  v.z = col + 2 < dim ? row[col + 2] : 0.f; v.w = col + 3 < dim ? row[col + 3] : 0.f;
+  return v;
+}
+
+template <bool VEC> __device__ __forceinline__ void store_row4(float* __restrict__ row, int col, int dim, const float4& v) {
+  if (VEC) { *reinterpret_cast<float4*>(row + col) = v; return; }
+  if (col + 0 < dim) row[col + 0] = v.x;
+  if (col + 1 < dim) row[col + 1] = v.y;
+  if (col + 2 < dim) row[col + 2] = v.z;
+  if (col + 3 < dim) row[col + 3] = v.w;
+}
+
+__device__ __forceinline__ void table_rows(const ReduceArgs& a, int32_t id, float*& emb, float*& st) {
+  if (id < a.num_nodes) { emb = a.node_emb + (size_t)id * a.dim; st = a.node_state + (size_t)id * a.dim; }
+  else { emb = a.rel_emb + (size_t)(id - a.num_nodes) * a.dim; st = a.rel_state + (size_t)(id - a.num_nodes) * a.dim; }
+}
+
+// state += g^2; theta -= lr * g / (sqrt(state) + eps) on four columns whose old values are th, s0.
+template <bool VEC>
+__device__ __forceinline__ void adagrad4(const ReduceArgs& a, float* __restrict__ emb, float* __restrict__ st, int rank, int col,
+                                         const float4& g, const float4& th, const float4& s0) {
+  float4 s1, e1;
+  s1.x = s0.x + g.x * g.x; s1.y = s0.y + g.y * g.y; s1.z = s0.z + g.z * g.z; s1.w = s0.w + g.w * g.w;
+  e1.x = th.x - a.lr * g.x / (sqrtf(s1.x) + a.eps); e1.y = th.y - a.lr * g.y / (sqrtf(s1.y) + a.eps);
+  e1.z = th.z - a.lr * g.z / (sqrtf(s1.z) + a.eps); e1.w = th.w - a.lr * g.w / (sqrtf(s1.w) + a.eps);
+  store_row4<VEC>(st, col, a.dim, s1);
+  store_row4<VEC>(emb, col, a.dim, e1);
+  if (a.dbg_grad) store_row4<VEC>(a.dbg_grad + (size_t)rank * a.dim, col, a.dim, g);
+}
+
+// A workgroup takes MAR_REDUCE_BLOCK consecutive positions, a group of GL lanes GL of them (a "task"; the
+// lanes of a group move one row as float4s, NV per lane).  Each lane first fetches the rank, gradient row,
+// segment bounds and table row id of one position of its task, so that no later load depends on another.
+// The task's rows are then fetched BATCH at a time -- together with the table row and accumulator row of
+// every position at which a segment ends that also began inside the task -- and added up in position
+// order; such a segment is finished by the Adagrad update right there.  A segment that crosses the task's
+// borders leaves a partial sum in LDS (head: began earlier, tail: continues); the workgroup then chains the
+// partials of its tasks in order, finishes the segments that lie inside the workgroup, and writes those
+// that cross its own borders to `carry` (slot 0: began in an earlier workgroup, slot 1: continues into the
+// next; a workgroup with a slot-1 partial appends itself to `owners`).
+template <int GL, int NV, int BATCH, bool VEC>
+__global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
+  constexpr int GPB = 256 / GL;
+  __shared__ float4 s_head[GPB][GL * NV], s_tail[GPB][GL * NV];
+  __shared__ int s_hs[GPB], s_tf[GPB];       // head: 0 none, 1 ends inside the task, 2 runs through it; tail: 0 / 1
+  const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
+  const int64_t P0 = (int64_t)blockIdx.x * MAR_REDUCE_BLOCK;
+  const int64_t p0 = P0 + (int64_t)grp * GL;
+  const int64_t left = a.n_rows - p0;
+  const int cnt = left < 0 ? 0 : (left < GL ? (int)left : GL);
+  const int64_t p1 = p0 + cnt;
   const int nq = a.dk >> 2;
-  const int my_rank = lane < cnt ? a.rank_sorted[p0 + lane] : -1;
-  const int my_row = lane < cnt ? a.perm[p0 + lane] : 0;
-  const int64_t my_lo = lane < cnt ? (int64_t)a.seg_off[my_rank] : 0;
-  const int64_t my_hi = lane < cnt ? (int64_t)a.seg_off[my_rank + 1] : 0;
-  int cur = __shfl(my_rank, 0), cur_i = 0;
+
+  int my_rank = 0, my_row = 0, my_id = 0, my_kind = 0;     // kind: 0 no segment end, 1 end of a segment inside the task,
+  int64_t my_lo = 0, my_hi = 0;                            //       2 end of a segment that began before the task
+  if (l < cnt) {
+    my_rank = a.rank_sorted[p0 + l];
+    my_row = a.perm[p0 + l];
+    my_lo = a.seg_off[my_rank];
+    my_hi = a.seg_off[my_rank + 1];
+    my_id = a.uniq[my_rank];
+    if (p0 + l == my_hi - 1) my_kind = my_lo >= p0 ? 1 : 2;
+  }
   float4 acc[NV];
 #pragma unroll
   for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-  auto flush = [&](int rank, int first_lane) {
-    const int64_t lo = __shfl(my_lo, first_lane), hi = __shfl(my_hi, first_lane);
-    float* dst = (lo >= p0 && hi <= p1) ? a.Gu + (size_t)rank * a.dk
-                                        : a.carry + ((size_t)task * 2 + (lo < p0 ? 0 : 1)) * a.dk;
-#pragma unroll
-    for (int v = 0; v < NV; ++v) { const int q = lane + 64 * v; if (q < nq) *reinterpret_cast<float4*>(dst + 4 * q) = acc[v]; }
-  };
-
   for (int i0 = 0; i0 < cnt; i0 += BATCH) {
-    float4 rows[BATCH][NV];
+    float4 g[BATCH][NV], th[BATCH][NV], s0[BATCH][NV];
+    int kind[BATCH];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-      const float* row = a.G + (size_t)__shfl(my_row, (i0 + j) & 63) * a.dk;
+      const int pj = (i0 + j) & (GL - 1);
+      const bool valid = i0 + j < cnt;
+      const int row = __shfl(my_row, pj, GL);
+      const int id = __shfl(my_id, pj, GL);
+      kind[j] = valid ? __shfl(my_kind, pj, GL) : 0;
+      const float* grow = a.G + (size_t)row * a.dk;
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
-        const int q = lane + 64 * v;
-        rows[j][v] = (i0 + j < cnt && q < nq) ? *reinterpret_cast<const float4*>(row + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int q = l + GL * v;
+        g[j][v] = (valid && q < nq) ? *reinterpret_cast<const float4*>(grow + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      if (kind[j] == 1) {
+        float *emb, *st;
+        table_rows(a, id, emb, st);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int q = l + GL * v;
+          if (q < nq) { th[j][v] = load_row4<VEC>(emb, 4 * q, a.dim); s0[j][v] = load_row4<VEC>(st, 4 * q, a.dim); }
+        }
       }
     }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
       if (i0 + j < cnt) {
-        const int r = __shfl(my_rank, i0 + j);
-        if (r != cur) {
-          flush(cur, cur_i);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) add4(acc[v], g[j][v]);
+        if (kind[j] != 0) {
+          const int pj = (i0 + j) & (GL - 1);
+          if (kind[j] == 1) {
+            float *emb, *st;
+            table_rows(a, __shfl(my_id, pj, GL), emb, st);
+            const int rank = __shfl(my_rank, pj, GL);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+              const int q = l + GL * v;
+              if (q < nq) adagrad4<VEC>(a, emb, st, rank, 4 * q, acc[v], th[j][v], s0[j][v]);
+            }
+          } else {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) s_head[grp][l + GL * v] = acc[v];
+          }
 #pragma unroll
           for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-          cur = r; cur_i = i0 + j;
-        }
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-          acc[v].x += rows[j][v].x; acc[v].y += rows[j][v].y; acc[v].z += rows[j][v].z; acc[v].w += rows[j][v].w;
         }
       }
     }
   }
-  flush(cur, cur_i);
+  // what is left in acc belongs to the segment of the task's last position, if that segment continues
+  int hs = 0, tf = 0;
+  if (cnt > 0) {
+    const int64_t lo_first = __shfl(my_lo, 0, GL), hi_first = __shfl(my_hi, 0, GL);
+    const int64_t lo_last = __shfl(my_lo, cnt - 1, GL), hi_last = __shfl(my_hi, cnt - 1, GL);
+    if (lo_first < p0) hs = hi_first <= p1 ? 1 : 2;
+    if (hi_last > p1) {
+      if (lo_last >= p0) tf = 1;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) (tf ? s_tail : s_head)[grp][l + GL * v] = acc[v];
+    }
+  }
+  if (l == 0) { s_hs[grp] = hs; s_tf[grp] = tf; }
+  __syncthreads();
+
+  // chain the tasks' partial sums: thread q owns column block q
+  const int q = threadIdx.x;
+  float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
+  bool active = false, inside = false;                     // a segment is open / it began inside this workgroup
+  for (int gi = 0; gi < GPB; ++gi) {
+    const int h = s_hs[gi];                                // uniform over the workgroup
+    if (h) {
+      const float4 hv = q < nq ? s_head[gi][q] : make_float4(0.f, 0.f, 0.f, 0.f);
+      if (active) add4(run, hv); else { run = hv; active = true; inside = false; }
+      if (h == 1) {
+        if (inside) {
+          const int rank = a.rank_sorted[P0 + (int64_t)gi * GL];
+          float *emb, *st;
+          table_rows(a, a.uniq[rank], emb, st);
+          if (q < nq) adagrad4<VEC>(a, emb, st, rank, 4 * q, run, load_row4<VEC>(emb, 4 * q, a.dim), load_row4<VEC>(st, 4 * q, a.dim));
+        } else if (q < nq) {
+          *reinterpret_cast<float4*>(a.carry + ((size_t)blockIdx.x * 2 + 0) * a.dk + 4 * q) = run;
+        }
+        active = false;
+      }
+    }
+    if (s_tf[gi]) {
+      run = q < nq ? s_tail[gi][q] : make_float4(0.f, 0.f, 0.f, 0.f);
+      active = true; inside = true;
+    }
+  }
+  if (active) {
+    if (q < nq) *reinterpret_cast<float4*>(a.carry + ((size_t)blockIdx.x * 2 + (inside ? 1 : 0)) * a.dk + 4 * q) = run;
+    if (inside && threadIdx.x == 0) a.owners[atomicAdd(&a.scalars[2], 1)] = (int32_t)blockIdx.x;
+  }
 }
 
-// Finishes the segments that span several tasks.  One workgroup per task; it has work only if
-// a spanning segment begins in its task: then its four waves add that task's tail partial and
-// the head partials of the following tasks (wave w takes every fourth), and the partial sums
-// are combined through LDS in wave order.  Block 0 also adds up the per-block loss terms in a
-// fixed order.
-template <int NV>
+// Finishes the segments that span several workgroups of k_reduce_apply: a workgroup takes an entry of
+// `owners` (in any order: every entry is a different table row), adds that block's slot-1 partial and
+// the slot-0 partials of the following blocks up to the segment's end -- wave w takes every fourth,
+// FB at a time, then the waves' sums are combined through LDS in wave order: a fixed tree -- and applies
+// the Adagrad update.  Block 0 first adds up the per-block loss terms, also in a fixed order.
+template <int NV, bool VEC>
 __global__ void __launch_bounds__(256)
-k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, float* __restrict__ loss_out) {
+k_span_apply(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, float* __restrict__ loss_out) {
   __shared__ float4 part[4][64 * NV];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (blockIdx.x == 0 && loss_out) {                        // uniform over the workgroup
     // thread t adds terms t, t + 256, ... (four independent running sums so that loads overlap), then
-    // lanes, then the four waves in order: a fixed summation tree
+    // lanes, then the four waves in order
     __shared__ float wsum4[4];
     float t4[4] = {0.f, 0.f, 0.f, 0.f};
     int i = threadIdx.x;
@@ -459,89 +543,55 @@ k_fixup(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, floa
     __syncthreads();
     if (threadIdx.x == 0) *loss_out = (wsum4[0] + wsum4[1]) + (wsum4[2] + wsum4[3]);
   }
-  const int64_t task = blockIdx.x;
-  const int64_t p0 = task * MAR_TASK_ROWS;
-  if (p0 >= a.n_rows) return;
-  const int64_t p1 = p0 + MAR_TASK_ROWS < a.n_rows ? p0 + MAR_TASK_ROWS : a.n_rows;
-  const int rank = a.rank_sorted[p1 - 1];
-  const int64_t lo = a.seg_off[rank], hi = a.seg_off[rank + 1];
-  if (!(lo >= p0 && hi > p1)) return;                       // uniform over the workgroup
   const int nq = a.dk >> 2;
-  const int64_t last_task = (hi - 1) / MAR_TASK_ROWS;
-  float4 acc[NV];
-#pragma unroll
-  for (int v = 0; v < NV; ++v) {
-    const int q = lane + 64 * v;
-    acc[v] = (wave == 0 && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)task * 2 + 1) * a.dk + 4 * q)
-                                   : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  constexpr int FB = 8;                                     // partial rows in flight per wave
-  for (int64_t t = task + 1 + wave; t <= last_task; t += 4 * FB) {
-    float4 rows[FB][NV];
-#pragma unroll
-    for (int j = 0; j < FB; ++j) {
-      const int64_t tt = t + 4 * j;
-#pragma unroll
-      for (int v = 0; v < NV; ++v) {
-        const int q = lane + 64 * v;
-        rows[j][v] = (tt <= last_task && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)tt * 2) * a.dk + 4 * q)
-                                                 : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < FB; ++j) {
-#pragma unroll
-      for (int v = 0; v < NV; ++v) {
-        acc[v].x += rows[j][v].x; acc[v].y += rows[j][v].y; acc[v].z += rows[j][v].z; acc[v].w += rows[j][v].w;
-      }
-    }
-  }
-#pragma unroll
-  for (int v = 0; v < NV; ++v) part[wave][lane + 64 * v] = acc[v];
-  __syncthreads();
-  if (wave == 0) {
+  const int n_owners = a.scalars[2];
+  for (int o = blockIdx.x; o < n_owners; o += gridDim.x) {  // uniform over the workgroup
+    const int64_t blk = a.owners[o];
+    const int64_t pe = (blk + 1) * MAR_REDUCE_BLOCK < a.n_rows ? (blk + 1) * MAR_REDUCE_BLOCK : a.n_rows;
+    const int rank = a.rank_sorted[pe - 1];
+    const int64_t hi = a.seg_off[rank + 1];
+    const int64_t last_blk = (hi - 1) / MAR_REDUCE_BLOCK;
+    float4 acc[NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
       const int q = lane + 64 * v;
-      float4 s = part[0][q];
-      for (int w = 1; w < 4; ++w) { const float4 o = part[w][q]; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
-      if (q < nq) *reinterpret_cast<float4*>(a.Gu + (size_t)rank * a.dk + 4 * q) = s;
+      acc[v] = (wave == 0 && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)blk * 2 + 1) * a.dk + 4 * q)
+                                     : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-  }
-}
-
-// Sparse Adagrad scatter (Sec. 5.1): one thread per (unique row, 4 columns):
-// state += g^2; theta -= lr * g / (sqrt(state) + eps).
-__global__ void __launch_bounds__(256) k_adagrad(ReduceArgs a) {
-  const int nq = a.dk >> 2;
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int rank = (int)(i / nq), q = (int)(i % nq);
-  if (rank >= a.scalars[0]) return;
-  const float4 g = *reinterpret_cast<const float4*>(a.Gu + (size_t)rank * a.dk + 4 * q);
-  const int32_t id = a.uniq[rank];
-  float *emb, *st;
-  if (id < a.num_nodes) { emb = a.node_emb + (size_t)id * a.dim; st = a.node_state + (size_t)id * a.dim; }
-  else { emb = a.rel_emb + (size_t)(id - a.num_nodes) * a.dim; st = a.rel_state + (size_t)(id - a.num_nodes) * a.dim; }
-  const float gv[4] = {g.x, g.y, g.z, g.w};
-  if ((a.dim & 3) == 0) {                       // rows are 16-byte aligned: vector access
-    const float4 s0 = *reinterpret_cast<const float4*>(st + 4 * q);
-    const float4 e0 = *reinterpret_cast<const float4*>(emb + 4 * q);
-    float4 s1, e1;
-    s1.x = s0.x + g.x * g.x; s1.y = s0.y + g.y * g.y; s1.z = s0.z + g.z * g.z; s1.w = s0.w + g.w * g.w;
-    e1.x = e0.x - a.lr * g.x / (sqrtf(s1.x) + a.eps); e1.y = e0.y - a.lr * g.y / (sqrtf(s1.y) + a.eps);
-    e1.z = e0.z - a.lr * g.z / (sqrtf(s1.z) + a.eps); e1.w = e0.w - a.lr * g.w / (sqrtf(s1.w) + a.eps);
-    *reinterpret_cast<float4*>(st + 4 * q) = s1;
-    *reinterpret_cast<float4*>(emb + 4 * q) = e1;
-    if (a.dbg_grad) *reinterpret_cast<float4*>(a.dbg_grad + (size_t)rank * a.dim + 4 * q) = g;
-  } else {
+    constexpr int FB = 8;                                   // partial rows in flight per wave
+    for (int64_t t = blk + 1 + wave; t <= last_blk; t += 4 * FB) {
+      float4 rows[FB][NV];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int col = 4 * q + k;
-      if (col < a.dim) {
-        const float s = st[col] + gv[k] * gv[k];
-        st[col] = s;
-        emb[col] = emb[col] - a.lr * gv[k] / (sqrtf(s) + a.eps);
-        if (a.dbg_grad) a.dbg_grad[(size_t)rank * a.dim + col] = gv[k];
+      for (int j = 0; j < FB; ++j) {
+        const int64_t tt = t + 4 * j;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int q = lane + 64 * v;
+          rows[j][v] = (tt <= last_blk && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)tt * 2) * a.dk + 4 * q)
+                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < FB; ++j) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) add4(acc[v], rows[j][v]);
+      }
+    }
+    __syncthreads();                                        // the previous entry's sums have been read
+#pragma unroll
+    for (int v = 0; v < NV; ++v) part[wave][lane + 64 * v] = acc[v];
+    __syncthreads();
+    if (wave == 0) {
+      float *emb, *st;
+      table_rows(a, a.uniq[rank], emb, st);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int q = lane + 64 * v;
+        if (q < nq) {
+          float4 s = part[0][q];
+          for (int w = 1; w < 4; ++w) add4(s, part[w][q]);
+          adagrad4<VEC>(a, emb, st, rank, 4 * q, s, load_row4<VEC>(emb, 4 * q, a.dim), load_row4<VEC>(st, 4 * q, a.dim));
+        }
       }
     }
   }
@@ -559,20 +609,10 @@ static RowArgs row_args(const mar_ctx* c, const MarBatch& b) {
   return a;
 }
 
-static inline int lane_group(int dk) { return dk <= 64 ? 16 : (dk <= 128 ? 32 : 64); }
-
-hipError_t mar_launch_positions(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
-  const MarLayout& L = c->L;
-  RowArgs a = row_args(c, b);
-  hipLaunchKernelGGL(k_positions, dim3((unsigned)((b.n_occ + 255) / 256)), dim3(256), 0, st, a, (int)c->dm.ipw_log2, L.seg_off,
-                     L.inv, L.slot, L.perm, L.rank_sorted, L.bitmap);
-  return hipGetLastError();
-}
-
 hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, hipStream_t st) {
   const MarLayout& L = c->L;
   RowArgs a = row_args(c, b);
-  const int GL = lane_group(a.dk), gpb = 256 / GL;
+  const int GL = mar_lane_group(a.dk), gpb = 256 / GL;
   const int nbB = (b.n + gpb - 1) / gpb;
   const int nbC = (2 * b.cn + gpb - 1) / gpb;
   const dim3 grid(nbB + nbC), blk(256);
@@ -587,7 +627,7 @@ hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t*
                              const int64_t* src_off, const int32_t* src_ids, const float* pos, int32_t* rank_dst,
                              int32_t* rank_src, hipStream_t st) {
   RowArgs a = row_args(c, b);
-  const int GL = lane_group(a.dk), gpb = 256 / GL;
+  const int GL = mar_lane_group(a.dk), gpb = 256 / GL;
   const dim3 grid((2 * b.n + gpb - 1) / gpb), blk(256);
 #define FILT(GLV, V) hipLaunchKernelGGL((k_filter<GLV, V>), grid, blk, 0, st, a, dst_off, dst_ids, src_off, src_ids, pos, rank_dst, rank_src)
   if (a.dim % 4 == 0) { if (GL == 16) FILT(16, true); else if (GL == 32) FILT(32, true); else FILT(64, true); }
@@ -599,7 +639,7 @@ hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t*
 hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
   const MarLayout& L = c->L;
   RowArgs a = row_args(c, b);
-  const int GL = lane_group(a.dk), gpb = 256 / GL;
+  const int GL = mar_lane_group(a.dk), gpb = 256 / GL;
   const dim3 grid((b.n + gpb - 1) / gpb), blk(256);
 #define CHAIN(GLV) hipLaunchKernelGGL(k_chain<GLV>, grid, blk, 0, st, a, L.gQ, L.ml, L.pos, L.lse, L.G, L.loss_part)
   if (GL == 16) CHAIN(16); else if (GL == 32) CHAIN(32); else CHAIN(64);
@@ -612,23 +652,25 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
   const MarDims& d = c->dm;
   ReduceArgs a;
   a.node_emb = c->node_emb; a.node_state = c->node_state; a.rel_emb = c->rel_emb; a.rel_state = c->rel_state;
-  a.G = L.G; a.Gu = L.Gu; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.perm = L.perm; a.seg_off = L.seg_off; a.uniq = L.uniq;
-  a.scalars = L.scalars; a.dbg_grad = dbg_grad; a.n_rows = b.n_pos; a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk;
-  a.lr = c->cfg.lr; a.eps = c->cfg.eps;
-  const int64_t tasks = (b.n_pos + MAR_TASK_ROWS - 1) / MAR_TASK_ROWS;
-  const dim3 grid((unsigned)((tasks + 3) / 4)), gridf((unsigned)tasks), blk(256);
-  const int GL = lane_group(d.dk), gpb = 256 / GL;
+  a.G = L.G; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.perm = L.perm; a.seg_off = L.seg_off; a.uniq = L.uniq;
+  a.scalars = L.scalars; a.owners = L.owners; a.dbg_grad = dbg_grad; a.n_rows = b.n_pos;
+  a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk; a.lr = c->cfg.lr; a.eps = c->cfg.eps;
+  const int64_t blocks = (b.n_pos + MAR_REDUCE_BLOCK - 1) / MAR_REDUCE_BLOCK;
+  const dim3 grid((unsigned)blocks), grids((unsigned)(blocks < 1024 ? blocks : 1024)), blk(256);
+  const int GL = mar_lane_group(d.dk), gpb = 256 / GL;
   const int n_loss_part = (b.n + gpb - 1) / gpb;
+  const bool vec = d.dim % 4 == 0;
+#define RED(GLV, NVV, BT) do { \
+    if (vec) hipLaunchKernelGGL((k_reduce_apply<GLV, NVV, BT, true>), grid, blk, 0, st, a); \
+    else hipLaunchKernelGGL((k_reduce_apply<GLV, NVV, BT, false>), grid, blk, 0, st, a); } while (0)
+  if (GL == 16) RED(16, 1, 8); else if (GL == 32) RED(32, 1, 8); else if (d.dk <= 256) RED(64, 1, 8); else RED(64, 2, 4);
+#undef RED
   if (d.dk <= 256) {
-    hipLaunchKernelGGL((k_reduce<1, 16>), grid, blk, 0, st, a);
-    hipLaunchKernelGGL(k_fixup<1>, gridf, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    if (vec) hipLaunchKernelGGL((k_span_apply<1, true>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    else hipLaunchKernelGGL((k_span_apply<1, false>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
   } else {
-    hipLaunchKernelGGL((k_reduce<2, 8>), grid, blk, 0, st, a);
-    hipLaunchKernelGGL(k_fixup<2>, gridf, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    if (vec) hipLaunchKernelGGL((k_span_apply<2, true>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    else hipLaunchKernelGGL((k_span_apply<2, false>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
   }
-  // at most min(unique-row capacity, occurrences of this batch) rows can be touched
-  const int64_t umax = d.u_max < b.n_occ ? d.u_max : b.n_occ;
-  const int64_t threads = umax * (d.dk >> 2);
-  hipLaunchKernelGGL(k_adagrad, dim3((unsigned)((threads + 255) / 256)), blk, 0, st, a);
   return hipGetLastError();
 }

@@ -63,8 +63,15 @@ def test_mean_loss_after_100_steps(name, steps):
     assert rel_final <= 1e-3 and rel_run <= 1e-3
     # every step, not just the last.  The per-edge loss starts near 2 log N and, on the tiny graph, passes
     # through zero on its way down; there the bar is absolute (1e-3 of one loss unit) instead of relative to
-    # the vanishing value.  (The two trajectories are not bit-identical: the GPU sums a row's gradient in an
-    # order that varies from run to run, and from a zero accumulator Adagrad's first update is lr * sign(G).)
-    # Envelope for the whole trajectory (not the stated bar, which is the final loss above): over 40 runs the
-    # largest value seen was 3.3e-4, at the zero crossing.
-    assert np.max(np.abs(mean_g - mean_o) / np.maximum(np.abs(mean_o), 1.0)) <= 3e-3
+    # the vanishing value.
+    assert np.max(np.abs(mean_g - mean_o) / np.maximum(np.abs(mean_o), 1.0)) <= 1e-3
+    # the trained tables themselves.  From a zero accumulator an element's first update is lr * sign(G), so an
+    # element whose gradient is zero up to rounding can start +-2 lr apart in fp32 and fp64 and carries that
+    # offset along; such elements are counted and bounded, all others must agree to 1e-3 of the table's scale.
+    for tg, to in zip(gt, ot):
+        scale = float(np.max(np.abs(to)))
+        diff = np.abs(tg.astype(np.float64) - to.astype(np.float64))
+        off = diff > 1e-3 * scale
+        print(name, "table elements off by more than 1e-3 of scale:", int(off.sum()), "of", off.size,
+              "largest", float(diff.max()) / scale, flush=True)
+        assert off.mean() <= 1e-4
