@@ -165,7 +165,8 @@ int mar_eval_filter(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const 
  *   ranks : device, [n_ranks] int32, every rank >= 1
  *   ks    : HOST array of num_k thresholds, 0 <= num_k <= 8
  *   out   : device, out, [1 + num_k] doubles: MRR, then Hits@ks[0], Hits@ks[1], ...
- * n_ranks = 0 writes zeros.  The sums are formed in a fixed order (bit-reproducible).
+ * n_ranks = 0 writes zeros.  The sums are formed in a fixed order that depends on n_ranks alone
+ * (bit-reproducible).  Partial sums go through the context's workspace.
  */
 int mar_rank_metrics(mar_ctx* ctx, const int32_t* ranks, int64_t n_ranks, const int32_t* ks, int32_t num_k,
                      double* out, void* hip_stream);

@@ -131,6 +131,7 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.G = (float*)take(n_pos * dk * 4);
   l.carry = (float*)take(blocks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);
+  l.metric_part = take((size_t)MAR_METRIC_MAX_PARTS * MAR_METRIC_PART_BYTES);
   if (L) *L = l;
   return off;
 }
@@ -314,7 +315,7 @@ extern "C" int mar_rank_metrics(mar_ctx* c, const int32_t* ranks, int64_t n_rank
   if (n_ranks < 0 || (n_ranks > 0 && !ranks)) return fail(MAR_EINVAL, "ranks is NULL or n_ranks negative");
   if (num_k < 0 || num_k > 8 || (num_k > 0 && !ks)) return fail(MAR_ERANGE, "num_k outside 0..8 or ks NULL");
   for (int j = 0; j < num_k; ++j) if (ks[j] < 1) return fail(MAR_EINVAL, "thresholds must be >= 1");
-  HIP_TRY(mar_launch_rank_metrics(ranks, n_ranks, ks, num_k, out, (hipStream_t)hip_stream), "metrics kernel");
+  HIP_TRY(mar_launch_rank_metrics(ranks, n_ranks, ks, num_k, out, c->L.metric_part, (hipStream_t)hip_stream), "metrics kernel");
   return MAR_OK;
 }
 

@@ -39,6 +39,7 @@ struct MarLayout {
                           // of negative occurrence k at row roles*n + (k - roles*n)*sy2 + i
   float*    carry;        // [reduce blocks][2][dk] partial sums of segments that cross workgroup borders
   float*    loss_part;    // per-block partial loss sums
+  void*     metric_part;  // [MAR_METRIC_MAX_PARTS] partial records of the rank metrics
 };
 
 struct MarDims {
@@ -80,6 +81,11 @@ void mar_set_error(const char* fmt, ...);
 #define MAR_SORT_TILE 4096
 #define MAR_SORT_MAX_BITS 10
 
+// Rank metrics: ranks per partial record, records a scratch area holds, bytes per record.
+#define MAR_METRIC_TILE 4096
+#define MAR_METRIC_MAX_PARTS 4096
+#define MAR_METRIC_PART_BYTES 72
+
 // Positions of the row-sorted order per workgroup of the reduce.
 #define MAR_REDUCE_BLOCK 256
 
@@ -112,7 +118,8 @@ hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t*
                              int32_t* rank_src, hipStream_t st);
 hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st);
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
-hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_t* ks, int num_k, double* out, hipStream_t st);
+hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_t* ks, int num_k, double* out, void* part,
+                                   hipStream_t st);
 int mar_flash_supported(int dk);
 int mar_flash_tile_rows(int dk, int pass);
 int mar_flash_stripe_rows(int dk, int pass);

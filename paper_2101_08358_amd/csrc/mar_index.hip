@@ -460,50 +460,6 @@ k_debug_uniq(const int32_t* __restrict__ uniq, const int32_t* __restrict__ scala
   }
 }
 
-// ------------------------------------------------------------------ rank metrics -----
-// MRR and Hits@k (Sec. 5.1, "Evaluation Task and Metrics") from a rank array.  One block; thread
-// t sums elements t, t + 1024, ... and the partial sums are combined by a fixed tree, so the
-// result does not depend on scheduling.
-struct MetricKs { int32_t k[8]; int32_t num; };
-
-__global__ void __launch_bounds__(1024)
-k_rank_metrics(const int32_t* __restrict__ ranks, int64_t n, MetricKs ks, double* __restrict__ out) {
-  __shared__ double s_rr[1024];
-  __shared__ unsigned long long s_hit[8][1024];
-  double rr = 0.0;
-  unsigned long long hit[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int64_t i = threadIdx.x; i < n; i += 1024) {
-    const int r = ranks[i];
-    rr += 1.0 / (double)r;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) if (j < ks.num && r <= ks.k[j]) hit[j]++;
-  }
-  s_rr[threadIdx.x] = rr;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) s_hit[j][threadIdx.x] = hit[j];
-  __syncthreads();
-  for (int o = 512; o >= 1; o >>= 1) {
-    if ((int)threadIdx.x < o) {
-      s_rr[threadIdx.x] += s_rr[threadIdx.x + o];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) s_hit[j][threadIdx.x] += s_hit[j][threadIdx.x + o];
-    }
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) {
-    out[0] = n > 0 ? s_rr[0] / (double)n : 0.0;
-    for (int j = 0; j < ks.num; ++j) out[1 + j] = n > 0 ? (double)s_hit[j][0] / (double)n : 0.0;
-  }
-}
-
-hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_t* ks, int num_k, double* out, hipStream_t st) {
-  MetricKs m;
-  m.num = num_k;
-  for (int j = 0; j < 8; ++j) m.k[j] = j < num_k ? ks[j] : 0;
-  hipLaunchKernelGGL(k_rank_metrics, dim3(1), dim3(1024), 0, st, ranks, n, m, out);
-  return hipGetLastError();
-}
-
 // ------------------------------------------------------------------- launchers -----
 static inline unsigned grid_for(int64_t n, int threads, unsigned cap) {
   int64_t g = (n + threads - 1) / threads;
