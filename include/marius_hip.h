@@ -172,6 +172,22 @@ int mar_rank_metrics(mar_ctx* ctx, const int32_t* ranks, int64_t n_ranks, const 
                      double* out, void* hip_stream);
 
 /*
+ * mar_rank_metrics for callers that cannot allocate device memory and therefore have no context and no
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and the same results bit for bit; the partial sums go through an array built into
+ * the library (MAR_RANK_METRICS_STATIC_MAX / 4096 records of 72 bytes = 288 KiB per GPU, held until the process
+ * ends).  The call allocates nothing and frees nothing; its first call on a device looks the array's address
+ * up.  It runs on the CURRENT device, to which hip_stream must belong.
+ *   n_ranks > MAR_RANK_METRICS_STATIC_MAX : MAR_ERANGE, nothing is enqueued (use mar_rank_metrics).
+ * All calls on one GPU share the array and overwrite what the previous call left in it (nothing has to start
+ * at zero: every record that is read was written by the same call); two calls that overlap in time on one GPU
+ * -- different streams, or different threads -- race and give undefined results.
+ */
+#define MAR_RANK_METRICS_STATIC_MAX ((int64_t)4096 * 4096)
+int mar_rank_metrics_static(const int32_t* ranks, int64_t n_ranks, const int32_t* ks, int32_t num_k,
+                            double* out, void* hip_stream);
+
+/*
  * Edge-bucket ordering for out-of-memory training (Sec. 4.1).  Host-only: all pointers are HOST memory.
  *   mar_beta_buffer_sequence  : Alg. 3.  Writes the sequence of partition buffers, row r = the c partition
  *                               ids in the buffer at step r; successive rows differ by one swapped

@@ -37,7 +37,7 @@ class MarDebugOut(ctypes.Structure):
 
 
 EXPORTS = ("mar_workspace_bytes", "mar_init_tables", "mar_sample_negatives", "mar_train_batch", "mar_eval_scores",
-           "mar_eval_filter", "mar_rank_metrics", "mar_beta_buffer_sequence", "mar_beta_edge_bucket_order", "mar_buffer_simulate",
+           "mar_eval_filter", "mar_rank_metrics", "mar_rank_metrics_static", "mar_beta_buffer_sequence", "mar_beta_edge_bucket_order", "mar_buffer_simulate",
            "mar_swap_lower_bound", "mar_beta_swap_count",
            "mar_profile_enable", "mar_profile_read", "mar_destroy", "mar_last_error")
 
@@ -64,6 +64,7 @@ def load_library():
     lib.mar_eval_scores.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.mar_eval_filter.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.mar_rank_metrics.argtypes = [vp, vp, i64, ctypes.POINTER(i32), i32, vp, vp]
+    lib.mar_rank_metrics_static.argtypes = [vp, i64, ctypes.POINTER(i32), i32, vp, vp]
     lib.mar_beta_buffer_sequence.argtypes = [i32, i32, vp, i64, ctypes.POINTER(i64)]
     lib.mar_beta_edge_bucket_order.argtypes = [i32, i32, i32, u64, vp]
     lib.mar_buffer_simulate.argtypes = [i32, i32, vp, i64, ctypes.POINTER(i64)]
@@ -149,6 +150,11 @@ def mar_eval_filter(ctx, src, rel, dst, n_edges, dst_off, dst_ids, src_off, src_
 def mar_rank_metrics(ctx, ranks, n_ranks, ks, out, stream=None):
     arr = (ctypes.c_int32 * max(len(ks), 1))(*ks)
     _check(load_library().mar_rank_metrics(ctx, _ptr(ranks), int(n_ranks), arr, len(ks), _ptr(out), _stream(stream)))
+
+
+def mar_rank_metrics_static(ranks, n_ranks, ks, out, stream=None):
+    arr = (ctypes.c_int32 * max(len(ks), 1))(*ks)
+    _check(load_library().mar_rank_metrics_static(_ptr(ranks), int(n_ranks), arr, len(ks), _ptr(out), _stream(stream)))
 
 
 def mar_swap_lower_bound(p, c):

@@ -2,8 +2,11 @@
 //
 // Two kernels: k_rank_partial sums 1/rank and the hit counts of MAR_METRIC_TILE ranks per workgroup into
 // one partial record, k_rank_final adds the records.  Every sum follows a fixed tree that depends only on
-// the number of ranks, so the result is bit-reproducible.  The partial records live in the context's
-// workspace.
+// the number of ranks, so the result is bit-reproducible.  The partial records live either in the
+// context's workspace (mar_rank_metrics) or in a file-scope device array (mar_rank_metrics_static, for
+// callers that have no workspace and may not allocate one).
+#include <mutex>
+
 #include "mar_common.h"
 
 struct MetricKs { int32_t k[8]; int32_t num; };
@@ -94,4 +97,44 @@ hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_
   if (nparts > 0) hipLaunchKernelGGL(k_rank_partial, dim3((unsigned)nparts), dim3(256), 0, st, ranks, n, m, p);
   hipLaunchKernelGGL(k_rank_final, dim3(1), dim3(256), 0, st, p, (int)nparts, n, m, out);
   return hipGetLastError();
+}
+
+// ------------------------------------------------ entry point that allocates nothing -----
+// Partial records of mar_rank_metrics_static.  One copy per GPU, held until the process ends; in host code
+// the name is only a handle for hipGetSymbolAddress, the device address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[MAR_METRIC_MAX_PARTS * MAR_METRIC_PART_BYTES];
+
+#define MAR_MAX_DEVICES 64
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[MAR_MAX_DEVICES];
+
+extern "C" int mar_rank_metrics_static(const int32_t* ranks, int64_t n_ranks, const int32_t* ks, int32_t num_k,
+                                       double* out, void* hip_stream) {
+  if (!out) { mar_set_error("out is NULL"); return MAR_EINVAL; }
+  if (n_ranks < 0 || (n_ranks > 0 && !ranks)) { mar_set_error("ranks is NULL or n_ranks negative"); return MAR_EINVAL; }
+  if (num_k < 0 || num_k > 8 || (num_k > 0 && !ks)) { mar_set_error("num_k outside 0..8 or ks NULL"); return MAR_ERANGE; }
+  for (int j = 0; j < num_k; ++j) if (ks[j] < 1) { mar_set_error("thresholds must be >= 1"); return MAR_EINVAL; }
+  if (n_ranks > MAR_RANK_METRICS_STATIC_MAX) {
+    mar_set_error("n_ranks %lld exceeds the %lld ranks the built-in scratch array serves; use mar_rank_metrics with a context",
+                  (long long)n_ranks, (long long)MAR_RANK_METRICS_STATIC_MAX);
+    return MAR_ERANGE;
+  }
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { mar_set_error("hipGetDevice: %s", hipGetErrorString(e)); return MAR_EHIP; }
+  if (dev < 0 || dev >= MAR_MAX_DEVICES) { mar_set_error("device index %d outside 0..%d", dev, MAR_MAX_DEVICES - 1); return MAR_ERANGE; }
+  void* part = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) { mar_set_error("hipGetSymbolAddress(scratch): %s", hipGetErrorString(e)); return MAR_EHIP; }
+      g_scratch_ptr[dev] = p;
+    }
+    part = g_scratch_ptr[dev];
+  }
+  e = mar_launch_rank_metrics(ranks, n_ranks, ks, num_k, out, part, (hipStream_t)hip_stream);
+  if (e != hipSuccess) { mar_set_error("metrics kernels: %s", hipGetErrorString(e)); return MAR_EHIP; }
+  return MAR_OK;
 }
