@@ -6,10 +6,16 @@ A step is one pass of the whole hot path over one batch: negative sampling, uniq
 index, row gather, score block + softmax + both gradient contractions on the matrix cores,
 chain rule, per-row reduce and the sparse Adagrad scatter.  All inputs (edge list, tables)
 are resident in device memory before the timed region.
+
+With no arguments the headline is the largest workload that fits one GPU (`wide`: 50 M x 400
+tables and accumulators, 160 GB, the full 500 M-edge list); the same record for the two
+d = 100 workloads (`social`, `kg_large`; full-size tables, edge lists shortened as stated in
+each record) rides along under "other_workloads".  `--workload NAME` measures one workload alone.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -19,9 +25,28 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3       # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
-# HBM bytes of the two contraction passes of one full kg_small step, from the rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs summarised in profiles/traffic_k_flash_kg_small.md (counters scaled by a 1 GiB copy).
-MEASURED_FLASH_TRAFFIC = {"kg_small": 238.0e6}
+DEFAULT_STEPS = {"tiny": (300, 30), "kg_small": (500, 50), "social": (150, 15), "social_dot": (150, 15),
+                 "kg_large": (150, 15), "wide": (100, 10)}
+
+
+def note(msg):
+    sys.stderr.write("bench: %s\n" % msg)
+    sys.stderr.flush()
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of each kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary committed as
+    profiles/traffic_<workload>.md (table rows `| `kernel` | fetch MB | write MB | total MB |`).  Returns
+    {kernel name without template arguments: bytes} or {} if there is no summary for this workload."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.md" % workload)
+    out = {}
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        m = re.match(r"\|\s*`(k_[a-z_0-9]+)[^`]*`\s*\|.*\|\s*([0-9.]+)\s*\|\s*$", line)
+        if m:
+            out[m.group(1)] = out.get(m.group(1), 0.0) + float(m.group(2)) * 1e6
+    return out
 
 
 def oracle_baseline(w, es, er, ed, budget_s=15.0):
@@ -36,10 +61,10 @@ def oracle_baseline(w, es, er, ed, budget_s=15.0):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     V = w.num_nodes
-    note = ""
+    extra = ""
     if V * w.dim > 400_000_000:
         V = 2_000_000
-        note = ", node table reduced to 2 M rows (ids folded)"
+        extra = ", node table reduced to 2 M rows (ids folded)"
         es, ed = es % V, ed % V
     rng = np.random.default_rng(w.seed)
     ne = (rng.standard_normal((V, w.dim), dtype=np.float32) * np.float32(w.init_std))
@@ -49,7 +74,6 @@ def oracle_baseline(w, es, er, ed, budget_s=15.0):
     steps = 0
     t_total = 0.0
     i = 0
-    last_note = time.perf_counter()
     while True:
         lo, hi = i * w.batch_size, min((i + 1) * w.batch_size, es.shape[0])
         t0 = time.perf_counter()
@@ -58,149 +82,189 @@ def oracle_baseline(w, es, er, ed, budget_s=15.0):
         ostep.train_batch(w.model, np.float32(w.lr), np.float32(w.eps), w.chunk_size, ne, ns, re_, rs,
                           es[lo:hi], er[lo:hi], ed[lo:hi], nsrc, ndst)
         dt = time.perf_counter() - t0
-        if time.perf_counter() - last_note > 20.0:          # a sign of life during long CPU work
-            sys.stderr.write("cpu baseline: oracle step %d took %.2f s\n" % (i, dt)); sys.stderr.flush()
-            last_note = time.perf_counter()
+        note("cpu baseline: oracle step %d took %.2f s" % (i, dt))
         if i > 0:                       # first step is warm-up (BLAS thread start, page faults)
             t_total += dt; edges += hi - lo; steps += 1
         i += 1
         if (steps >= 3 and t_total >= budget_s) or steps >= 40 or (i + 1) * w.batch_size > es.shape[0]:
             break
     return dict(value=edges / t_total, unit="edges/s", cores=int(threads), kind="oracle",
-                sample="%d whole steps of workload %s (batch %d) after 1 warm-up step, numpy fp64%s" % (steps, w.name, w.batch_size, note))
+                sample="%d whole steps of workload %s (batch %d) after 1 warm-up step, numpy fp64%s" % (steps, w.name, w.batch_size, extra))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="kg_small")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--edges", type=int, default=0, help="shorten the synthetic edge list (the per-step work is unchanged)")
-    ap.add_argument("--nodes", type=int, default=0, help="shrink the node table (row width and batch geometry are unchanged)")
-    ap.add_argument("--no-phase-events", action="store_true", help="time the steps without the per-phase HIP events")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
-
-    import numpy as np
+def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_baseline=False):
+    """Builds the workload's inputs on the device, times `steps` training steps and returns the record."""
     import torch
     import synth
     import paper_2101_08358_amd as mar
 
-    if not os.path.exists(mar.library_path()):
-        from paper_2101_08358_amd import build
-        build.build()
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    w = synth.get_workload(args.workload)
-    if args.edges:
-        w = w.scaled(num_edges=args.edges)
-    if args.nodes:
-        w = w.scaled(num_nodes=args.nodes)
+    w = synth.get_workload(name)
+    full_edges = w.num_edges
+    if edges and edges < w.num_edges:
+        w = w.scaled(num_edges=edges)
+    if nodes:
+        w = w.scaled(num_nodes=nodes)
+    t_build = time.perf_counter()
     src, rel, dst = synth.make_graph(w.num_nodes, w.num_rels, w.num_edges, w.node_zipf, w.rel_zipf, seed=w.seed,
                                      device=dev if w.num_edges > 10_000_000 else "cpu")
     d_src, d_rel, d_dst = src.to(dev), rel.to(dev), dst.to(dev)
     tr = mar.Trainer(w.num_nodes, w.num_rels, w.dim, w.model, w.batch_size, w.num_chunks, w.negs_per_chunk,
                      w.deg_negs_per_chunk, w.lr, w.eps, w.init_std, w.seed, device=dev)
+    torch.cuda.synchronize()
+    note("%s: %d edges, %.1f GB of tables built in %.1f s" % (w.name, w.num_edges, 2 * 4e-9 * w.dim * (w.num_nodes + w.num_rels),
+                                                           time.perf_counter() - t_build))
     nb = (w.num_edges + w.batch_size - 1) // w.batch_size
-    bounds = [(b * w.batch_size, min((b + 1) * w.batch_size, w.num_edges)) for b in range(nb)]
-    batches = [(d_src[lo:hi], d_rel[lo:hi], d_dst[lo:hi], hi - lo) for lo, hi in bounds]
+    bounds = lambda b: (b * w.batch_size, min((b + 1) * w.batch_size, w.num_edges))
 
     def step(i):
-        s, r, d, n = batches[i % nb]
+        lo, hi = bounds(i % nb)
         mar.mar_sample_negatives(tr.ctx, i, d_src, d_dst, w.num_edges, tr.neg_src, tr.neg_dst)
-        mar.mar_train_batch(tr.ctx, s, r, d, n, tr.neg_src, tr.neg_dst, tr.loss, None)
-        return n
+        mar.mar_train_batch(tr.ctx, d_src[lo:hi], d_rel[lo:hi], d_dst[lo:hi], hi - lo, tr.neg_src, tr.neg_dst, tr.loss, None)
+        return hi - lo
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     # Timed region: K steps; only the dominant kernel (the two contraction passes) carries HIP events
     # (two per launch, on the stream it is launched on) so that the events cost the step little.
     FLASH = (1 << 2) | (1 << 3)
-    if not args.no_phase_events:
-        mar.mar_profile_enable(tr.ctx, min(args.steps, 4096), FLASH)
-    edges = 0
+    if phase_events:
+        mar.mar_profile_enable(tr.ctx, min(steps, 4096), FLASH)
+    edges_done = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.warmup, args.warmup + args.steps):
-        edges += step(i)
+    for i in range(warmup, warmup + steps):
+        edges_done += step(i)
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    elapsed = t1 - t0
-    if args.no_phase_events:
-        flash_phase, prof_steps = [0.0] * mar.NUM_PHASES, 0
-    else:
+    elapsed = time.perf_counter() - t0
+    if phase_events:
         flash_phase, prof_steps = mar.mar_profile_read(tr.ctx)
+    else:
+        flash_phase, prof_steps = [0.0] * mar.NUM_PHASES, 0
     loss = float(tr.loss.item())
-    last_batch_edges = batches[(args.warmup + args.steps - 1) % nb][3]
+    last_batch_edges = bounds((warmup + steps - 1) % nb)[1] - bounds((warmup + steps - 1) % nb)[0]
 
     # edges covered by the profiled steps (the first prof_steps of the timed region)
-    prof_edges = sum(batches[i % nb][3] for i in range(args.warmup, args.warmup + prof_steps))
-    flash_ms = flash_phase[2] + flash_phase[3]
-    algo_flops = 12.0 * prof_edges * w.negs_per_chunk * w.dim          # 3 contractions x 2 sides x 2 n N d
-    achieved = algo_flops / (flash_ms * 1e-3) / 1e12 if flash_ms > 0 else 0.0
-    flash_us = flash_ms / max(prof_steps, 1) * 1e3
+    prof_edges = sum(bounds(i % nb)[1] - bounds(i % nb)[0] for i in range(warmup, warmup + prof_steps))
+    per_launch = lambda ms: ms / max(prof_steps, 1) * 1e3                     # us per launch
+    flops = lambda k: k * prof_edges * w.negs_per_chunk * w.dim / max(prof_steps, 1)
+    tflops = lambda fl, us: fl / (us * 1e-6) / 1e12 if us > 0 else 0.0
+    flash_us = per_launch(flash_phase[2] + flash_phase[3])
+    achieved = tflops(flops(12.0), flash_us)                                  # 3 contractions x 2 sides x 2 n N d
 
     # A second, untimed pass with events on every phase for the per-phase report.
-    all_steps = min(args.steps, 200)
+    all_steps = min(steps, 100)
     mar.mar_profile_enable(tr.ctx, all_steps, (1 << mar.NUM_PHASES) - 1)
-    for i in range(args.warmup + args.steps, args.warmup + args.steps + all_steps):
+    for i in range(warmup + steps, warmup + steps + all_steps):
         step(i)
     torch.cuda.synchronize()
     phase_ms, phase_steps = mar.mar_profile_read(tr.ctx)
     mar.mar_profile_enable(tr.ctx, 0, 0)
 
     # one extra step with debug outputs for the unique-row count behind the bandwidth figures
-    s, r, d, n = batches[0]
+    lo, hi = bounds(0)
+    n = hi - lo
     dbg, t = tr.make_debug(n)
-    mar.mar_train_batch(tr.ctx, s, r, d, n, tr.neg_src, tr.neg_dst, tr.loss, dbg)
+    mar.mar_train_batch(tr.ctx, d_src[lo:hi], d_rel[lo:hi], d_dst[lo:hi], n, tr.neg_src, tr.neg_dst, tr.loss, dbg)
     torch.cuda.synchronize()
     nu = t["num_uniq"].cpu().numpy()
     U = int(nu[0] + nu[1])
+    roles = 2 if w.model == 3 else 3
     cn = w.num_chunks * w.negs_per_chunk
-    n_occ = 3 * n + 2 * cn
     dk = (w.dim + 3) // 4 * 4
     per_step = lambda ms: ms / max(phase_steps, 1)
-    gather_bytes = (3 * n + 2 * cn) * w.dim * 4 + (2 * n + 2 * cn) * dk * 4        # rows read + operands written
-    scatter_bytes = n_occ * dk * 4 + U * w.dim * 16                                 # gradient rows read + theta/state r+w
-    phases = {name: round(per_step(ms) * 1e3, 2) for name, ms in zip(mar.binding.PHASE_NAMES, phase_ms)}
-    out = {
-        "metric": "training edges/sec per MI355X; achieved HBM GB/s + MFMA util vs peak",
-        "value": edges / elapsed,
+    gather_bytes = (roles * n + 2 * cn) * w.dim * 4 + (2 * n + 2 * cn) * dk * 4     # rows read + operands written
+    scatter_bytes = (roles * n + 2 * cn) * dk * 4 + U * w.dim * 16                   # gradient rows read + theta/state r+w
+    chain_bytes = n * (2 * dk + 2 * roles * w.dim) * 4                               # operand gradients + s/r/d read, gradient rows written
+    phases = {nm: round(per_step(ms) * 1e3, 2) for nm, ms in zip(mar.binding.PHASE_NAMES, phase_ms)}
+    traffic = measured_traffic(w.name) if not nodes else {}          # per-launch bytes do not depend on the edge list
+    flash_traffic = (traffic.get("k_flash", 0.0) + traffic.get("k_flash_bwd", 0.0)) or None
+    gbs = lambda b, ms: b / (per_step(ms) * 1e-3) / 1e9 if ms > 0 else None
+    cfg = {"workload": w.name, "num_nodes": w.num_nodes, "num_rels": w.num_rels, "num_edges": w.num_edges,
+           "score": ["DistMult", "ComplEx", "TransE", "Dot"][w.model], "dim": w.dim, "batch": w.batch_size,
+           "chunks": w.num_chunks, "negs_per_chunk": w.negs_per_chunk, "deg_negs_per_chunk": w.deg_negs_per_chunk,
+           "table_bytes": 2 * 4 * w.dim * (w.num_nodes + w.num_rels)}
+    if w.num_edges != full_edges:
+        cfg["edge_list"] = "shortened from %d edges (the per-step work does not depend on the list's length)" % full_edges
+    rec = {
+        "value": edges_done / elapsed,
         "unit": "edges/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": elapsed / steps * 1e3,
         "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": w.name, "num_nodes": w.num_nodes, "num_rels": w.num_rels, "num_edges": w.num_edges,
-                   "score": ["DistMult", "ComplEx", "TransE", "Dot"][w.model], "dim": w.dim, "batch": w.batch_size,
-                   "chunks": w.num_chunks, "negs_per_chunk": w.negs_per_chunk, "deg_negs_per_chunk": w.deg_negs_per_chunk},
-        "roofline": {"bound": "mfma", "kernel": "k_flash (pass 1 + pass 2 of every step)", "achieved": achieved,
-                     "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": MEASURED_FLASH_TRAFFIC.get(w.name) if not (args.edges or args.nodes) else None,
+        "config": cfg,
+        "roofline": {"bound": "mfma", "kernel": "k_flash + k_flash_bwd (the two contraction launches of every step)",
+                     "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": flash_traffic,
                      "us_per_step": round(flash_us, 2),
-                     "algorithmic_flops_per_step": 12.0 * w.batch_size * w.negs_per_chunk * w.dim},
+                     "algorithmic_flops_per_step": 12.0 * w.batch_size * w.negs_per_chunk * w.dim,
+                     "k_flash": {"us": round(per_launch(flash_phase[2]), 2), "flops": flops(8.0),
+                                 "frac": tflops(flops(8.0), per_launch(flash_phase[2])) / PEAK_FP32_MFMA_TFLOPS},
+                     "k_flash_bwd": {"us": round(per_launch(flash_phase[3]), 2), "flops": flops(4.0),
+                                     "frac": tflops(flops(4.0), per_launch(flash_phase[3])) / PEAK_FP32_MFMA_TFLOPS}},
         "phases_us_per_step": phases,
         "hbm_phases": {
-            "gather": {"bytes": gather_bytes, "GB/s": gather_bytes / (per_step(phase_ms[1]) * 1e-3) / 1e9 if phase_ms[1] > 0 else None,
-                       "peak": PEAK_HBM_GBS},
-            "reduce_adagrad": {"bytes": scatter_bytes, "unique_rows": U,
-                               "GB/s": scatter_bytes / (per_step(phase_ms[5]) * 1e-3) / 1e9 if phase_ms[5] > 0 else None,
-                               "peak": PEAK_HBM_GBS}},
+            "gather": {"kernel": "k_prep", "bytes": gather_bytes, "GB/s": gbs(gather_bytes, phase_ms[1]),
+                       "frac": (gbs(gather_bytes, phase_ms[1]) or 0.0) / PEAK_HBM_GBS, "counter_bytes": traffic.get("k_prep")},
+            "chain_rule": {"kernel": "k_chain", "bytes": chain_bytes, "GB/s": gbs(chain_bytes, phase_ms[4]),
+                           "frac": (gbs(chain_bytes, phase_ms[4]) or 0.0) / PEAK_HBM_GBS, "counter_bytes": traffic.get("k_chain")},
+            "reduce_adagrad": {"kernel": "k_reduce_apply + k_span_apply", "bytes": scatter_bytes, "unique_rows": U,
+                               "GB/s": gbs(scatter_bytes, phase_ms[5]),
+                               "frac": (gbs(scatter_bytes, phase_ms[5]) or 0.0) / PEAK_HBM_GBS,
+                               "counter_bytes": (traffic.get("k_reduce_apply", 0.0) + traffic.get("k_span_apply", 0.0)) or None},
+            "peak_GB/s": PEAK_HBM_GBS},
         "final_loss_per_edge": loss / last_batch_edges,
     }
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         m = min(w.num_edges, 64 * w.batch_size)          # the oracle only walks the first batches
-        out["cpu_baseline"] = oracle_baseline(w, src[:m].cpu().numpy(), rel[:m].cpu().numpy(), dst[:m].cpu().numpy())
+        rec["cpu_baseline"] = oracle_baseline(w, src[:m].cpu().numpy(), rel[:m].cpu().numpy(), dst[:m].cpu().numpy())
     tr.close()
+    del tr, d_src, d_rel, d_dst, src, rel, dst, dbg, t
+    torch.cuda.empty_cache()
+    return rec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: per workload, about a second of GPU time)")
+    ap.add_argument("--warmup", type=int, default=0)
+    ap.add_argument("--workload", default="", help="measure this workload alone (default: wide, with social and kg_large beside it)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the records of the other workloads")
+    ap.add_argument("--edges", type=int, default=0, help="shorten the synthetic edge list (the per-step work is unchanged)")
+    ap.add_argument("--other-edges", type=int, default=100_000_000, help="edge-list length of the other workloads' records")
+    ap.add_argument("--nodes", type=int, default=0, help="shrink the node table (row width and batch geometry are unchanged)")
+    ap.add_argument("--no-phase-events", action="store_true", help="time the steps without the per-phase HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import paper_2101_08358_amd as mar
+
+    if not os.path.exists(mar.library_path()):
+        from paper_2101_08358_amd import build
+        build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    name = args.workload or "wide"
+    steps, warmup = DEFAULT_STEPS.get(name, (100, 10))
+    steps, warmup = args.steps or steps, args.warmup or warmup
+    rec = run_workload(name, steps, warmup, args.edges, args.nodes, not args.no_phase_events, not args.no_cpu_baseline)
+    out = {"metric": "training edges/sec per MI355X; achieved HBM GB/s + MFMA util vs peak",
+           "value": rec["value"], "unit": "edges/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+           "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic"}
+    for k in ("config", "roofline", "cpu_baseline", "phases_us_per_step", "hbm_phases", "final_loss_per_edge"):
+        if k in rec:
+            out[k] = rec[k]
+    if not args.workload and not args.no_others:
+        out["other_workloads"] = {}
+        for other in ("social", "kg_large"):
+            s, wu = DEFAULT_STEPS[other]
+            out["other_workloads"][other] = run_workload(other, s, wu, args.other_edges)
     print(json.dumps(out))
 
 
