@@ -31,7 +31,12 @@ static int hip_fail(hipError_t e, const char* what) {
 }
 
 // ------------------------------------------------------------------ configuration -----
-#define MAR_FLASH_TARGET_WGS 640
+#ifndef MAR_FLASH_TARGET_WGS1
+#define MAR_FLASH_TARGET_WGS1 640
+#endif
+#ifndef MAR_FLASH_TARGET_WGS2
+#define MAR_FLASH_TARGET_WGS2 640
+#endif
 
 static int check_config(const mar_config* cfg, MarDims* d) {
   if (!cfg) return fail(MAR_EINVAL, "config is NULL");
@@ -67,7 +72,7 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   // MAR_FLASH_TARGET_WGS workgroups (measured best for a 10,000-edge batch; the 50,000-edge shapes have
   // enough stripes and are not split).
   auto split = [&](int pass, int n_x, int n_y, int32_t* sy, int32_t* tps) {
-    const long target = MAR_FLASH_TARGET_WGS;
+    const long target = pass == 1 ? MAR_FLASH_TARGET_WGS1 : MAR_FLASH_TARGET_WGS2;
     const int sr = mar_flash_stripe_rows(d->dk, pass);
     const long wgs = 2L * d->C * ((n_x + sr - 1) / sr);
     const int ty = mar_flash_tile_rows(d->dk, pass);

@@ -17,6 +17,8 @@
 // so k_flash_bwd reads them back instead of multiplying again and runs only the second product,
 // with the roles of Q and K swapped.  Evaluation (PASS 3) only counts negatives scoring above
 // the positive.  TransE uses |q - n|^2 = |q|^2 + |n|^2 - 2 q.n for the scores and W = P / distance.
+#include <type_traits>
+
 #include "mar_common.h"
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -126,6 +128,20 @@ struct FlashGeom {
   static constexpr int NT = NK % 4;                                   // remaining k groups of 4
 };
 
+// Which float4 of a TY x NK tile (NK float4s per row) a thread moves in its u-th staging step.  Narrow rows:
+// a thread owns one column group (thread % NKP, NKP = NK rounded up to a power of two; the threads beyond NK
+// load a copy of the last group and store nothing) and steps through the rows with a fixed stride, so the
+// only per-thread state is a row, a column and an LDS offset, and every step's LDS offset is a constant apart.
+// Wide rows have no lanes to waste: slot = thread + 256 u over the row-major tile, recomputed where used.
+template <int NK, int TY>
+struct StageMap {
+  static constexpr bool PO2 = NK <= 64;
+  static constexpr int NKP = NK <= 16 ? 16 : (NK <= 32 ? 32 : 64);
+  static constexpr int RPS = 256 / NKP;                                // rows per step
+  static constexpr int NU = PO2 ? (TY + RPS - 1) / RPS : (TY * NK + 255) / 256;
+  static_assert(!PO2 || TY % RPS == 0, "tile rows must be a multiple of the rows per staging step");
+};
+
 // PASS: 1 scores + online softmax + gQ (training), 3 rank counts (evaluation).  L2: TransE scores.
 // XB: 16-row x-blocks per wave (a workgroup's stripe has 64*XB stationary rows); every LDS
 // fragment of Y then feeds XB matrix instructions.
@@ -133,17 +149,18 @@ struct FlashGeom {
 // fragments of the next block's score product are fetched before the current block's
 // second product is issued, and each row of the second product is fetched while the
 // previous row is being multiplied.
-#ifndef MAR_FLASH_WAVES_SMALL
-#define MAR_FLASH_WAVES_SMALL 2
-#endif
+// Waves per SIMD a kernel is built for: the register allocator may use the whole share of the register file
+// that this occupancy leaves to a wave, and does not trade spills for a higher occupancy.
+#define MAR_WAVES_PER_SIMD(n) __attribute__((amdgpu_waves_per_eu(n, n)))
+
 template <int NK, int NC, int VT, int TY, int XB, int PASS, int L2>
-__global__ void __launch_bounds__(256, (NK * XB <= 32 ? MAR_FLASH_WAVES_SMALL : (NK * XB <= 64 ? 2 : 1)))
+__global__ void __launch_bounds__(256) MAR_WAVES_PER_SIMD((NK * XB <= 64 ? 2 : 1))
 k_flash(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
   constexpr int N16 = GM::N16, NT = GM::NT;
   constexpr int PD = N16 <= 8 ? N16 : 4;                  // float4 fragments of the score product kept in flight
-  constexpr int NU = (TY * NK + 255) / 256;              // float4 units staged per thread
+  constexpr int NU = StageMap<NK, TY>::NU;                // float4 units staged per thread
   constexpr int SR = 64 * XB;                             // stationary rows per workgroup
   __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
   __shared__ float auy[TY];                               // per streamed row: squared norm (TransE)
@@ -214,42 +231,41 @@ k_flash(FlashArgs a) {
   const int ntiles_all = (n_y + TY - 1) / TY;
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);     // this part streams tiles [t_begin, ntiles); may be empty
-  // Per-thread staging slots: which row / float4 of a tile this thread moves.  For narrow rows everything
-  // that does not depend on the tile is computed once here (the vector ALU does not run beside the matrix
-  // pipe on this chip, so index arithmetic in the tile loop costs matrix time); wide rows have many slots
-  // and no registers to spare, so they recompute the slot (a division by a constant) where it is used.
-  constexpr bool HOIST = NK <= 32;
-  constexpr int NH = HOIST ? NU : 1;
-  float4 stage[NU];
+  // Per-thread staging slots: which row / float4 of a tile this thread moves (see StageMap).
+  typedef StageMap<NK, TY> SM;
+  v4f stage[NU];                                           // plain vectors: a struct copy from global memory would pin the array in memory
   float st_auy = 0.f;
-  int srow[NH], sgofs[NH], slofs[NH];                     // tile row, float offset in the tile (global), LDS offset
-  auto slot_of = [&](int u, int& row, int& gofs, int& lofs) {
-    const int unit = threadIdx.x + 256 * u;
-    const int r = unit / NK, cu = unit % NK;
-    row = (unit < TY * NK && 4 * cu < dk) ? r : (1 << 30);   // invalid slots: never below the rows left, load zeros
-    gofs = r * dk + 4 * cu;
-    lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+  const int s_cu = threadIdx.x % SM::NKP, s_r0 = threadIdx.x / SM::NKP;   // narrow rows: this thread's column group and first row
+  const int s_col = min(4 * s_cu, dk - 4);
+  const int s_lds = s_r0 * PITCH + 4 * s_cu;
+  auto slot_of = [&](int u, int& row, int& col, int& lofs) {
+    if (SM::PO2) {
+      row = s_r0 + SM::RPS * u; col = s_col;
+      lofs = s_cu < NK ? s_lds + u * SM::RPS * PITCH : -1;
+    } else {
+      const int unit = threadIdx.x + 256 * u;
+      const int r = unit / NK, cu = unit % NK;
+      row = unit < TY * NK ? r : TY - 1;
+      col = min(4 * cu, dk - 4);
+      lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+    }
   };
-  if (HOIST) {
-#pragma unroll
-    for (int u = 0; u < NU; ++u) slot_of(u, srow[u], sgofs[u], slofs[u]);
-  }
+  // Every staging load is issued unconditionally from an address clamped into the chunk's rows (and into
+  // the row's dk columns): no branch, no zero fill.  A row beyond the chunk then holds a copy of the last
+  // valid row; its scores are masked to -inf, so it weighs nothing.  A column group beyond dk holds a copy of
+  // the row's last four columns; it meets zero fragments of the stationary rows in the score product and
+  // produces output columns that are never stored.
   auto load_tile = [&](int t) {
     const int y0 = t * TY;
-    const int left = n_y - y0;                            // valid rows of this tile
+    const int last = n_y - y0 - 1;                        // last valid row of this tile (>= 0)
     const float* __restrict__ src = a.Y + (y_base + y0) * dk;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, gofs, lofs;
-      if (HOIST) { row = srow[u]; gofs = sgofs[u]; } else slot_of(u, row, gofs, lofs);
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row < left) v = *reinterpret_cast<const float4*>(src + gofs);
-      stage[u] = v;
+      int row, col, lofs;
+      slot_of(u, row, col, lofs);
+      stage[u] = *reinterpret_cast<const v4f*>(src + min(row, last) * dk + col);
     }
-    if (L2 && threadIdx.x < TY) {
-      const int yr = y0 + threadIdx.x;
-      st_auy = yr < n_y ? a.yy[y_base + yr] : 0.f;
-    }
+    if (L2 && threadIdx.x < TY) st_auy = a.yy[y_base + y0 + min((int)threadIdx.x, last)];
   };
   if (t_begin < ntiles) load_tile(t_begin);
 
@@ -269,9 +285,9 @@ k_flash(FlashArgs a) {
   auto stage_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, gofs, lofs;
-      if (HOIST) lofs = slofs[u]; else slot_of(u, row, gofs, lofs);
-      if (lofs >= 0) *reinterpret_cast<float4*>(&tile[lofs]) = stage[u];
+      int row, col, lofs;
+      slot_of(u, row, col, lofs);
+      if (lofs >= 0) *reinterpret_cast<v4f*>(&tile[lofs]) = stage[u];
     }
     if (L2 && threadIdx.x < TY) auy[threadIdx.x] = st_auy;
   };
@@ -280,11 +296,16 @@ k_flash(FlashArgs a) {
     __syncthreads();
   }
 
-  for (int t = t_begin; t < ntiles; ++t) {
-    const bool has_next = t + 1 < ntiles;
-    if (has_next) load_tile(t + 1);
+  // One tile.  HAS_NEXT (compile time): another tile follows, it is prefetched and this tile is full; the
+  // last tile of the part is a second copy of the code without prefetch, with row masks if it is partial.
+  // Keeping the prefetch unconditional inside a copy matters: a load under a branch makes the compiler
+  // wait for every outstanding memory operation (the score stores' round trip included) where the branches
+  // join.
+  auto do_tile = [&](const int t, auto has_next_c) __attribute__((always_inline)) {
+    constexpr bool HAS_NEXT = decltype(has_next_c)::value;
+    if (HAS_NEXT) load_tile(t + 1);
     const int y0 = t * TY;
-    const int nblk = min(TY / 16, (n_y - y0 + 15) / 16);
+    const int nblk = HAS_NEXT ? TY / 16 : min(TY / 16, (n_y - y0 + 15) / 16);
     load_head(0);
     // One 16-row block of the tile.  For a full tile the blocks are unrolled so that the compiler can count
     // the score stores issued after the next tile's prefetch loads and wait for the loads alone (loads and
@@ -312,6 +333,7 @@ k_flash(FlashArgs a) {
         for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.z, xf[b][4 * s + 2], tacc[b]);
 #pragma unroll
         for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.w, xf[b][4 * s + 3], tacc[b]);
+        if (N16 > PD) __builtin_amdgcn_sched_barrier(0);    // keeps the read PD fragments ahead of its use
       }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
@@ -378,8 +400,10 @@ k_flash(FlashArgs a) {
           wsum[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
         }
       }
-      // first fragments of the next block's score product, fetched under the second product
+      // first fragments of the next block's score product, fetched under the second product (the fence keeps
+      // the compiler from sinking the reads down to their uses, where their latency would be exposed)
       if (more) load_head(yb + 1);
+      __builtin_amdgcn_sched_barrier(0);
       if (PASS != 3) {
         // -- O^T[c][x] += sum_y Y[y][c] W[y][x]: A = Y fragment (row c), B = W (lane x)
 #pragma unroll
@@ -404,21 +428,22 @@ k_flash(FlashArgs a) {
         }
       }
     };
-    const bool full = y0 + TY <= n_y;                      // full tile: no row masks
-    if (NK <= 32 && full) {                                // narrow rows: blocks unrolled (wide rows lack the registers)
+    if (HAS_NEXT && NK <= 32) {                            // narrow rows: blocks unrolled (wide rows lack the registers)
 #pragma unroll
       for (int yb = 0; yb < TY / 16; ++yb) process_block(yb, yb + 1 < TY / 16, false);
-      __syncthreads();                                     // every wave is done with this tile
-      if (has_next) stage_tile();
-      __syncthreads();
     } else {
+      const bool full = y0 + TY <= n_y;                    // full tile: no row masks
 #pragma unroll 1
       for (int yb = 0; yb < nblk; ++yb) process_block(yb, yb + 1 < nblk, !full);
-      __syncthreads();
-      if (has_next) stage_tile();
+    }
+    if (HAS_NEXT) {
+      __syncthreads();                                     // every wave is done with this tile
+      stage_tile();
       __syncthreads();
     }
-  }
+  };
+  for (int t = t_begin; t + 1 < ntiles; ++t) do_tile(t, std::true_type());
+  if (t_begin < ntiles) do_tile(ntiles - 1, std::false_type());
 
   // ---- epilogue
 #pragma unroll
@@ -462,19 +487,23 @@ k_flash(FlashArgs a) {
 
 // Gradient w.r.t. the negatives' rows from stored scores: gK[j] = sum_e exp(T[e][j] - lse[e]) Q[e]
 // (TransE: weights divided by the distance, minus n_j times their sum).  A workgroup owns 64*XB
-// negatives (16*XB per wave) and streams the chunk's edges in tiles of TY: the Q rows go through
+// negatives (16*XB per wave; XB = 1 measured best: more, smaller workgroups fill the chip more evenly than
+// two blocks per wave save in LDS reads) and streams the chunk's edges in tiles of TY: the Q rows go through
 // LDS, the scores straight from memory into registers -- lane (g, m) takes T[e = 4g + r][j = m]
 // of its 16-negative block, which is the B-operand layout of O^T[c][j] += sum_e Q[e][c] W[e][j] --
 // one tile ahead: as soon as a block's scores are consumed the same registers are refilled with
 // the next tile's.  Only the second product runs on the matrix cores.
+#ifndef MAR_BWD_WAVES
+#define MAR_BWD_WAVES 2
+#endif
 template <int NK, int NC, int VT, int TY, int XB, int L2>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256) MAR_WAVES_PER_SIMD((NK * XB <= 32 ? MAR_BWD_WAVES : 2))
 k_flash_bwd(FlashArgs a) {
   typedef FlashGeom<NK> GM;
   constexpr int PITCH = GM::PITCH;
   constexpr int SR = 64 * XB;                             // negatives per workgroup
   constexpr int NB = TY / 16;                             // 16-row blocks per tile
-  constexpr int NU = (TY * NK + 255) / 256;              // float4 units of the Q tile staged per thread
+  constexpr int NU = StageMap<NK, TY>::NU;                // float4 units of the Q tile staged per thread
   __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
   __shared__ float aux[TY];                               // log-sum-exp of the streamed edges
 
@@ -508,26 +537,30 @@ k_flash_bwd(FlashArgs a) {
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);
 
-  // staging slots of the Q tile (index arithmetic hoisted out of the tile loop for narrow rows, see k_flash)
-  constexpr bool HOIST = NK <= 32;
-  constexpr int NH = HOIST ? NU : 1;
-  float4 stage[NU];
-  float st_aux = 0.f;
-  int srow[NH], sgofs[NH], slofs[NH];
-  auto slot_of = [&](int u, int& row, int& gofs, int& lofs) {
-    const int unit = threadIdx.x + 256 * u;
-    const int r = unit / NK, cu = unit % NK;
-    row = (unit < TY * NK && 4 * cu < dk) ? r : (1 << 30);
-    gofs = r * dk + 4 * cu;
-    lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+  // staging slots of the Q tile (see StageMap).  As in k_flash every load is unconditional, from a row clamped into the chunk: a row beyond the chunk is
+  // a copy of the last one and carries lse = +inf, so it weighs nothing.
+  typedef StageMap<NK, TY> SM;
+  v4f stage[NU];                                           // plain vectors: a struct copy from global memory would pin the array in memory
+  float2 st_ml;                                           // softmax statistics (part 0) of this thread's streamed row
+  const int s_cu = threadIdx.x % SM::NKP, s_r0 = threadIdx.x / SM::NKP;   // narrow rows: this thread's column group and first row
+  const int s_col = min(4 * s_cu, dk - 4);
+  const int s_lds = s_r0 * PITCH + 4 * s_cu;
+  auto slot_of = [&](int u, int& row, int& col, int& lofs) {
+    if (SM::PO2) {
+      row = s_r0 + SM::RPS * u; col = s_col;
+      lofs = s_cu < NK ? s_lds + u * SM::RPS * PITCH : -1;
+    } else {
+      const int unit = threadIdx.x + 256 * u;
+      const int r = unit / NK, cu = unit % NK;
+      row = unit < TY * NK ? r : TY - 1;
+      col = min(4 * cu, dk - 4);
+      lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+    }
   };
-  if (HOIST) {
-#pragma unroll
-    for (int u = 0; u < NU; ++u) slot_of(u, srow[u], sgofs[u], slofs[u]);
-  }
   // scores of the current tile: tr[yb][b][r] = T[e = y0 + 16 yb + 4g + r][j = stripe*SR + (wave*XB + b)*16 + m].
-  // The buffer is padded to whole tiles and stripes, so every address is valid; rows beyond the chunk
-  // carry lse = +inf and weigh nothing.
+  // The buffer is padded to whole tiles and stripes, so every address is valid, and pass 1 has written every
+  // row of a 64-row stripe that holds at least one edge (finite values); rows beyond the chunk carry
+  // lse = +inf and weigh nothing.
   float tr[NB][XB][4];
   const float* __restrict__ tcol = a.T + (size_t)cs * a.trows * a.tpitch + (size_t)(4 * g) * a.tpitch + stripe * SR + wave * XB * 16 + m;
   auto load_scores = [&](int t, int yb) {
@@ -538,56 +571,64 @@ k_flash_bwd(FlashArgs a) {
       for (int b = 0; b < XB; ++b) tr[yb][b][r] = p[(size_t)r * a.tpitch + 16 * b];
     }
   };
+  const size_t ml_stride = (size_t)2 * a.B;               // rows per part of pass 1's statistics
   auto load_tile = [&](int t) {
     const int y0 = t * TY;
-    const int left = n_y - y0;
+    const int last = n_y - y0 - 1;                        // last valid row of this tile (>= 0)
     const float* __restrict__ src = a.Y + (y_base + y0) * dk;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, gofs, lofs;
-      if (HOIST) { row = srow[u]; gofs = sgofs[u]; } else slot_of(u, row, gofs, lofs);
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row < left) v = *reinterpret_cast<const float4*>(src + gofs);
-      stage[u] = v;
+      int row, col, lofs;
+      slot_of(u, row, col, lofs);
+      stage[u] = *reinterpret_cast<const v4f*>(src + min(row, last) * dk + col);
     }
-    if (threadIdx.x < TY) {
-      // log-sum-exp of streamed row yr from the parts of pass 1
-      const int yr = y0 + threadIdx.x;
-      st_aux = __builtin_inff();
-      if (yr < n_y) {
-        const size_t pr = (size_t)2 * a.B;
-        float mm = -3.0e38f, ll = 0.f;
-        for (int p = 0; p < a.sy_ml; ++p) mm = fmaxf(mm, a.ml[(p * pr + y_base + yr) * 2]);
-        for (int p = 0; p < a.sy_ml; ++p) ll += a.ml[(p * pr + y_base + yr) * 2 + 1] * __expf(a.ml[(p * pr + y_base + yr) * 2] - mm);
-        st_aux = mm + logf(ll);
-      }
-    }
+    // statistics of streamed row threadIdx.x % TY (part 0 of pass 1); the log-sum-exp is formed from them only
+    // when the tile is staged, so that nothing waits for this load here
+    st_ml = reinterpret_cast<const float2*>(a.ml)[y_base + y0 + min((int)(threadIdx.x % TY), last)];
   };
-  auto stage_tile = [&]() {
+  auto stage_tile = [&](int t) {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, gofs, lofs;
-      if (HOIST) lofs = slofs[u]; else slot_of(u, row, gofs, lofs);
-      if (lofs >= 0) *reinterpret_cast<float4*>(&tile[lofs]) = stage[u];
+      int row, col, lofs;
+      slot_of(u, row, col, lofs);
+      if (lofs >= 0) *reinterpret_cast<v4f*>(&tile[lofs]) = stage[u];
     }
-    if (threadIdx.x < TY) aux[threadIdx.x] = st_aux;
+    {                                                      // every thread holds row threadIdx.x % TY: threads that share a
+      const int yr = t * TY + (int)(threadIdx.x % TY);     // row write the same value, and no wave takes a branch of its own
+      float mm = st_ml.x, ll = st_ml.y;
+      if (a.sy_ml > 1 && yr < n_y) {                       // pass 1 was split (small batches): merge the parts
+        const float2* __restrict__ mlp = reinterpret_cast<const float2*>(a.ml) + y_base + yr;
+        for (int p = 1; p < a.sy_ml; ++p) mm = fmaxf(mm, mlp[p * ml_stride].x);
+        ll *= __expf(st_ml.x - mm);
+        for (int p = 1; p < a.sy_ml; ++p) { const float2 v = mlp[p * ml_stride]; ll += v.y * __expf(v.x - mm); }
+      }
+      aux[threadIdx.x % TY] = yr < n_y ? mm + logf(ll) : __builtin_inff();
+    }
   };
   if (t_begin < ntiles) {
     load_tile(t_begin);
 #pragma unroll
     for (int yb = 0; yb < NB; ++yb) load_scores(t_begin, yb);
-    stage_tile();
+    stage_tile(t_begin);
     __syncthreads();
   }
 
-  for (int t = t_begin; t < ntiles; ++t) {
-    const bool has_next = t + 1 < ntiles;
-    if (has_next) load_tile(t + 1);
+  // One tile; HAS_NEXT (compile time): another tile follows and is prefetched -- its Q rows into the staging
+  // registers at the start, its scores into the registers of each block as soon as the block has consumed
+  // them -- with no branch around any load (see k_flash).  The last tile is a second copy without prefetch.
+  auto do_tile = [&](const int t, auto has_next_c) __attribute__((always_inline)) {
+    constexpr bool HAS_NEXT = decltype(has_next_c)::value;
+    // the copy for the last tile forms its lane coordinates afresh (from a thread id the compiler cannot see
+    // through) instead of keeping values alive across the main loop, which has no registers to spare
+    int tid_l = threadIdx.x;
+    if (!HAS_NEXT) asm volatile("" : "+v"(tid_l));
+    const int g = (tid_l & 63) >> 4, m = tid_l & 15;
+    if (HAS_NEXT) load_tile(t + 1);
     const int y0 = t * TY;
-    const int nblk = min(NB, (n_y - y0 + 15) / 16);
+    const int nblk = HAS_NEXT ? NB : min(NB, (n_y - y0 + 15) / 16);
 #pragma unroll
     for (int yb = 0; yb < NB; ++yb) {
-      if (yb < nblk) {                                     // uniform over the workgroup
+      if (HAS_NEXT || yb < nblk) {                         // uniform over the workgroup
         const int yl = yb * 16 + 4 * g;
         const float* ycol = &tile[yl * PITCH];
         float ya[NC];
@@ -604,7 +645,7 @@ k_flash_bwd(FlashArgs a) {
             w[b][r] = v;
           }
         }
-        if (has_next) load_scores(t + 1, yb);              // refill the registers just consumed
+        if (HAS_NEXT) load_scores(t + 1, yb);              // refill the registers just consumed
         if (L2) {
 #pragma unroll
           for (int b = 0; b < XB; ++b) wsum[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
@@ -629,15 +670,23 @@ k_flash_bwd(FlashArgs a) {
             }
           }
         }
-      } else if (has_next) {
-        load_scores(t + 1, yb);
-      }
+        __builtin_amdgcn_sched_barrier(0);                 // blocks are scheduled one by one: hoisting the next block's
+      }                                                    // LDS reads over this one costs more registers than there are
     }
-    __syncthreads();                                       // every wave is done with this tile
-    if (has_next) stage_tile();
-    __syncthreads();
-  }
+    if (HAS_NEXT) {
+      __syncthreads();                                     // every wave is done with this tile
+      stage_tile(t + 1);
+      __syncthreads();
+    }
+  };
+  for (int t = t_begin; t + 1 < ntiles; ++t) do_tile(t, std::true_type());
+  if (t_begin < ntiles) do_tile(ntiles - 1, std::false_type());
 
+  // The epilogue derives its lane coordinates from a copy of the thread id that the compiler cannot see
+  // through, so that they are formed here instead of being carried (spilled) across the tile loop.
+  int tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int wave_e = tid_e >> 6, g_e = (tid_e & 63) >> 4, m_e = tid_e & 15;
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
     float ws = wsum[b];
@@ -650,14 +699,14 @@ k_flash_bwd(FlashArgs a) {
       ot.x += __shfl_xor(ot.x, 16); ot.y += __shfl_xor(ot.y, 16); ot.z += __shfl_xor(ot.z, 16); ot.w += __shfl_xor(ot.w, 16);
       ot.x += __shfl_xor(ot.x, 32); ot.y += __shfl_xor(ot.y, 32); ot.z += __shfl_xor(ot.z, 32); ot.w += __shfl_xor(ot.w, 32);
     }
-    const int x = stripe * SR + (wave * XB + b) * 16 + m;
+    const int x = stripe * SR + (wave_e * XB + b) * 16 + m_e;
     if (x >= n_x) continue;
     const float* xrow = a.X + (x_base + x) * dk;
     // gradient row of part `part` of this negative's occurrence (occurrences: roles*n edge-side ones, then the
     // destination-replacing negatives, then the source-replacing ones)
     float* orow = a.out + (a.roles * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x) * a.sy + part) * dk;
-    store_orow<NC, L2 != 0>(orow, xrow, ws, dk, g, oacc[b]);
-    if (VT && g == 0 && 16 * NC < dk) {
+    store_orow<NC, L2 != 0>(orow, xrow, ws, dk, g_e, oacc[b]);
+    if (VT && g_e == 0 && 16 * NC < dk) {
       float4 o = ot;
       if (L2) {
         const float4 xs = *reinterpret_cast<const float4*>(xrow + 16 * NC);
@@ -676,17 +725,18 @@ int mar_flash_tile_rows(int dk, int pass) { return dk / 4 <= 32 ? 64 : (pass == 
 
 // Stationary rows per workgroup (64 per x-block of the instantiation that serves dk): pass 1 / 3 and pass 2.
 #ifndef MAR_BWD_XB
-#define MAR_BWD_XB 2
+#define MAR_BWD_XB 1
 #endif
 int mar_flash_stripe_rows(int dk, int pass) { return pass == 2 && dk / 4 <= 32 ? 64 * MAR_BWD_XB : 64; }
 
-template <int NK, int NC, int VT, int TY, int XB, int BXB, int BTY>
+// NK, NC, VT, TY, XB: pass 1 / 3 instantiation; BNC, BVT, BXB, BTY: pass 2's.
+template <int NK, int NC, int VT, int TY, int XB, int BNC, int BVT, int BXB, int BTY>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
 #define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, VT, TY, XB, P, L>), grid, dim3(256), 0, st, a)
   if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
   else if (pass == 2) {
-    if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, BTY, BXB, 1>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_flash_bwd<NK, NC, VT, BTY, BXB, 0>), grid, dim3(256), 0, st, a);
+    if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, BNC, BVT, BTY, BXB, 1>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_flash_bwd<NK, BNC, BVT, BTY, BXB, 0>), grid, dim3(256), 0, st, a);
   }
   else { if (l2) FL(3, 1); else FL(3, 0); }
 #undef FL
@@ -715,9 +765,13 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
-  if (nk <= 13) return launch_sized<13, 3, 1, 64, 1, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
-  if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
-  if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
-  if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 1, 32>(a, pass, l2, grid, st);
-  return launch_sized<100, 25, 0, 32, 1, 1, 16>(a, pass, l2, grid, st);
+#ifndef MAR_BWD_TAIL_MFMA
+#define MAR_BWD_TAIL_MFMA 0
+#endif
+  constexpr int BV = MAR_BWD_TAIL_MFMA ? 0 : 1;         // pass 2: last 4 columns on the vector ALU, or one more matrix block
+  if (nk <= 13) return launch_sized<13, 3, 1, 64, 1, 3 + (1 - BV), BV, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
+  if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, 6 + (1 - BV), BV, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
+  if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, 8, 0, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
+  if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 16, 0, 1, 32>(a, pass, l2, grid, st);
+  return launch_sized<100, 25, 0, 32, 1, 25, 0, 1, 16>(a, pass, l2, grid, st);
 }
