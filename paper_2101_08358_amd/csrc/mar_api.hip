@@ -92,6 +92,8 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   while (((int64_t)1 << nbits) < d->u_max) ++nbits;
   d->sort_passes = (nbits + MAR_SORT_MAX_BITS - 1) / MAR_SORT_MAX_BITS;
   d->sort_bits = (nbits + d->sort_passes - 1) / d->sort_passes;
+  // score pairs x row width per step: above ~2e9 the contraction passes are long enough to hide the index build
+  d->index_after_gather = (double)cfg->batch_size * cfg->negs_per_chunk * d->dk >= 2.0e9;
   return MAR_OK;
 }
 
@@ -245,6 +247,14 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   hipEvent_t* ev = nullptr;
   if (c->prof_events && c->prof_steps < c->prof_max) ev = c->prof_events + (size_t)c->prof_steps * 2 * MAR_NUM_PHASES;
 #define MARK(phase, end, stream) do { if (ev && (c->prof_mask >> (phase) & 1u)) HIP_TRY(hipEventRecord(ev[2 * (phase) + (end)], stream), "event record"); } while (0)
+  // Two orders of the first launches.  Large batches: the gather runs alone at memory speed and the index build
+  // starts behind it, beside the first contraction pass that hides it.  Small batches: the index build is the
+  // longer path to the reduce, so it starts first and the gather runs beside it.
+  if (c->dm.index_after_gather) {
+    MARK(1, 0, st);
+    HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, st), "gather kernel");
+    MARK(1, 1, st);
+  }
   HIP_TRY(hipEventRecord(c->ev_fork, st), "fork");
   HIP_TRY(hipStreamWaitEvent(ax, c->ev_fork, 0), "fork");
   MARK(0, 0, ax);
@@ -252,9 +262,11 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   if (dbg) HIP_TRY(mar_launch_debug_copy(c, b, dbg, ax), "debug copy");
   MARK(0, 1, ax);
   HIP_TRY(hipEventRecord(c->ev_index, ax), "join");
-  MARK(1, 0, st);
-  HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, st), "gather kernel");
-  MARK(1, 1, st);
+  if (!c->dm.index_after_gather) {
+    MARK(1, 0, st);
+    HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, st), "gather kernel");
+    MARK(1, 1, st);
+  }
   MARK(2, 0, st);
   HIP_TRY(mar_launch_flash(c, b, 1, nullptr, nullptr, st), "score/softmax kernel");
   MARK(2, 1, st);

@@ -55,6 +55,7 @@ struct MarDims {
   int64_t nwords;                  // words of the touched-id map
   int32_t ipw_log2;                // ids per word: 5 = one bit per id (atomic marks), 2 = one byte per id (plain stores)
   int32_t sort_passes, sort_bits;  // radix sort of the gradient rows by rank: passes, bits per pass
+  int32_t index_after_gather;      // launch order of a step: gather first, index build behind it (large batches)
 };
 
 #define MAR_MAX_PROFILE_STEPS 4096

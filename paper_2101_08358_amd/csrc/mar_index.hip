@@ -329,24 +329,38 @@ k_sort_hist(OccArgs a, int64_t n_pos, int sy2, int L, const uint32_t* __restrict
   __syncthreads();
   const int64_t base = (int64_t)blockIdx.x * MAR_SORT_TILE;
   const int64_t n3 = a.roles * (int64_t)a.n;
-#pragma unroll 4
-  for (int j = 0; j < MAR_SORT_TILE / 256; ++j) {
-    const int64_t gr = base + j * 256 + threadIdx.x;
-    const bool valid = gr < n_pos;
-    uint32_t key = 0u;
-    if (valid) {
-      if (FIRST) {
-        const int64_t k = gr < n3 ? gr : n3 + (gr - n3) / sy2;
-        const uint32_t id = (uint32_t)occ_unified_id(a, k);
-        const uint32_t w = id >> L;
-        key = word_prefix[w] + __popc(bitmap[w] & ((1u << map_bitpos(id, L)) - 1u));
-        keys_out[gr] = key;
-      } else {
-        key = keys_in[gr];
-      }
+  constexpr int ITEMS = MAR_SORT_TILE / 256;
+  // keys of this thread's elements; the three dependent loads behind a key (id, map word, prefix) are issued
+  // level by level for all elements, so the kernel pays three memory round trips, not three per element
+  uint32_t key[ITEMS];
+  if (FIRST) {
+    uint32_t id[ITEMS], word[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+      const int64_t gr = base + j * 256 + threadIdx.x;
+      const int64_t grc = gr < n_pos ? gr : n_pos - 1;
+      id[j] = (uint32_t)occ_unified_id(a, grc < n3 ? grc : n3 + (grc - n3) / sy2);
     }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) { word[j] = bitmap[id[j] >> L]; key[j] = word_prefix[id[j] >> L]; }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+      key[j] += __popc(word[j] & ((1u << map_bitpos(id[j], L)) - 1u));
+      const int64_t gr = base + j * 256 + threadIdx.x;
+      if (gr < n_pos) keys_out[gr] = key[j];
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+      const int64_t gr = base + j * 256 + threadIdx.x;
+      key[j] = gr < n_pos ? keys_in[gr] : 0u;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < ITEMS; ++j) {
+    const bool valid = base + j * 256 + threadIdx.x < n_pos;
     // one LDS atomic per distinct digit of the wave (a hot row fills whole waves with one key)
-    const uint32_t digit = (key >> shift) & (uint32_t)(bins - 1);
+    const uint32_t digit = (key[j] >> shift) & (uint32_t)(bins - 1);
     const uint64_t same = match_digit(digit, bits, valid);
     if (valid && (same & ((1ull << lane) - 1ull)) == 0ull) atomicAdd(&h[digit], (uint32_t)__popcll(same));
   }
@@ -380,14 +394,21 @@ k_sort_scatter(const uint32_t* __restrict__ keys_in, const int32_t* __restrict__
   const int per = (bins + 255) / 256;
   uint32_t before[4] = {0u, 0u, 0u, 0u}, total[4] = {0u, 0u, 0u, 0u};
   const int d0 = threadIdx.x * per;
-  for (int b = 0; b < ntiles; ++b) {
-    const uint32_t* hrow = hist + (size_t)b * bins;
+  // the tiles' counts are fetched eight tiles at a time (independent loads), summed in tile order
+  for (int b0 = 0; b0 < ntiles; b0 += 8) {
+    uint32_t v[8][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (j < per && d0 + j < bins) {
-        const uint32_t v = hrow[d0 + j];
-        total[j] += v;
-        if (b < (int)blockIdx.x) before[j] += v;
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t* hrow = hist + (size_t)(b0 + i) * bins;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[i][j] = (b0 + i < ntiles && j < per && d0 + j < bins) ? hrow[d0 + j] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        total[j] += v[i][j];
+        if (b0 + i < (int)blockIdx.x) before[j] += v[i][j];
       }
     }
   }

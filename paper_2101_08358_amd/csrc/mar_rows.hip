@@ -21,13 +21,24 @@ template <int GL> __device__ __forceinline__ float group_sum(float v) {
 }
 
 // ---------------------------------------------------------------------- gather -----
-// Edge blocks: one lane group per edge builds the two edge-side operands
+// Edge blocks: one lane group per PREP_EDGES edges builds the two edge-side operands of each
 //     side DST (negatives replace d): a_ej = <q, n_j>,  q = s*r (DistMult), s.r complex (ComplEx)
 //     side SRC (negatives replace s): b_ej = <q, m_j>,  q = r*d,            conj(r).d
 //   for TransE the scores are -|q - n_j| with q = s + r and q = d - r; also the positive score.
-// Negative blocks: one lane group per negative copies its row into the dense per-chunk matrix.
-// VEC: dim is a multiple of 4, rows are moved as float4 (float2 pairs for the two halves of a ComplEx row).
-template <int GL, bool VEC>
+// Negative blocks: one lane group per PREP_NEGS negatives copies their rows into the dense per-chunk matrix.
+// A group issues the loads of all its rows before the first use: the gathers are bound by the latency of
+// scattered row reads (address translation included), so bytes in flight per lane are what counts.
+// VEC: dim is a multiple of 4, rows are moved as float4 (float2 pairs for the two halves of a ComplEx row) and
+// a lane holds all its pieces of a row (NV per row); otherwise one element per lane and step.
+// MODEL: the score function, resolved at compile time.
+#ifndef PREP_EDGES
+#define PREP_EDGES 2
+#endif
+#ifndef PREP_NEGS
+#define PREP_NEGS 4
+#endif
+
+template <int GL, int NV, bool VEC, int MODEL>
 __global__ void __launch_bounds__(256)
 k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float* __restrict__ qq,
        float* __restrict__ kk, float* __restrict__ pos, float* __restrict__ pos_user) {
@@ -36,105 +47,196 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
   const int dim = a.dim, dk = a.dk;
   if (blk < nbB) {
-    const int e = blk * GPB + grp;
-    if (e >= a.n) return;
-    const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
-    const float* r_row = a.rel_emb + (size_t)(a.model == MAR_MODEL_DOT ? 0 : a.rel[e]) * dim;     // unused by Dot
-    const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
-    float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
-    float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
-    float acc = 0.f, nd = 0.f, ns = 0.f;
-    if (VEC && a.model == MAR_MODEL_COMPLEX) {
+    const int e0 = (blk * GPB + grp) * PREP_EDGES;
+    if (e0 >= a.n) return;
+    const float *s_row[PREP_EDGES], *r_row[PREP_EDGES], *d_row[PREP_EDGES];
+#pragma unroll
+    for (int j = 0; j < PREP_EDGES; ++j) {
+      const int e = min(e0 + j, a.n - 1);                        // a group's surplus edge repeats the last one (not stored)
+      s_row[j] = a.node_emb + (size_t)a.src[e] * dim;
+      r_row[j] = a.rel_emb + (size_t)(MODEL == MAR_MODEL_DOT ? 0 : a.rel[e]) * dim;     // unused by Dot
+      d_row[j] = a.node_emb + (size_t)a.dst[e] * dim;
+    }
+    float acc[PREP_EDGES], nd[PREP_EDGES], ns[PREP_EDGES];
+#pragma unroll
+    for (int j = 0; j < PREP_EDGES; ++j) acc[j] = nd[j] = ns[j] = 0.f;
+    if (VEC && MODEL == MAR_MODEL_COMPLEX) {
       const int h = dim >> 1;
-      for (int k = 2 * l; k < h; k += 2 * GL) {
-        const float2 sr = *reinterpret_cast<const float2*>(s_row + k), si = *reinterpret_cast<const float2*>(s_row + h + k);
-        const float2 rr = *reinterpret_cast<const float2*>(r_row + k), ri = *reinterpret_cast<const float2*>(r_row + h + k);
-        const float2 dr = *reinterpret_cast<const float2*>(d_row + k), di = *reinterpret_cast<const float2*>(d_row + h + k);
-        const float2 ure = make_float2(sr.x * rr.x - si.x * ri.x, sr.y * rr.y - si.y * ri.y);
-        const float2 uim = make_float2(sr.x * ri.x + si.x * rr.x, sr.y * ri.y + si.y * rr.y);
-        const float2 wre = make_float2(rr.x * dr.x + ri.x * di.x, rr.y * dr.y + ri.y * di.y);
-        const float2 wim = make_float2(rr.x * di.x - ri.x * dr.x, rr.y * di.y - ri.y * dr.y);
-        acc += (ure.x * dr.x + uim.x * di.x) + (ure.y * dr.y + uim.y * di.y);
-        *reinterpret_cast<float2*>(qd + k) = ure; *reinterpret_cast<float2*>(qd + h + k) = uim;
-        *reinterpret_cast<float2*>(qs + k) = wre; *reinterpret_cast<float2*>(qs + h + k) = wim;
+      float2 sr[PREP_EDGES][NV], si[PREP_EDGES][NV], rr[PREP_EDGES][NV], ri[PREP_EDGES][NV], dr[PREP_EDGES][NV], di[PREP_EDGES][NV];
+#pragma unroll
+      for (int j = 0; j < PREP_EDGES; ++j) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int k = 2 * (l + GL * v);
+          if (k < h) {
+            sr[j][v] = *reinterpret_cast<const float2*>(s_row[j] + k); si[j][v] = *reinterpret_cast<const float2*>(s_row[j] + h + k);
+            rr[j][v] = *reinterpret_cast<const float2*>(r_row[j] + k); ri[j][v] = *reinterpret_cast<const float2*>(r_row[j] + h + k);
+            dr[j][v] = *reinterpret_cast<const float2*>(d_row[j] + k); di[j][v] = *reinterpret_cast<const float2*>(d_row[j] + h + k);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PREP_EDGES; ++j) {
+        if (e0 + j < a.n) {
+          float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e0 + j) * dk;
+          float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e0 + j) * dk;
+#pragma unroll
+          for (int v = 0; v < NV; ++v) {
+            const int k = 2 * (l + GL * v);
+            if (k < h) {
+              const float2 ure = make_float2(sr[j][v].x * rr[j][v].x - si[j][v].x * ri[j][v].x, sr[j][v].y * rr[j][v].y - si[j][v].y * ri[j][v].y);
+              const float2 uim = make_float2(sr[j][v].x * ri[j][v].x + si[j][v].x * rr[j][v].x, sr[j][v].y * ri[j][v].y + si[j][v].y * rr[j][v].y);
+              const float2 wre = make_float2(rr[j][v].x * dr[j][v].x + ri[j][v].x * di[j][v].x, rr[j][v].y * dr[j][v].y + ri[j][v].y * di[j][v].y);
+              const float2 wim = make_float2(rr[j][v].x * di[j][v].x - ri[j][v].x * dr[j][v].x, rr[j][v].y * di[j][v].y - ri[j][v].y * dr[j][v].y);
+              acc[j] += (ure.x * dr[j][v].x + uim.x * di[j][v].x) + (ure.y * dr[j][v].y + uim.y * di[j][v].y);
+              *reinterpret_cast<float2*>(qd + k) = ure; *reinterpret_cast<float2*>(qd + h + k) = uim;
+              *reinterpret_cast<float2*>(qs + k) = wre; *reinterpret_cast<float2*>(qs + h + k) = wim;
+            }
+          }
+        }
       }
     } else if (VEC) {
-      for (int k = 4 * l; k < dim; k += 4 * GL) {
-        const float4 s = *reinterpret_cast<const float4*>(s_row + k), d = *reinterpret_cast<const float4*>(d_row + k);
-        float4 r = make_float4(0.f, 0.f, 0.f, 0.f), u, w;
-        if (a.model != MAR_MODEL_DOT) r = *reinterpret_cast<const float4*>(r_row + k);
-        if (a.model == MAR_MODEL_DISTMULT) {
-          u = make_float4(s.x * r.x, s.y * r.y, s.z * r.z, s.w * r.w);
-          w = make_float4(r.x * d.x, r.y * d.y, r.z * d.z, r.w * d.w);
-          acc += (u.x * d.x + u.y * d.y) + (u.z * d.z + u.w * d.w);
-        } else if (a.model == MAR_MODEL_DOT) {
-          u = s; w = d;
-          acc += (s.x * d.x + s.y * d.y) + (s.z * d.z + s.w * d.w);
-        } else {
-          u = make_float4(s.x + r.x, s.y + r.y, s.z + r.z, s.w + r.w);
-          w = make_float4(d.x - r.x, d.y - r.y, d.z - r.z, d.w - r.w);
-          const float4 df = make_float4(u.x - d.x, u.y - d.y, u.z - d.z, u.w - d.w);
-          acc += (df.x * df.x + df.y * df.y) + (df.z * df.z + df.w * df.w);
-          nd += (u.x * u.x + u.y * u.y) + (u.z * u.z + u.w * u.w);
-          ns += (w.x * w.x + w.y * w.y) + (w.z * w.z + w.w * w.w);
+      float4 s4[PREP_EDGES][NV], r4[PREP_EDGES][NV], d4[PREP_EDGES][NV];
+#pragma unroll
+      for (int j = 0; j < PREP_EDGES; ++j) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int k = 4 * (l + GL * v);
+          if (k < dim) {
+            s4[j][v] = *reinterpret_cast<const float4*>(s_row[j] + k); d4[j][v] = *reinterpret_cast<const float4*>(d_row[j] + k);
+            r4[j][v] = MODEL == MAR_MODEL_DOT ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(r_row[j] + k);
+          }
         }
-        *reinterpret_cast<float4*>(qd + k) = u; *reinterpret_cast<float4*>(qs + k) = w;
       }
-    } else if (a.model == MAR_MODEL_COMPLEX) {
-      const int h = dim >> 1;
-      for (int k = l; k < h; k += GL) {
-        const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
-        const float ure = sr * rr - si * ri, uim = sr * ri + si * rr;
-        const float wre = rr * dr + ri * di, wim = rr * di - ri * dr;
-        acc += ure * dr + uim * di;
-        qd[k] = ure; qd[h + k] = uim; qs[k] = wre; qs[h + k] = wim;
+#pragma unroll
+      for (int j = 0; j < PREP_EDGES; ++j) {
+        if (e0 + j < a.n) {
+          float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e0 + j) * dk;
+          float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e0 + j) * dk;
+#pragma unroll
+          for (int v = 0; v < NV; ++v) {
+            const int k = 4 * (l + GL * v);
+            if (k < dim) {
+              const float4 s = s4[j][v], r = r4[j][v], d = d4[j][v];
+              float4 u, w;
+              if (MODEL == MAR_MODEL_DISTMULT) {
+                u = make_float4(s.x * r.x, s.y * r.y, s.z * r.z, s.w * r.w);
+                w = make_float4(r.x * d.x, r.y * d.y, r.z * d.z, r.w * d.w);
+                acc[j] += (u.x * d.x + u.y * d.y) + (u.z * d.z + u.w * d.w);
+              } else if (MODEL == MAR_MODEL_DOT) {
+                u = s; w = d;
+                acc[j] += (s.x * d.x + s.y * d.y) + (s.z * d.z + s.w * d.w);
+              } else {
+                u = make_float4(s.x + r.x, s.y + r.y, s.z + r.z, s.w + r.w);
+                w = make_float4(d.x - r.x, d.y - r.y, d.z - r.z, d.w - r.w);
+                const float4 df = make_float4(u.x - d.x, u.y - d.y, u.z - d.z, u.w - d.w);
+                acc[j] += (df.x * df.x + df.y * df.y) + (df.z * df.z + df.w * df.w);
+                nd[j] += (u.x * u.x + u.y * u.y) + (u.z * u.z + u.w * u.w);
+                ns[j] += (w.x * w.x + w.y * w.y) + (w.z * w.z + w.w * w.w);
+              }
+              *reinterpret_cast<float4*>(qd + k) = u; *reinterpret_cast<float4*>(qs + k) = w;
+            }
+          }
+        }
       }
     } else {
-      for (int k = l; k < dim; k += GL) {
-        const float s = s_row[k], r = r_row[k], d = d_row[k];
-        float u, w;
-        if (a.model == MAR_MODEL_DISTMULT) { u = s * r; w = r * d; acc += u * d; }
-        else if (a.model == MAR_MODEL_DOT) { u = s; w = d; acc += s * d; }
-        else { u = s + r; w = d - r; const float df = u - d; acc += df * df; nd += u * u; ns += w * w; }
-        qd[k] = u; qs[k] = w;
+      for (int j = 0; j < PREP_EDGES; ++j) {
+        if (e0 + j >= a.n) break;
+        float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e0 + j) * dk;
+        float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e0 + j) * dk;
+        if (MODEL == MAR_MODEL_COMPLEX) {
+          const int h = dim >> 1;
+          for (int k = l; k < h; k += GL) {
+            const float sr = s_row[j][k], si = s_row[j][h + k], rr = r_row[j][k], ri = r_row[j][h + k], dr = d_row[j][k], di = d_row[j][h + k];
+            const float ure = sr * rr - si * ri, uim = sr * ri + si * rr;
+            const float wre = rr * dr + ri * di, wim = rr * di - ri * dr;
+            acc[j] += ure * dr + uim * di;
+            qd[k] = ure; qd[h + k] = uim; qs[k] = wre; qs[h + k] = wim;
+          }
+        } else {
+          for (int k = l; k < dim; k += GL) {
+            const float s = s_row[j][k], r = MODEL == MAR_MODEL_DOT ? 0.f : r_row[j][k], d = d_row[j][k];
+            float u, w;
+            if (MODEL == MAR_MODEL_DISTMULT) { u = s * r; w = r * d; acc[j] += u * d; }
+            else if (MODEL == MAR_MODEL_DOT) { u = s; w = d; acc[j] += s * d; }
+            else { u = s + r; w = d - r; const float df = u - d; acc[j] += df * df; nd[j] += u * u; ns[j] += w * w; }
+            qd[k] = u; qs[k] = w;
+          }
+        }
+        for (int k = dim + l; k < dk; k += GL) { qd[k] = 0.f; qs[k] = 0.f; }
       }
     }
-    for (int k = dim + l; k < dk; k += GL) { qd[k] = 0.f; qs[k] = 0.f; }
-    acc = group_sum<GL>(acc);
-    if (a.model == MAR_MODEL_TRANSE) {
-      nd = group_sum<GL>(nd); ns = group_sum<GL>(ns);
-      acc = -sqrtf(acc);
-      if (l == 0) { qq[(size_t)MAR_SIDE_DST * a.B + e] = nd; qq[(size_t)MAR_SIDE_SRC * a.B + e] = ns; }
+#pragma unroll
+    for (int j = 0; j < PREP_EDGES; ++j) {
+      const int e = e0 + j;
+      float sc = group_sum<GL>(acc[j]);
+      if (MODEL == MAR_MODEL_TRANSE) {
+        const float sd = group_sum<GL>(nd[j]), ss = group_sum<GL>(ns[j]);
+        sc = -sqrtf(sc);
+        if (l == 0 && e < a.n) { qq[(size_t)MAR_SIDE_DST * a.B + e] = sd; qq[(size_t)MAR_SIDE_SRC * a.B + e] = ss; }
+      }
+      if (l == 0 && e < a.n) { pos[e] = sc; if (pos_user) pos_user[e] = sc; }
     }
-    if (l == 0) { pos[e] = acc; if (pos_user) pos_user[e] = acc; }
     return;
   }
   {
-    const int rr = (blk - nbB) * GPB + grp;                // row among 2*cn negatives
-    if (rr >= 2 * a.cn) return;
-    const int side = rr >= a.cn ? MAR_SIDE_DST : MAR_SIDE_SRC;
-    const int cj = rr - (side == MAR_SIDE_DST ? a.cn : 0);  // chunk*N + j
-    const int32_t id = side == MAR_SIDE_DST ? a.neg_dst[cj] : a.neg_src[cj];
-    const float* row = a.node_emb + (size_t)id * dim;
-    const size_t krow = (size_t)side * a.C * a.N + cj;
-    float* out = Km + krow * dk;
-    float nn = 0.f;
+    const int rr0 = ((blk - nbB) * GPB + grp) * PREP_NEGS;       // first row among the 2*cn negatives
+    if (rr0 >= 2 * a.cn) return;
+    const float* row[PREP_NEGS];
+    size_t krow[PREP_NEGS];
+#pragma unroll
+    for (int j = 0; j < PREP_NEGS; ++j) {
+      const int rr = min(rr0 + j, 2 * a.cn - 1);
+      const int side = rr >= a.cn ? MAR_SIDE_DST : MAR_SIDE_SRC;
+      const int cj = rr - (side == MAR_SIDE_DST ? a.cn : 0);    // chunk*N + j
+      const int32_t id = side == MAR_SIDE_DST ? a.neg_dst[cj] : a.neg_src[cj];
+      row[j] = a.node_emb + (size_t)id * dim;
+      krow[j] = (size_t)side * a.C * a.N + cj;
+    }
     if (VEC) {
-      for (int k = 4 * l; k < dim; k += 4 * GL) {
-        const float4 v = *reinterpret_cast<const float4*>(row + k);
-        nn += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-        *reinterpret_cast<float4*>(out + k) = v;
+      float4 v4[PREP_NEGS][NV];
+#pragma unroll
+      for (int j = 0; j < PREP_NEGS; ++j) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int k = 4 * (l + GL * v);
+          if (k < dim) v4[j][v] = *reinterpret_cast<const float4*>(row[j] + k);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PREP_NEGS; ++j) {
+        float nn = 0.f;
+        if (rr0 + j < 2 * a.cn) {
+#pragma unroll
+          for (int v = 0; v < NV; ++v) {
+            const int k = 4 * (l + GL * v);
+            if (k < dim) {
+              const float4 x = v4[j][v];
+              nn += (x.x * x.x + x.y * x.y) + (x.z * x.z + x.w * x.w);
+              *reinterpret_cast<float4*>(Km + krow[j] * dk + k) = x;
+            }
+          }
+        }
+        if (MODEL == MAR_MODEL_TRANSE) {
+          nn = group_sum<GL>(nn);
+          if (l == 0 && rr0 + j < 2 * a.cn) kk[krow[j]] = nn;
+        }
       }
     } else {
-      for (int k = l; k < dk; k += GL) {
-        const float v = k < dim ? row[k] : 0.f;
-        nn += v * v;
-        out[k] = v;
+      for (int j = 0; j < PREP_NEGS; ++j) {
+        float nn = 0.f;
+        if (rr0 + j < 2 * a.cn) {
+          for (int k = l; k < dk; k += GL) {
+            const float x = k < dim ? row[j][k] : 0.f;
+            nn += x * x;
+            Km[krow[j] * dk + k] = x;
+          }
+        }
+        if (MODEL == MAR_MODEL_TRANSE) {
+          nn = group_sum<GL>(nn);
+          if (l == 0 && rr0 + j < 2 * a.cn) kk[krow[j]] = nn;
+        }
       }
-    }
-    if (a.model == MAR_MODEL_TRANSE) {
-      nn = group_sum<GL>(nn);
-      if (l == 0) kk[krow] = nn;
     }
   }
 }
@@ -142,96 +244,182 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
 // ------------------------------------------------------------------ chain rule -----
 // From the gradients w.r.t. the two edge-side operands (gq_dst w.r.t. the DST-side q, gq_src
 // w.r.t. the SRC-side q) and the positive term -2 f(e) to gradient rows of s, r, d, written at
-// the occurrences' row-sorted positions.  Also the per-edge loss terms, summed per block in a
-// fixed order.
-template <int GL>
-__global__ void __launch_bounds__(256, 8)
+// the occurrences' fixed places.  Also the per-edge loss terms, summed per block in a fixed order.
+//
+// Pass 1 leaves, per part p of a stripe, the softmax reference m_p, the sum l_p and the unnormalised
+// O_p = sum_j exp(a_j - m_p) n_j.  merge_parts turns them into the log-sum-exp and one factor per part,
+// fac_p = exp(m_p - m) / l with m = max m_p and l = sum_p l_p exp(m_p - m), so that gq = sum_p fac_p O_p.
+#define MAR_MAX_PARTS 8
+
+__device__ __forceinline__ float merge_parts(const float* __restrict__ ml, size_t row, size_t part_rows, int sy1,
+                                             float (&fac)[MAR_MAX_PARTS]) {
+  const float2* __restrict__ p2 = reinterpret_cast<const float2*>(ml) + row;
+  float2 v[MAR_MAX_PARTS];
+#pragma unroll
+  for (int p = 0; p < MAR_MAX_PARTS; ++p) v[p] = p < sy1 ? p2[p * part_rows] : make_float2(-3.0e38f, 0.f);
+  float mx = v[0].x;
+#pragma unroll
+  for (int p = 1; p < MAR_MAX_PARTS; ++p) mx = fmaxf(mx, v[p].x);
+  float ls = 0.f;
+#pragma unroll
+  for (int p = 0; p < MAR_MAX_PARTS; ++p) { fac[p] = __expf(v[p].x - mx); ls += fac[p] * v[p].y; }
+  const float il = 1.f / ls;
+#pragma unroll
+  for (int p = 0; p < MAR_MAX_PARTS; ++p) fac[p] *= il;
+  return mx + logf(ls);
+}
+
+// Chain rule of one element: from s, r, d, the merged operand gradients u (DST side) and w (SRC side).
+template <int MODEL>
+__device__ __forceinline__ void chain1(float s, float r, float d, float u, float w, float inv2, float& gs, float& gd, float& gr) {
+  if (MODEL == MAR_MODEL_DISTMULT) {
+    gs = r * (u - 2.f * d); gd = r * (w - 2.f * s); gr = s * u + d * w - 2.f * s * d;
+  } else if (MODEL == MAR_MODEL_DOT) {
+    gs = u - 2.f * d; gd = w - 2.f * s; gr = 0.f;
+  } else {                                               // TransE: inv2 = 2 / distance (0 at distance 0)
+    const float dl = (s + r - d) * inv2;                 // 2 * unit(s + r - d)
+    gs = u + dl; gr = u - w + dl; gd = w - dl;
+  }
+}
+
+// ComplEx, one complex element: g_s = conj(r) (gU - 2 d), g_d = r (gW - 2 s), g_r = conj(s) gU + conj(gW) d - 2 conj(s) d.
+__device__ __forceinline__ void chain_complex(float sr, float si, float rr, float ri, float dr, float di, float ure, float uim,
+                                              float wre, float wim, float& gsr, float& gsi, float& gdr, float& gdi,
+                                              float& grr, float& gri) {
+  const float zr = ure - 2.f * dr, zi = uim - 2.f * di;
+  gsr = rr * zr + ri * zi;  gsi = rr * zi - ri * zr;
+  const float yr = wre - 2.f * sr, yi = wim - 2.f * si;
+  gdr = rr * yr - ri * yi;  gdi = rr * yi + ri * yr;
+  grr = sr * ure + si * uim + wre * dr + wim * di - 2.f * (sr * dr + si * di);
+  gri = sr * uim - si * ure + wre * di - wim * dr - 2.f * (sr * di - si * dr);
+}
+
+// One group of GL lanes per edge.  VEC (dim % 4 == 0): a lane moves NV float4s per row (for ComplEx NV float2s of
+// the real half and the matching float2s of the imaginary half), every load of the edge is issued before the
+// first use; SY1 > 0: pass 1 was split into exactly SY1 parts (1 for the large batch shapes), SY1 = 0: a.sy1 parts.
+template <int GL, int NV, int MODEL, bool VEC, int SY1>
+__global__ void __launch_bounds__(256)
 k_chain(RowArgs a, const float* __restrict__ gQ, const float* __restrict__ ml, const float* __restrict__ pos,
         float* __restrict__ lse, float* __restrict__ G, float* __restrict__ loss_part) {
   constexpr int GPB = 256 / GL;
-  constexpr int MAXP = 8;
+  constexpr int P = SY1 ? SY1 : MAR_MAX_PARTS;
   __shared__ float lsum[GPB];
-  __shared__ float fac[GPB][2][MAXP];          // per edge and side: exp(m_p - m) / l for each part p
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
   const int e = blockIdx.x * GPB + grp;
   const int dim = a.dim, dk = a.dk;
+  const int sy1 = SY1 ? SY1 : a.sy1;
   const size_t part_rows = (size_t)2 * a.B;
   float le = 0.f;
-  // Merge the parts of the online softmax: part p holds (m_p, l_p) and O_p = sum_j exp(a_j - m_p) n_j.
-  if (e < a.n && l < 2) {
-    const int side = l == 0 ? MAR_SIDE_DST : MAR_SIDE_SRC;
-    const size_t row = (size_t)side * a.B + e;
-    float mx = -3.0e38f;
-    for (int p = 0; p < a.sy1; ++p) mx = fmaxf(mx, ml[(p * part_rows + row) * 2]);
-    float ls = 0.f;
-    for (int p = 0; p < a.sy1; ++p) {
-      const float f = __expf(ml[(p * part_rows + row) * 2] - mx);
-      fac[grp][l][p] = f;
-      ls += f * ml[(p * part_rows + row) * 2 + 1];
-    }
-    const float il = 1.f / ls;
-    for (int p = 0; p < a.sy1; ++p) fac[grp][l][p] *= il;
-    lse[row] = mx + logf(ls);
-  }
-  __syncthreads();
   if (e < a.n) {
-    const float* gu0 = gQ + ((size_t)MAR_SIDE_DST * a.B + e) * dk;
-    const float* gw0 = gQ + ((size_t)MAR_SIDE_SRC * a.B + e) * dk;
+    // every lane of the group merges the parts of both sides (same addresses: one broadcast load each)
+    float facu[MAR_MAX_PARTS], facw[MAR_MAX_PARTS];
+    const size_t row_u = (size_t)MAR_SIDE_DST * a.B + e, row_w = (size_t)MAR_SIDE_SRC * a.B + e;
+    const float lse_u = merge_parts(ml, row_u, part_rows, sy1, facu);
+    const float lse_w = merge_parts(ml, row_w, part_rows, sy1, facw);
+    const float pe = pos[e];
+    if (l == 0) { lse[row_u] = lse_u; lse[row_w] = lse_w; }
+    le = -2.f * pe + lse_u + lse_w;
+    const float* gu0 = gQ + row_u * dk;
+    const float* gw0 = gQ + row_w * dk;
     const size_t pstride = part_rows * dk;
-    const float* fu = fac[grp][0];
-    const float* fw = fac[grp][1];
-    auto merged = [&](const float* base, const float* f, int k) {
-      float v = 0.f;
-#pragma unroll 1
-      for (int p = 0; p < a.sy1; ++p) v += f[p] * base[p * pstride + k];
-      return v;
-    };
     const float* s_row = a.node_emb + (size_t)a.src[e] * dim;
-    const float* r_row = a.rel_emb + (size_t)(a.model == MAR_MODEL_DOT ? 0 : a.rel[e]) * dim;
+    const float* r_row = a.rel_emb + (size_t)(MODEL == MAR_MODEL_DOT ? 0 : a.rel[e]) * dim;
     const float* d_row = a.node_emb + (size_t)a.dst[e] * dim;
     float* gs = G + (size_t)e * dk;                              // gradient row of occurrence k is row k
     float* gd = G + ((size_t)a.n + e) * dk;
     float* gr = G + (2 * (size_t)a.n + e) * dk;
-    if (a.model == MAR_MODEL_COMPLEX) {
+    float inv2 = 0.f;
+    if (MODEL == MAR_MODEL_TRANSE) { const float dist = -pe; inv2 = dist > 0.f ? 2.f / dist : 0.f; }
+    if (VEC && MODEL == MAR_MODEL_COMPLEX) {
       const int h = dim >> 1;
-      for (int k = l; k < h; k += GL) {
-        const float sr = s_row[k], si = s_row[h + k], rr = r_row[k], ri = r_row[h + k], dr = d_row[k], di = d_row[h + k];
-        const float ure = merged(gu0, fu, k), uim = merged(gu0, fu, h + k);
-        const float wre = merged(gw0, fw, k), wim = merged(gw0, fw, h + k);
-        // g_s = conj(r) (gU - 2 d);  g_d = r (gW - 2 s)
-        const float zr = ure - 2.f * dr, zi = uim - 2.f * di;
-        gs[k] = rr * zr + ri * zi;  gs[h + k] = rr * zi - ri * zr;
-        const float yr = wre - 2.f * sr, yi = wim - 2.f * si;
-        gd[k] = rr * yr - ri * yi;  gd[h + k] = rr * yi + ri * yr;
-        // g_r = conj(s) gU + conj(gW) d - 2 conj(s) d
-        gr[k]     = sr * ure + si * uim + wre * dr + wim * di - 2.f * (sr * dr + si * di);
-        gr[h + k] = sr * uim - si * ure + wre * di - wim * dr - 2.f * (sr * di - si * dr);
+      float2 sr[NV], si[NV], rr[NV], ri[NV], dr[NV], di[NV], ur[NV], ui[NV], wr[NV], wi[NV];
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int k = 2 * (l + GL * v);
+        if (k < h) {
+          sr[v] = *reinterpret_cast<const float2*>(s_row + k); si[v] = *reinterpret_cast<const float2*>(s_row + h + k);
+          rr[v] = *reinterpret_cast<const float2*>(r_row + k); ri[v] = *reinterpret_cast<const float2*>(r_row + h + k);
+          dr[v] = *reinterpret_cast<const float2*>(d_row + k); di[v] = *reinterpret_cast<const float2*>(d_row + h + k);
+          ur[v] = ui[v] = wr[v] = wi[v] = make_float2(0.f, 0.f);
+#pragma unroll
+          for (int p = 0; p < P; ++p) {
+            if (SY1 || p < sy1) {
+              const float2 a0 = *reinterpret_cast<const float2*>(gu0 + p * pstride + k), a1 = *reinterpret_cast<const float2*>(gu0 + p * pstride + h + k);
+              const float2 b0 = *reinterpret_cast<const float2*>(gw0 + p * pstride + k), b1 = *reinterpret_cast<const float2*>(gw0 + p * pstride + h + k);
+              ur[v].x += facu[p] * a0.x; ur[v].y += facu[p] * a0.y; ui[v].x += facu[p] * a1.x; ui[v].y += facu[p] * a1.y;
+              wr[v].x += facw[p] * b0.x; wr[v].y += facw[p] * b0.y; wi[v].x += facw[p] * b1.x; wi[v].y += facw[p] * b1.y;
+            }
+          }
+        }
       }
-    } else if (a.model == MAR_MODEL_DOT) {
-      for (int k = l; k < dim; k += GL) {
-        gs[k] = merged(gu0, fu, k) - 2.f * d_row[k];
-        gd[k] = merged(gw0, fw, k) - 2.f * s_row[k];
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int k = 2 * (l + GL * v);
+        if (k < h) {
+          float2 osr, osi, odr, odi, orr, ori;
+          chain_complex(sr[v].x, si[v].x, rr[v].x, ri[v].x, dr[v].x, di[v].x, ur[v].x, ui[v].x, wr[v].x, wi[v].x, osr.x, osi.x, odr.x, odi.x, orr.x, ori.x);
+          chain_complex(sr[v].y, si[v].y, rr[v].y, ri[v].y, dr[v].y, di[v].y, ur[v].y, ui[v].y, wr[v].y, wi[v].y, osr.y, osi.y, odr.y, odi.y, orr.y, ori.y);
+          *reinterpret_cast<float2*>(gs + k) = osr; *reinterpret_cast<float2*>(gs + h + k) = osi;
+          *reinterpret_cast<float2*>(gd + k) = odr; *reinterpret_cast<float2*>(gd + h + k) = odi;
+          *reinterpret_cast<float2*>(gr + k) = orr; *reinterpret_cast<float2*>(gr + h + k) = ori;
+        }
       }
-    } else if (a.model == MAR_MODEL_DISTMULT) {
-      for (int k = l; k < dim; k += GL) {
-        const float s = s_row[k], r = r_row[k], d = d_row[k], u = merged(gu0, fu, k), w = merged(gw0, fw, k);
-        gs[k] = r * (u - 2.f * d);
-        gd[k] = r * (w - 2.f * s);
-        gr[k] = s * u + d * w - 2.f * s * d;
+    } else if (VEC) {
+      float4 s4[NV], r4[NV], d4[NV], u4[NV], w4[NV];
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int k = 4 * (l + GL * v);
+        if (k < dim) {
+          s4[v] = *reinterpret_cast<const float4*>(s_row + k); d4[v] = *reinterpret_cast<const float4*>(d_row + k);
+          r4[v] = MODEL == MAR_MODEL_DOT ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(r_row + k);
+          u4[v] = w4[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+          for (int p = 0; p < P; ++p) {
+            if (SY1 || p < sy1) {
+              const float4 a0 = *reinterpret_cast<const float4*>(gu0 + p * pstride + k), b0 = *reinterpret_cast<const float4*>(gw0 + p * pstride + k);
+              u4[v].x += facu[p] * a0.x; u4[v].y += facu[p] * a0.y; u4[v].z += facu[p] * a0.z; u4[v].w += facu[p] * a0.w;
+              w4[v].x += facw[p] * b0.x; w4[v].y += facw[p] * b0.y; w4[v].z += facw[p] * b0.z; w4[v].w += facw[p] * b0.w;
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int k = 4 * (l + GL * v);
+        if (k < dim) {
+          float4 os, od, og;
+          chain1<MODEL>(s4[v].x, r4[v].x, d4[v].x, u4[v].x, w4[v].x, inv2, os.x, od.x, og.x);
+          chain1<MODEL>(s4[v].y, r4[v].y, d4[v].y, u4[v].y, w4[v].y, inv2, os.y, od.y, og.y);
+          chain1<MODEL>(s4[v].z, r4[v].z, d4[v].z, u4[v].z, w4[v].z, inv2, os.z, od.z, og.z);
+          chain1<MODEL>(s4[v].w, r4[v].w, d4[v].w, u4[v].w, w4[v].w, inv2, os.w, od.w, og.w);
+          *reinterpret_cast<float4*>(gs + k) = os; *reinterpret_cast<float4*>(gd + k) = od;
+          if (MODEL != MAR_MODEL_DOT) *reinterpret_cast<float4*>(gr + k) = og;
+        }
       }
     } else {
-      const float dist = -pos[e];
-      const float inv2 = dist > 0.f ? 2.f / dist : 0.f;
-      for (int k = l; k < dim; k += GL) {
-        const float dl = (s_row[k] + r_row[k] - d_row[k]) * inv2;     // 2 * unit(s + r - d)
-        const float u = merged(gu0, fu, k), w = merged(gw0, fw, k);
-        gs[k] = u + dl;
-        gr[k] = u - w + dl;
-        gd[k] = w - dl;
+      // any width: one element (ComplEx: one complex element) per lane and step
+      auto merged = [&](const float* base, const float (&f)[MAR_MAX_PARTS], int k) {
+        float v = 0.f;
+#pragma unroll
+        for (int p = 0; p < P; ++p) if (SY1 || p < sy1) v += f[p] * base[p * pstride + k];
+        return v;
+      };
+      if (MODEL == MAR_MODEL_COMPLEX) {
+        const int h = dim >> 1;
+        for (int k = l; k < h; k += GL) {
+          chain_complex(s_row[k], s_row[h + k], r_row[k], r_row[h + k], d_row[k], d_row[h + k], merged(gu0, facu, k), merged(gu0, facu, h + k),
+                        merged(gw0, facw, k), merged(gw0, facw, h + k), gs[k], gs[h + k], gd[k], gd[h + k], gr[k], gr[h + k]);
+        }
+      } else {
+        for (int k = l; k < dim; k += GL) {
+          float os, od, og;
+          chain1<MODEL>(s_row[k], MODEL == MAR_MODEL_DOT ? 0.f : r_row[k], d_row[k], merged(gu0, facu, k), merged(gw0, facw, k), inv2, os, od, og);
+          gs[k] = os; gd[k] = od;
+          if (MODEL != MAR_MODEL_DOT) gr[k] = og;
+        }
       }
+      for (int k = dim + l; k < dk; k += GL) { gs[k] = 0.f; gd[k] = 0.f; if (MODEL != MAR_MODEL_DOT) gr[k] = 0.f; }
     }
-    for (int k = dim + l; k < dk; k += GL) { gs[k] = 0.f; gd[k] = 0.f; if (a.roles == 3) gr[k] = 0.f; }
-    le = -2.f * pos[e] + lse[(size_t)MAR_SIDE_DST * a.B + e] + lse[(size_t)MAR_SIDE_SRC * a.B + e];
   }
   if (l == 0) lsum[grp] = le;
   __syncthreads();
@@ -395,6 +583,7 @@ __global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
   constexpr int GPB = 256 / GL;
   __shared__ float4 s_head[GPB][GL * NV], s_tail[GPB][GL * NV];
   __shared__ int s_hs[GPB], s_tf[GPB];       // head: 0 none, 1 ends inside the task, 2 runs through it; tail: 0 / 1
+  __shared__ int s_fin[GPB];                 // the head slot of this task holds a finished sum (set by the chaining step)
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
   const int64_t P0 = (int64_t)blockIdx.x * MAR_REDUCE_BLOCK;
   const int64_t p0 = P0 + (int64_t)grp * GL;
@@ -481,10 +670,13 @@ __global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
       for (int v = 0; v < NV; ++v) (tf ? s_tail : s_head)[grp][l + GL * v] = acc[v];
     }
   }
-  if (l == 0) { s_hs[grp] = hs; s_tf[grp] = tf; }
+  if (l == 0) { s_hs[grp] = hs; s_tf[grp] = tf; s_fin[grp] = 0; }
   __syncthreads();
 
-  // chain the tasks' partial sums: thread q owns column block q
+  // Chain the tasks' partial sums in task order: thread q owns column block q and walks the tasks (LDS only).
+  // A segment that ends inside the workgroup and also began inside it leaves its sum in the head slot of the
+  // task it ends in (s_fin marks it); those sums are then turned into Adagrad updates by all lane groups at
+  // once -- group g takes task g -- so that their table reads do not queue up behind one another.
   const int q = threadIdx.x;
   float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
   bool active = false, inside = false;                     // a segment is open / it began inside this workgroup
@@ -495,10 +687,8 @@ __global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
       if (active) add4(run, hv); else { run = hv; active = true; inside = false; }
       if (h == 1) {
         if (inside) {
-          const int rank = a.rank_sorted[P0 + (int64_t)gi * GL];
-          float *emb, *st;
-          table_rows(a, a.uniq[rank], emb, st);
-          if (q < nq) adagrad4<VEC>(a, emb, st, rank, 4 * q, run, load_row4<VEC>(emb, 4 * q, a.dim), load_row4<VEC>(st, 4 * q, a.dim));
+          if (q < nq) s_head[gi][q] = run;
+          if (q == 0) s_fin[gi] = 1;
         } else if (q < nq) {
           *reinterpret_cast<float4*>(a.carry + ((size_t)blockIdx.x * 2 + 0) * a.dk + 4 * q) = run;
         }
@@ -514,34 +704,45 @@ __global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
     if (q < nq) *reinterpret_cast<float4*>(a.carry + ((size_t)blockIdx.x * 2 + (inside ? 1 : 0)) * a.dk + 4 * q) = run;
     if (inside && threadIdx.x == 0) a.owners[atomicAdd(&a.scalars[2], 1)] = (int32_t)blockIdx.x;
   }
+  __syncthreads();
+  if (s_fin[grp]) {                                        // uniform over the lane group
+    const int rank = __shfl(my_rank, 0, GL);               // the segment that ends in task grp is the one its first position belongs to
+    float *emb, *st;
+    table_rows(a, __shfl(my_id, 0, GL), emb, st);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int qq = l + GL * v;
+      if (qq < nq) adagrad4<VEC>(a, emb, st, rank, 4 * qq, s_head[grp][qq], load_row4<VEC>(emb, 4 * qq, a.dim), load_row4<VEC>(st, 4 * qq, a.dim));
+    }
+  }
 }
 
-// Finishes the segments that span several workgroups of k_reduce_apply: a workgroup takes an entry of
-// `owners` (in any order: every entry is a different table row), adds that block's slot-1 partial and
-// the slot-0 partials of the following blocks up to the segment's end -- wave w takes every fourth,
+// Finishes the segments that span several workgroups of k_reduce_apply: a workgroup of SPAN_WAVES waves takes an
+// entry of `owners` (in any order: every entry is a different table row), adds that block's slot-1 partial
+// and the slot-0 partials of the following blocks up to the segment's end -- wave w takes every SPAN_WAVES-th,
 // FB at a time, then the waves' sums are combined through LDS in wave order: a fixed tree -- and applies
 // the Adagrad update.  Block 0 first adds up the per-block loss terms, also in a fixed order.
+#define SPAN_WAVES 16
 template <int NV, bool VEC>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * SPAN_WAVES)
 k_span_apply(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part, float* __restrict__ loss_out) {
-  __shared__ float4 part[4][64 * NV];
+  constexpr int NT = 64 * SPAN_WAVES;
+  __shared__ float4 part[SPAN_WAVES][64 * NV];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (blockIdx.x == 0 && loss_out) {                        // uniform over the workgroup
-    // thread t adds terms t, t + 256, ... (four independent running sums so that loads overlap), then
-    // lanes, then the four waves in order
-    __shared__ float wsum4[4];
-    float t4[4] = {0.f, 0.f, 0.f, 0.f};
-    int i = threadIdx.x;
-    for (; i + 768 < n_loss_part; i += 1024) {
-      t4[0] += loss_part[i]; t4[1] += loss_part[i + 256]; t4[2] += loss_part[i + 512]; t4[3] += loss_part[i + 768];
-    }
-    for (; i < n_loss_part; i += 256) t4[0] += loss_part[i];
-    float t = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+    // thread t adds terms t, t + NT, ..., then lanes, then the waves in order
+    __shared__ float wsum[SPAN_WAVES];
+    float t = 0.f;
+    for (int i = threadIdx.x; i < n_loss_part; i += NT) t += loss_part[i];
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) t += __shfl_xor(t, o);
-    if (lane == 0) wsum4[wave] = t;
+    if (lane == 0) wsum[wave] = t;
     __syncthreads();
-    if (threadIdx.x == 0) *loss_out = (wsum4[0] + wsum4[1]) + (wsum4[2] + wsum4[3]);
+    if (threadIdx.x == 0) {
+      float s = 0.f;
+      for (int w = 0; w < SPAN_WAVES; ++w) s += wsum[w];
+      *loss_out = s;
+    }
   }
   const int nq = a.dk >> 2;
   const int n_owners = a.scalars[2];
@@ -558,12 +759,12 @@ k_span_apply(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part,
       acc[v] = (wave == 0 && q < nq) ? *reinterpret_cast<const float4*>(a.carry + ((size_t)blk * 2 + 1) * a.dk + 4 * q)
                                      : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    constexpr int FB = 8;                                   // partial rows in flight per wave
-    for (int64_t t = blk + 1 + wave; t <= last_blk; t += 4 * FB) {
+    constexpr int FB = 4;                                   // partial rows in flight per wave
+    for (int64_t t = blk + 1 + wave; t <= last_blk; t += SPAN_WAVES * FB) {
       float4 rows[FB][NV];
 #pragma unroll
       for (int j = 0; j < FB; ++j) {
-        const int64_t tt = t + 4 * j;
+        const int64_t tt = t + SPAN_WAVES * j;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
           const int q = lane + 64 * v;
@@ -589,7 +790,7 @@ k_span_apply(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part,
         const int q = lane + 64 * v;
         if (q < nq) {
           float4 s = part[0][q];
-          for (int w = 1; w < 4; ++w) add4(s, part[w][q]);
+          for (int w = 1; w < SPAN_WAVES; ++w) add4(s, part[w][q]);
           adagrad4<VEC>(a, emb, st, rank, 4 * q, s, load_row4<VEC>(emb, 4 * q, a.dim), load_row4<VEC>(st, 4 * q, a.dim));
         }
       }
@@ -613,13 +814,23 @@ hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, 
   const MarLayout& L = c->L;
   RowArgs a = row_args(c, b);
   const int GL = mar_lane_group(a.dk), gpb = 256 / GL;
-  const int nbB = (b.n + gpb - 1) / gpb;
-  const int nbC = (2 * b.cn + gpb - 1) / gpb;
+  const int nbB = (b.n + gpb * PREP_EDGES - 1) / (gpb * PREP_EDGES);
+  const int nbC = (2 * b.cn + gpb * PREP_NEGS - 1) / (gpb * PREP_NEGS);
   const dim3 grid(nbB + nbC), blk(256);
-#define PREP(GLV, V) hipLaunchKernelGGL((k_prep<GLV, V>), grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
-  if (a.dim % 4 == 0) { if (GL == 16) PREP(16, true); else if (GL == 32) PREP(32, true); else PREP(64, true); }
-  else { if (GL == 16) PREP(16, false); else if (GL == 32) PREP(32, false); else PREP(64, false); }
+#define PREP3(GLV, NVV, V, M) hipLaunchKernelGGL((k_prep<GLV, NVV, V, M>), grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
+#define PREP(GLV, NVV, V) do { switch (a.model) { \
+    case MAR_MODEL_DISTMULT: PREP3(GLV, NVV, V, MAR_MODEL_DISTMULT); break; \
+    case MAR_MODEL_COMPLEX: PREP3(GLV, NVV, V, MAR_MODEL_COMPLEX); break; \
+    case MAR_MODEL_TRANSE: PREP3(GLV, NVV, V, MAR_MODEL_TRANSE); break; \
+    default: PREP3(GLV, NVV, V, MAR_MODEL_DOT); break; } } while (0)
+  // lanes x float4s per lane cover a row (ComplEx: lanes x float2s cover half a row)
+  if (a.dim % 4 == 0) {
+    if (GL == 16) PREP(16, 1, true); else if (GL == 32) PREP(32, 1, true); else if (a.dk <= 256) PREP(64, 1, true); else PREP(64, 2, true);
+  } else {
+    if (GL == 16) PREP(16, 1, false); else if (GL == 32) PREP(32, 1, false); else PREP(64, 1, false);
+  }
 #undef PREP
+#undef PREP3
   return hipGetLastError();
 }
 
@@ -636,14 +847,34 @@ hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t*
   return hipGetLastError();
 }
 
+template <int GL, int NV, int MODEL>
+static void launch_chain(const RowArgs& a, const MarLayout& L, dim3 grid, hipStream_t st) {
+#define CHAIN(V, S) hipLaunchKernelGGL((k_chain<GL, NV, MODEL, V, S>), grid, dim3(256), 0, st, a, L.gQ, L.ml, L.pos, L.lse, L.G, L.loss_part)
+  if (a.dim % 4 == 0) { if (a.sy1 == 1) CHAIN(true, 1); else if (a.sy1 == 2) CHAIN(true, 2); else CHAIN(true, 0); }
+  else CHAIN(false, 0);
+#undef CHAIN
+}
+
+template <int GL, int NV>
+static void launch_chain_model(const RowArgs& a, const MarLayout& L, dim3 grid, hipStream_t st) {
+  switch (a.model) {
+    case MAR_MODEL_DISTMULT: launch_chain<GL, NV, MAR_MODEL_DISTMULT>(a, L, grid, st); break;
+    case MAR_MODEL_COMPLEX:  launch_chain<GL, NV, MAR_MODEL_COMPLEX>(a, L, grid, st); break;
+    case MAR_MODEL_TRANSE:   launch_chain<GL, NV, MAR_MODEL_TRANSE>(a, L, grid, st); break;
+    default:                 launch_chain<GL, NV, MAR_MODEL_DOT>(a, L, grid, st); break;
+  }
+}
+
 hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
   const MarLayout& L = c->L;
   RowArgs a = row_args(c, b);
   const int GL = mar_lane_group(a.dk), gpb = 256 / GL;
-  const dim3 grid((b.n + gpb - 1) / gpb), blk(256);
-#define CHAIN(GLV) hipLaunchKernelGGL(k_chain<GLV>, grid, blk, 0, st, a, L.gQ, L.ml, L.pos, L.lse, L.G, L.loss_part)
-  if (GL == 16) CHAIN(16); else if (GL == 32) CHAIN(32); else CHAIN(64);
-#undef CHAIN
+  const dim3 grid((b.n + gpb - 1) / gpb);
+  // lanes x float4s per lane cover a row (ComplEx: lanes x float2s cover half a row)
+  if (GL == 16) launch_chain_model<16, 1>(a, L, grid, st);
+  else if (GL == 32) launch_chain_model<32, 1>(a, L, grid, st);
+  else if (a.dk <= 256) launch_chain_model<64, 1>(a, L, grid, st);
+  else launch_chain_model<64, 2>(a, L, grid, st);
   return hipGetLastError();
 }
 
@@ -656,7 +887,7 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
   a.scalars = L.scalars; a.owners = L.owners; a.dbg_grad = dbg_grad; a.n_rows = b.n_pos;
   a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk; a.lr = c->cfg.lr; a.eps = c->cfg.eps;
   const int64_t blocks = (b.n_pos + MAR_REDUCE_BLOCK - 1) / MAR_REDUCE_BLOCK;
-  const dim3 grid((unsigned)blocks), grids((unsigned)(blocks < 1024 ? blocks : 1024)), blk(256);
+  const dim3 grid((unsigned)blocks), grids((unsigned)(blocks < 512 ? blocks : 512)), blk(256), blks(64 * SPAN_WAVES);
   const int GL = mar_lane_group(d.dk), gpb = 256 / GL;
   const int n_loss_part = (b.n + gpb - 1) / gpb;
   const bool vec = d.dim % 4 == 0;
@@ -666,11 +897,11 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
   if (GL == 16) RED(16, 1, 8); else if (GL == 32) RED(32, 1, 8); else if (d.dk <= 256) RED(64, 1, 8); else RED(64, 2, 4);
 #undef RED
   if (d.dk <= 256) {
-    if (vec) hipLaunchKernelGGL((k_span_apply<1, true>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
-    else hipLaunchKernelGGL((k_span_apply<1, false>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    if (vec) hipLaunchKernelGGL((k_span_apply<1, true>), grids, blks, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    else hipLaunchKernelGGL((k_span_apply<1, false>), grids, blks, 0, st, a, L.loss_part, n_loss_part, loss_out);
   } else {
-    if (vec) hipLaunchKernelGGL((k_span_apply<2, true>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
-    else hipLaunchKernelGGL((k_span_apply<2, false>), grids, blk, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    if (vec) hipLaunchKernelGGL((k_span_apply<2, true>), grids, blks, 0, st, a, L.loss_part, n_loss_part, loss_out);
+    else hipLaunchKernelGGL((k_span_apply<2, false>), grids, blks, 0, st, a, L.loss_part, n_loss_part, loss_out);
   }
   return hipGetLastError();
 }
