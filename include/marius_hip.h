@@ -148,7 +148,8 @@ int mar_eval_scores(mar_ctx* ctx, const int32_t* src, const int32_t* rel, const 
  *     rank_dst[i] -= #{k : f(s, r, dst_ids[k]) > f(s, r, d)},   rank_src[i] likewise.
  * Scores are evaluated per candidate on the vector ALU in the same operation order as the positive score
  * (a candidate equal to the edge's own endpoint never counts); the ranks from mar_eval_scores come from the
- * matrix cores, so a candidate within rounding of the positive can be counted on one side and not the other.
+ * matrix cores, so a candidate within rounding of the positive can be counted on one side and not the other;
+ * a filtered rank never goes below 1.
  *   dst_off, src_off : device, [n_edges + 1] int64, non-decreasing, off[0] = 0
  *   dst_ids, src_ids : device, node ids
  *   pos_scores       : device, [n_edges], as written by mar_eval_scores

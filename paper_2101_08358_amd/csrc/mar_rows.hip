@@ -508,7 +508,13 @@ k_filter(RowArgs a, const int64_t* __restrict__ dst_off, const int32_t* __restri
                                          : group_score<GL, VEC>(a.model, dim, c_row, r_row, d_row, l);
     better += f > p ? 1 : 0;
   }
-  if (l == 0 && better) (side == MAR_SIDE_DST ? rank_dst : rank_src)[e] -= better;
+  // The unfiltered rank comes from the matrix cores, this count from the vector ALU: a candidate within rounding
+  // of the edge's score can be counted here and not there, so the difference is kept at 1 or above.
+  if (l == 0 && better) {
+    int32_t* rk = (side == MAR_SIDE_DST ? rank_dst : rank_src) + e;
+    const int32_t v = *rk - better;
+    *rk = v < 1 ? 1 : v;
+  }
 }
 
 // ------------------------------------------------- per-row reduce + Adagrad scatter -----
