@@ -16,7 +16,8 @@
 // throughput is ~20 flop per HBM byte on this chip while recomputing a score costs 2d flops,
 // so k_flash_bwd reads them back instead of multiplying again and runs only the second product,
 // with the roles of Q and K swapped.  Evaluation (PASS 3) only counts negatives scoring above
-// the positive.  TransE uses |q - n|^2 = |q|^2 + |n|^2 - 2 q.n for the scores and W = P / distance.
+// the positive.  TransE uses |q - n|^2 = |q|^2 + |n|^2 - 2 q.n for the scores (pairs for which that expansion
+// cancels are recomputed from the differences) and W = P / distance.
 #include <type_traits>
 
 #include "mar_common.h"
@@ -351,13 +352,56 @@ k_flash(FlashArgs a) {
       for (int b = 0; b < XB; ++b) {
         float sc[4], dist[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          sc[r] = tacc[b][r];
-          if (L2) {
-            const float d2 = fmaxf(xnorm[b] + yy4[r] - 2.f * tacc[b][r], 0.f);
-            dist[r] = sqrtf(d2);
-            sc[r] = -dist[r];
+        for (int r = 0; r < 4; ++r) sc[r] = tacc[b][r];
+        if (L2) {
+          // |q - n|^2 = |q|^2 + |n|^2 - 2 q.n cancels when n is close to q: its rounding error is of the size of
+          // 2^-22 (|q|^2 + |n|^2).  Pairs whose expanded value falls below 2^-8 of that sum (the expansion is
+          // then left with fewer than ~14 good bits) are recomputed from the differences q_k - n_k themselves:
+          // the four lanes that hold the fragments of stationary row m each sum their own columns of the
+          // streamed row, one flagged pair of the column at a time (rare: the loop is skipped by the whole wave
+          // when nothing is flagged).
+          float d2[4];
+          unsigned flags = 0u;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float sum2 = xnorm[b] + yy4[r];
+            d2[r] = fmaxf(sum2 - 2.f * tacc[b][r], 0.f);
+            if (d2[r] < 0.00390625f * sum2) flags |= 1u << r;
           }
+          if (__any(flags != 0u)) {
+            unsigned F = flags << (4 * g);                 // bit 4 g' + r: streamed row yb*16 + 4 g' + r against stationary row m
+            F |= __shfl_xor(F, 16);
+            F |= __shfl_xor(F, 32);
+            while (__any(F != 0u)) {
+              const int idx = F ? __ffs(F) - 1 : 0;
+              const float* yfix = &tile[(yb * 16 + idx) * PITCH];
+              float part = 0.f;
+              if (F) {
+#pragma unroll
+                for (int s2 = 0; s2 < N16; ++s2) {
+                  if (16 * s2 + 4 * g < dk) {
+                    const float4 yv = *reinterpret_cast<const float4*>(yfix + 16 * s2 + 4 * g);
+                    const float e0 = xf[b][4 * s2 + 0] - yv.x, e1 = xf[b][4 * s2 + 1] - yv.y;
+                    const float e2 = xf[b][4 * s2 + 2] - yv.z, e3 = xf[b][4 * s2 + 3] - yv.w;
+                    part += (e0 * e0 + e1 * e1) + (e2 * e2 + e3 * e3);
+                  }
+                }
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                  if (16 * N16 + 4 * j + g < dk) { const float e0 = xf[b][4 * N16 + j] - yfix[16 * N16 + 4 * j + g]; part += e0 * e0; }
+                }
+              }
+              part += __shfl_xor(part, 16);
+              part += __shfl_xor(part, 32);
+              if (F && (idx >> 2) == g) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) if ((idx & 3) == r) d2[r] = part;
+              }
+              F &= F - 1u;
+            }
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) { dist[r] = sqrtf(d2[r]); sc[r] = -dist[r]; }
         }
         if (PASS == 1) {
           // keep the raw scores for the negatives' gradient pass: row = edge, 4 consecutive negatives.  The
