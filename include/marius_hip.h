@@ -211,6 +211,39 @@ int64_t mar_swap_lower_bound(int32_t p, int32_t c);
 int64_t mar_beta_swap_count(int32_t p, int32_t c);
 
 /*
+ * Training with the node table outside device memory (Sec. 3: "Pipelined training architecture" and "Bounded
+ * Staleness").  The node embeddings and their Adagrad accumulators live in pinned host memory that the GPU can
+ * address (hipHostMalloc); relation tables stay in device memory.  A batch passes through three stages on three
+ * streams -- in: unique set of the batch and staging of its node rows into a compact device table; step: gather,
+ * scores, loss and gradients on the staged rows, relation rows updated at once (relations are never stale); out:
+ * Adagrad on the host table with the batch's summed node gradients -- and up to `depth` batches are in flight.
+ * The stages are ordered so that batch j reads the node table after the updates of batches 0 .. j - depth and
+ * before the update of batch j - depth + 1: every run has the same staleness of exactly depth - 1 batches, and
+ * depth = 1 reproduces mar_train_batch bit for bit.  A batch's node gradient is applied to whatever the host table
+ * holds when its turn comes (updates are applied in batch order).
+ *   host_node_emb, host_node_state : [num_nodes * dim] floats in pinned, device-accessible host memory
+ *   rel_emb, rel_state             : device, [num_rels * dim]
+ *   workspace                      : device, >= mar_pipe_workspace_bytes(cfg, depth), 256-byte aligned
+ *   depth                          : 1 .. MAR_PIPE_MAX_DEPTH batches in flight
+ * mar_pipe_submit enqueues one batch (arguments as mar_train_batch, n_edges >= 1).  The id arrays are copied by the
+ * first stage, which waits for the work enqueued so far on ids_stream (the stream that wrote them; hip_stream itself
+ * is allowed, but then the staging of a batch also waits for the step of the batch before it and nothing overlaps);
+ * they may be reused once hip_stream has passed this call.  loss_sum_out receives the batch's loss on hip_stream.  mar_pipe_drain enqueues the updates
+ * still outstanding and makes hip_stream wait for them: after it, work on hip_stream sees the final host tables.
+ * Between the first submit and the drain the host tables must not be touched by anyone else.
+ */
+#define MAR_PIPE_MAX_DEPTH 32
+typedef struct mar_pipe mar_pipe;
+int mar_pipe_workspace_bytes(const mar_config* cfg, int32_t depth, size_t* out_bytes);
+int mar_pipe_create(const mar_config* cfg, float* host_node_emb, float* host_node_state, float* rel_emb,
+                    float* rel_state, void* workspace, size_t workspace_bytes, int32_t depth, void* hip_stream,
+                    mar_pipe** out);
+int mar_pipe_submit(mar_pipe* pipe, const int32_t* src, const int32_t* rel, const int32_t* dst, int32_t n_edges,
+                    const int32_t* neg_src, const int32_t* neg_dst, float* loss_sum_out, void* ids_stream, void* hip_stream);
+int mar_pipe_drain(mar_pipe* pipe, void* hip_stream);
+int mar_pipe_destroy(mar_pipe* pipe);
+
+/*
  * Per-phase device timing of mar_train_batch with HIP events on the stream each phase runs on
  * (phases 0 and 4 run on the context's second stream beside phases 1-3, so the six times
  * overlap and do not add up to the step time).

@@ -7,5 +7,6 @@ from .binding import (MarConfig, MarDebugOut, MODEL_DISTMULT, MODEL_COMPLEX, MOD
                       mar_sample_negatives, mar_train_batch, mar_eval_scores, mar_eval_filter, mar_rank_metrics, mar_rank_metrics_static,
                       mar_beta_buffer_sequence,
                       mar_beta_edge_bucket_order, mar_buffer_simulate, mar_swap_lower_bound, mar_beta_swap_count,
+                      mar_pipe_workspace_bytes, mar_pipe_create, mar_pipe_submit, mar_pipe_drain, mar_pipe_destroy,
                       mar_profile_enable,
                       mar_profile_read, mar_destroy, mar_last_error, Trainer)

@@ -39,6 +39,7 @@ class MarDebugOut(ctypes.Structure):
 EXPORTS = ("mar_workspace_bytes", "mar_init_tables", "mar_sample_negatives", "mar_train_batch", "mar_eval_scores",
            "mar_eval_filter", "mar_rank_metrics", "mar_rank_metrics_static", "mar_beta_buffer_sequence", "mar_beta_edge_bucket_order", "mar_buffer_simulate",
            "mar_swap_lower_bound", "mar_beta_swap_count",
+           "mar_pipe_workspace_bytes", "mar_pipe_create", "mar_pipe_submit", "mar_pipe_drain", "mar_pipe_destroy",
            "mar_profile_enable", "mar_profile_read", "mar_destroy", "mar_last_error")
 
 
@@ -70,6 +71,11 @@ def load_library():
     lib.mar_buffer_simulate.argtypes = [i32, i32, vp, i64, ctypes.POINTER(i64)]
     lib.mar_swap_lower_bound.argtypes = [i32, i32]
     lib.mar_beta_swap_count.argtypes = [i32, i32]
+    lib.mar_pipe_workspace_bytes.argtypes = [ctypes.POINTER(MarConfig), i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.mar_pipe_create.argtypes = [ctypes.POINTER(MarConfig), vp, vp, vp, vp, vp, ctypes.c_size_t, i32, vp, ctypes.POINTER(vp)]
+    lib.mar_pipe_submit.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.mar_pipe_drain.argtypes = [vp, vp]
+    lib.mar_pipe_destroy.argtypes = [vp]
     lib.mar_profile_enable.argtypes = [vp, i32, ctypes.c_uint32]
     lib.mar_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.mar_destroy.argtypes = [vp]
@@ -190,6 +196,33 @@ def mar_buffer_simulate(p, c, pairs):
     loads = ctypes.c_int64(0)
     _check(load_library().mar_buffer_simulate(p, c, arr.ctypes.data, arr.shape[0], ctypes.byref(loads)))
     return loads.value
+
+
+def mar_pipe_workspace_bytes(cfg, depth):
+    out = ctypes.c_size_t(0)
+    _check(load_library().mar_pipe_workspace_bytes(ctypes.byref(cfg), int(depth), ctypes.byref(out)))
+    return out.value
+
+
+def mar_pipe_create(cfg, host_node_emb, host_node_state, rel_emb, rel_state, workspace, workspace_bytes, depth, stream=None):
+    pipe = ctypes.c_void_p(None)
+    _check(load_library().mar_pipe_create(ctypes.byref(cfg), _ptr(host_node_emb), _ptr(host_node_state), _ptr(rel_emb),
+                                          _ptr(rel_state), _ptr(workspace), workspace_bytes, int(depth), _stream(stream),
+                                          ctypes.byref(pipe)))
+    return pipe
+
+
+def mar_pipe_submit(pipe, src, rel, dst, n_edges, neg_src, neg_dst, loss_sum_out=None, ids_stream=None, stream=None):
+    _check(load_library().mar_pipe_submit(pipe, _ptr(src), _ptr(rel), _ptr(dst), int(n_edges), _ptr(neg_src), _ptr(neg_dst),
+                                          _ptr(loss_sum_out), _stream(ids_stream), _stream(stream)))
+
+
+def mar_pipe_drain(pipe, stream=None):
+    _check(load_library().mar_pipe_drain(pipe, _stream(stream)))
+
+
+def mar_pipe_destroy(pipe):
+    _check(load_library().mar_pipe_destroy(pipe))
 
 
 def mar_profile_enable(ctx, max_steps, phase_mask=(1 << NUM_PHASES) - 1):

@@ -282,7 +282,7 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   HIP_TRY(hipStreamWaitEvent(st, c->ev_index, 0), "join");
   HIP_TRY(hipStreamWaitEvent(st, c->ev_chain, 0), "join");
   MARK(5, 0, st);
-  HIP_TRY(mar_launch_reduce(c, b, loss_sum_out, dbg ? dbg->grad_rows : nullptr, st), "reduce/Adagrad kernels");
+  HIP_TRY(mar_launch_reduce(c, b, loss_sum_out, dbg ? dbg->grad_rows : nullptr, nullptr, st), "reduce/Adagrad kernels");
   MARK(5, 1, st);
 #undef MARK
   if (ev) c->prof_steps++;
@@ -333,6 +333,211 @@ extern "C" int mar_rank_metrics(mar_ctx* c, const int32_t* ranks, int64_t n_rank
   if (num_k < 0 || num_k > 8 || (num_k > 0 && !ks)) return fail(MAR_ERANGE, "num_k outside 0..8 or ks NULL");
   for (int j = 0; j < num_k; ++j) if (ks[j] < 1) return fail(MAR_EINVAL, "thresholds must be >= 1");
   HIP_TRY(mar_launch_rank_metrics(ranks, n_ranks, ks, num_k, out, c->L.metric_part, (hipStream_t)hip_stream), "metrics kernel");
+  return MAR_OK;
+}
+
+// ------------------------------------------------------- out-of-memory pipelined training -----
+// Sec. 3: node embeddings and their optimiser state live outside device memory; a batch goes through
+//   in   : unique set + staging of its node rows into a compact device table          (stream s_in)
+//   step : gather / score / loss / backward on the staged rows, relation rows updated  (caller's stream)
+//   out  : Adagrad on the host table with the batch's summed node gradients            (stream s_out)
+// and up to `depth` batches are in flight.  Events order the stages so that batch j stages its rows after the
+// updates of batches <= j - depth and before the update of batch j - depth + 1: the staleness is exactly
+// depth - 1 batches in every run.
+struct PipeSlot {
+  mar_ctx* ctx;                // context over the compact table (node_emb = compact) and the resident relation tables
+  MarStage sg;
+  int32_t *src, *rel, *dst, *neg_src, *neg_dst;    // the slot's copy of the batch's ids
+  MarBatch b_ids, b_rank;      // the batch over real ids (index build) and over ranks (gather, chain rule)
+  hipEvent_t ev_in, ev_step, ev_out;
+};
+
+struct mar_pipe {
+  mar_config cfg; MarDims dm;
+  int32_t depth;
+  float *host_emb, *host_state, *rel_emb, *rel_state;
+  hipStream_t s_in, s_out;
+  hipEvent_t ev_call;
+  PipeSlot* slots;
+  int64_t submitted, applied;  // batches submitted / batches whose update has been enqueued
+};
+
+static size_t pipe_slot_extra(const MarDims& d, char* base, PipeSlot* ps) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> void* {
+    void* p = base ? base + off : nullptr;
+    off += (bytes + 255) & ~(size_t)255;
+    return p;
+  };
+  const size_t B = d.B, CN = (size_t)d.C * d.N;
+  const size_t rows = (size_t)(2 * B + 2 * CN < (size_t)d.num_nodes ? 2 * B + 2 * CN : (size_t)d.num_nodes);
+  PipeSlot t;
+  t.sg.compact = (float*)take(rows * d.dim * 4 + 16);
+  t.sg.gsum = (float*)take((size_t)d.u_max * d.dk * 4);
+  t.sg.c_src = (int32_t*)take(B * 4); t.sg.c_dst = (int32_t*)take(B * 4);
+  t.sg.c_neg_dst = (int32_t*)take(CN * 4); t.sg.c_neg_src = (int32_t*)take(CN * 4);
+  t.src = (int32_t*)take(B * 4); t.rel = (int32_t*)take(B * 4); t.dst = (int32_t*)take(B * 4);
+  t.neg_src = (int32_t*)take(CN * 4); t.neg_dst = (int32_t*)take(CN * 4);
+  if (ps) { ps->sg.compact = t.sg.compact; ps->sg.gsum = t.sg.gsum; ps->sg.c_src = t.sg.c_src; ps->sg.c_dst = t.sg.c_dst;
+            ps->sg.c_neg_dst = t.sg.c_neg_dst; ps->sg.c_neg_src = t.sg.c_neg_src; ps->src = t.src; ps->rel = t.rel; ps->dst = t.dst;
+            ps->neg_src = t.neg_src; ps->neg_dst = t.neg_dst; }
+  return off;
+}
+
+static int pipe_check(const mar_config* cfg, int32_t depth, MarDims* d) {
+  const int rc = check_config(cfg, d);
+  if (rc) return rc;
+  if (depth < 1 || depth > MAR_PIPE_MAX_DEPTH) return fail(MAR_ERANGE, "depth %d outside 1..%d", depth, MAR_PIPE_MAX_DEPTH);
+  return MAR_OK;
+}
+
+extern "C" int mar_pipe_workspace_bytes(const mar_config* cfg, int32_t depth, size_t* out_bytes) {
+  MarDims d;
+  const int rc = pipe_check(cfg, depth, &d);
+  if (rc) return rc;
+  if (!out_bytes) return fail(MAR_EINVAL, "out_bytes is NULL");
+  *out_bytes = (size_t)depth * (carve(d, nullptr, nullptr) + pipe_slot_extra(d, nullptr, nullptr));
+  return MAR_OK;
+}
+
+extern "C" int mar_pipe_destroy(mar_pipe* p) {
+  if (!p) return MAR_OK;
+  if (p->s_in) { (void)hipStreamSynchronize(p->s_in); (void)hipStreamDestroy(p->s_in); }
+  if (p->s_out) { (void)hipStreamSynchronize(p->s_out); (void)hipStreamDestroy(p->s_out); }
+  if (p->ev_call) (void)hipEventDestroy(p->ev_call);
+  if (p->slots) {
+    for (int i = 0; i < p->depth; ++i) {
+      hipEvent_t evs[3] = {p->slots[i].ev_in, p->slots[i].ev_step, p->slots[i].ev_out};
+      for (int k = 0; k < 3; ++k) if (evs[k]) (void)hipEventDestroy(evs[k]);
+      mar_destroy(p->slots[i].ctx);
+    }
+    delete[] p->slots;
+  }
+  delete p;
+  return MAR_OK;
+}
+
+extern "C" int mar_pipe_create(const mar_config* cfg, float* host_node_emb, float* host_node_state, float* rel_emb,
+                               float* rel_state, void* workspace, size_t workspace_bytes, int32_t depth, void* hip_stream,
+                               mar_pipe** out) {
+  MarDims d;
+  const int rc = pipe_check(cfg, depth, &d);
+  if (rc) return rc;
+  if (!out) return fail(MAR_EINVAL, "out is NULL");
+  if (!host_node_emb || !host_node_state || !rel_emb || !rel_state) return fail(MAR_EINVAL, "a table pointer is NULL");
+  if (((uintptr_t)host_node_emb | (uintptr_t)host_node_state | (uintptr_t)rel_emb | (uintptr_t)rel_state) & 15)
+    return fail(MAR_EINVAL, "table pointers must be 16-byte aligned");
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(MAR_EINVAL, "workspace must be non-NULL and 256-byte aligned");
+  // the host tables must be memory the GPU can address; kernels use the device-side alias the runtime reports
+  float* host_tabs[2] = {host_node_emb, host_node_state};
+  for (int i = 0; i < 2; ++i) {
+    hipPointerAttribute_t at;
+    const hipError_t pe = hipPointerGetAttributes(&at, host_tabs[i]);
+    if (pe != hipSuccess) { (void)hipGetLastError(); return fail(MAR_EINVAL, "host table %d is not memory known to the HIP runtime (allocate it pinned)", i); }
+    if (at.type != hipMemoryTypeHost || !at.devicePointer) return fail(MAR_EINVAL, "host table %d is not pinned, device-accessible host memory", i);
+    host_tabs[i] = (float*)at.devicePointer;
+  }
+  host_node_emb = host_tabs[0]; host_node_state = host_tabs[1];
+  const size_t ctx_bytes = carve(d, nullptr, nullptr), extra = pipe_slot_extra(d, nullptr, nullptr);
+  if (workspace_bytes < (size_t)depth * (ctx_bytes + extra))
+    return fail(MAR_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, (size_t)depth * (ctx_bytes + extra));
+  mar_pipe* p = new (std::nothrow) mar_pipe();
+  if (!p) return fail(MAR_ENOMEM, "out of host memory");
+  p->cfg = *cfg; p->dm = d; p->depth = depth;
+  p->host_emb = host_node_emb; p->host_state = host_node_state; p->rel_emb = rel_emb; p->rel_state = rel_state;
+  p->s_in = p->s_out = nullptr; p->ev_call = nullptr; p->submitted = p->applied = 0;
+  p->slots = new (std::nothrow) PipeSlot[depth]();
+  if (!p->slots) { delete p; return fail(MAR_ENOMEM, "out of host memory"); }
+  hipError_t e = hipStreamCreateWithFlags(&p->s_in, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->s_out, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_call, hipEventDisableTiming);
+  char* base = (char*)workspace;
+  for (int i = 0; i < depth && e == hipSuccess; ++i) {
+    PipeSlot& ps = p->slots[i];
+    char* sb = base + (size_t)i * (ctx_bytes + extra);
+    pipe_slot_extra(d, sb + ctx_bytes, &ps);
+    ps.sg.host_emb = host_node_emb; ps.sg.host_state = host_node_state;
+    // the slot's context: the compact table stands in for the node table (no fill; its accumulators are never used)
+    const int rc2 = mar_init_tables(cfg, ps.sg.compact, ps.sg.compact, rel_emb, rel_state, sb, ctx_bytes, 0, hip_stream, &ps.ctx);
+    if (rc2) { mar_pipe_destroy(p); return rc2; }
+    hipEvent_t* evs[3] = {&ps.ev_in, &ps.ev_step, &ps.ev_out};
+    for (int k = 0; k < 3 && e == hipSuccess; ++k) e = hipEventCreateWithFlags(evs[k], hipEventDisableTiming);
+  }
+  if (e != hipSuccess) { mar_pipe_destroy(p); return hip_fail(e, "pipeline set-up"); }
+  *out = p;
+  return MAR_OK;
+}
+
+__global__ void __launch_bounds__(256)
+k_copy_ids(const int32_t* __restrict__ s0, const int32_t* __restrict__ r0, const int32_t* __restrict__ d0,
+           const int32_t* __restrict__ ns0, const int32_t* __restrict__ nd0, int n, int cn, int32_t* __restrict__ s1,
+           int32_t* __restrict__ r1, int32_t* __restrict__ d1, int32_t* __restrict__ ns1, int32_t* __restrict__ nd1) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) { s1[i] = s0[i]; d1[i] = d0[i]; if (r0) r1[i] = r0[i]; }
+  if (i < cn) { ns1[i] = ns0[i]; nd1[i] = nd0[i]; }
+}
+
+#define PIPE_TRY(expr, what) do { const hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_, what); } while (0)
+
+// Enqueues the update stage of batch i on s_out; `gather_of` >= 0: it must also wait for the staging of that batch.
+static int pipe_enqueue_update(mar_pipe* p, int64_t i, int64_t gather_of) {
+  PipeSlot& ps = p->slots[i % p->depth];
+  PIPE_TRY(hipStreamWaitEvent(p->s_out, ps.ev_step, 0), "update stage");
+  if (gather_of >= 0) PIPE_TRY(hipStreamWaitEvent(p->s_out, p->slots[gather_of % p->depth].ev_in, 0), "update stage");
+  PIPE_TRY(mar_launch_stage_out(ps.ctx, ps.b_ids, ps.sg, p->s_out), "update kernel");
+  PIPE_TRY(hipEventRecord(ps.ev_out, p->s_out), "update stage");
+  p->applied = i + 1;
+  return MAR_OK;
+}
+
+extern "C" int mar_pipe_submit(mar_pipe* p, const int32_t* src, const int32_t* rel, const int32_t* dst, int32_t n_edges,
+                               const int32_t* neg_src, const int32_t* neg_dst, float* loss_sum_out, void* ids_stream,
+                               void* hip_stream) {
+  if (!p) return fail(MAR_EINVAL, "pipeline is NULL");
+  if (n_edges < 1) return fail(MAR_EINVAL, "n_edges must be >= 1");
+  const int64_t j = p->submitted;
+  PipeSlot& ps = p->slots[j % p->depth];
+  mar_ctx* c = ps.ctx;
+  int rc = make_batch(c, src, rel, dst, n_edges, neg_src, neg_dst, &ps.b_ids);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int roles = c->dm.roles;
+  // ---- in: after the work enqueued so far on the stream the ids come from, and after the update of the batch that
+  // used this slot before (batch j - depth: its buffers are free, and its update is the newest one batch j may see)
+  PIPE_TRY(hipEventRecord(p->ev_call, (hipStream_t)ids_stream), "submit");
+  PIPE_TRY(hipStreamWaitEvent(p->s_in, p->ev_call, 0), "submit");
+  if (j >= p->depth) PIPE_TRY(hipStreamWaitEvent(p->s_in, ps.ev_out, 0), "stage in");
+  const int work = n_edges > ps.b_ids.cn ? n_edges : ps.b_ids.cn;
+  hipLaunchKernelGGL(k_copy_ids, dim3((work + 255) / 256), dim3(256), 0, p->s_in, src, roles == 3 ? rel : nullptr, dst, neg_src, neg_dst,
+                     n_edges, ps.b_ids.cn, ps.src, ps.rel, ps.dst, ps.neg_src, ps.neg_dst);
+  PIPE_TRY(hipGetLastError(), "id copy");
+  ps.b_ids.src = ps.src; ps.b_ids.rel = ps.rel; ps.b_ids.dst = ps.dst; ps.b_ids.neg_src = ps.neg_src; ps.b_ids.neg_dst = ps.neg_dst;
+  ps.b_rank = ps.b_ids;
+  ps.b_rank.src = ps.sg.c_src; ps.b_rank.dst = ps.sg.c_dst; ps.b_rank.neg_src = ps.sg.c_neg_src; ps.b_rank.neg_dst = ps.sg.c_neg_dst;
+  if (c->bitmap_dirty) { PIPE_TRY(mar_launch_clear_bitmap(c, p->s_in), "bitmap reset"); c->bitmap_dirty = 0; }
+  PIPE_TRY(mar_launch_index(c, ps.b_ids, p->s_in), "index kernels");
+  PIPE_TRY(mar_launch_stage_in(c, ps.b_ids, ps.sg, p->s_in), "staging kernels");
+  PIPE_TRY(hipEventRecord(ps.ev_in, p->s_in), "stage in");
+  // ---- step on the caller's stream: staged rows, ranks as ids; node gradients are left in gsum, relation rows updated
+  PIPE_TRY(hipStreamWaitEvent(st, ps.ev_in, 0), "step");
+  PIPE_TRY(mar_launch_prep(c, ps.b_rank, nullptr, st), "gather kernel");
+  PIPE_TRY(mar_launch_flash(c, ps.b_rank, 1, nullptr, nullptr, st), "score/softmax kernel");
+  PIPE_TRY(mar_launch_chain(c, ps.b_rank, st), "chain-rule kernel");
+  PIPE_TRY(mar_launch_flash(c, ps.b_rank, 2, nullptr, nullptr, st), "negative-gradient kernel");
+  PIPE_TRY(mar_launch_reduce(c, ps.b_ids, loss_sum_out, nullptr, ps.sg.gsum, st), "reduce kernels");
+  PIPE_TRY(hipEventRecord(ps.ev_step, st), "step");
+  p->submitted = j + 1;
+  // ---- out: the update of batch j - depth + 1 goes behind this batch's staging
+  const int64_t i = j - p->depth + 1;
+  if (i >= 0) { rc = pipe_enqueue_update(p, i, j); if (rc) return rc; }
+  return MAR_OK;
+}
+
+extern "C" int mar_pipe_drain(mar_pipe* p, void* hip_stream) {
+  if (!p) return fail(MAR_EINVAL, "pipeline is NULL");
+  for (int64_t i = p->applied; i < p->submitted; ++i) { const int rc = pipe_enqueue_update(p, i, -1); if (rc) return rc; }
+  if (p->submitted > 0)
+    PIPE_TRY(hipStreamWaitEvent((hipStream_t)hip_stream, p->slots[(p->submitted - 1) % p->depth].ev_out, 0), "drain");
   return MAR_OK;
 }
 

@@ -117,7 +117,16 @@ hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st)
 hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t* dst_off, const int32_t* dst_ids,
                              const int64_t* src_off, const int32_t* src_ids, const float* pos, int32_t* rank_dst,
                              int32_t* rank_src, hipStream_t st);
-hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st);
+hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, float* defer_grad, hipStream_t st);
+
+// Staging buffers of one batch of out-of-memory training (see mar_rows.hip).
+struct MarStage {
+  float *host_emb, *host_state;                      // node table and accumulators in pinned host memory
+  float *compact, *gsum;                             // [unique rows][dim] staged rows, [unique rows][dk] summed gradients
+  int32_t *c_src, *c_dst, *c_neg_dst, *c_neg_src;    // the batch's node ids replaced by ranks
+};
+hipError_t mar_launch_stage_in(const mar_ctx* c, const MarBatch& b, const MarStage& sg, hipStream_t st);
+hipError_t mar_launch_stage_out(const mar_ctx* c, const MarBatch& b, const MarStage& sg, hipStream_t st);
 hipError_t mar_launch_debug_copy(const mar_ctx* c, const MarBatch& b, const mar_debug_out* dbg, hipStream_t st);
 hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_t* ks, int num_k, double* out, void* part,
                                    hipStream_t st);

@@ -532,6 +532,8 @@ struct ReduceArgs {
   int32_t* scalars;          // [2] = number of entries in `owners`
   int32_t* owners;           // blocks in which a segment begins that continues into later blocks
   float* dbg_grad;           // [unique rows][dim] summed gradients (debug output), or NULL
+  float* defer_grad;         // [unique rows][dk], or NULL: if set, a node row's summed gradient is stored here and the row is
+                             // left alone (its update is applied later, by k_stage_apply); relation rows are updated as usual
   int64_t n_rows;
   int32_t num_nodes, dim, dk;
   float lr, eps;
@@ -561,17 +563,34 @@ __device__ __forceinline__ void table_rows(const ReduceArgs& a, int32_t id, floa
   else { emb = a.rel_emb + (size_t)(id - a.num_nodes) * a.dim; st = a.rel_state + (size_t)(id - a.num_nodes) * a.dim; }
 }
 
-// state += g^2; theta -= lr * g / (sqrt(state) + eps) on four columns whose old values are th, s0.
-template <bool VEC>
-__device__ __forceinline__ void adagrad4(const ReduceArgs& a, float* __restrict__ emb, float* __restrict__ st, int rank, int col,
-                                         const float4& g, const float4& th, const float4& s0) {
-  float4 s1, e1;
+// state += g^2; theta -= lr * g / (sqrt(state) + eps) on four columns whose old values are th, s0 (Sec. 5.1: Adagrad).
+// The one place where the update is spelled out: every kernel that applies it goes through here.
+__device__ __forceinline__ void adagrad_math(const float4& g, const float4& th, const float4& s0, float lr, float eps, float4& e1, float4& s1) {
   s1.x = s0.x + g.x * g.x; s1.y = s0.y + g.y * g.y; s1.z = s0.z + g.z * g.z; s1.w = s0.w + g.w * g.w;
-  e1.x = th.x - a.lr * g.x / (sqrtf(s1.x) + a.eps); e1.y = th.y - a.lr * g.y / (sqrtf(s1.y) + a.eps);
-  e1.z = th.z - a.lr * g.z / (sqrtf(s1.z) + a.eps); e1.w = th.w - a.lr * g.w / (sqrtf(s1.w) + a.eps);
+  e1.x = th.x - lr * g.x / (sqrtf(s1.x) + eps); e1.y = th.y - lr * g.y / (sqrtf(s1.y) + eps);
+  e1.z = th.z - lr * g.z / (sqrtf(s1.z) + eps); e1.w = th.w - lr * g.w / (sqrtf(s1.w) + eps);
+}
+
+__device__ __forceinline__ bool row_deferred(const ReduceArgs& a, int32_t id) { return a.defer_grad != nullptr && id < a.num_nodes; }
+
+// Finishes a table row whose summed gradient over four columns is g: Adagrad on the row (old values th, s0), or,
+// for a deferred node row, the gradient goes to defer_grad and the table is not touched.
+template <bool VEC>
+__device__ __forceinline__ void adagrad4(const ReduceArgs& a, int32_t id, float* __restrict__ emb, float* __restrict__ st, int rank, int col,
+                                         const float4& g, const float4& th, const float4& s0) {
+  if (a.dbg_grad) store_row4<VEC>(a.dbg_grad + (size_t)rank * a.dim, col, a.dim, g);
+  if (row_deferred(a, id)) { *reinterpret_cast<float4*>(a.defer_grad + (size_t)rank * a.dk + col) = g; return; }
+  float4 s1, e1;
+  adagrad_math(g, th, s0, a.lr, a.eps, e1, s1);
   store_row4<VEC>(st, col, a.dim, s1);
   store_row4<VEC>(emb, col, a.dim, e1);
-  if (a.dbg_grad) store_row4<VEC>(a.dbg_grad + (size_t)rank * a.dim, col, a.dim, g);
+}
+
+// Old values of four columns of a table row; a deferred row is not read.
+template <bool VEC>
+__device__ __forceinline__ void load_old4(const ReduceArgs& a, int32_t id, const float* emb, const float* st, int col, float4& th, float4& s0) {
+  if (row_deferred(a, id)) { th = s0 = make_float4(0.f, 0.f, 0.f, 0.f); return; }
+  th = load_row4<VEC>(emb, col, a.dim); s0 = load_row4<VEC>(st, col, a.dim);
 }
 
 // A workgroup takes MAR_REDUCE_BLOCK consecutive positions, a group of GL lanes GL of them (a "task"; the
@@ -634,7 +653,7 @@ __global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
           const int q = l + GL * v;
-          if (q < nq) { th[j][v] = load_row4<VEC>(emb, 4 * q, a.dim); s0[j][v] = load_row4<VEC>(st, 4 * q, a.dim); }
+          if (q < nq) load_old4<VEC>(a, id, emb, st, 4 * q, th[j][v], s0[j][v]);
         }
       }
     }
@@ -647,12 +666,13 @@ __global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
           const int pj = (i0 + j) & (GL - 1);
           if (kind[j] == 1) {
             float *emb, *st;
-            table_rows(a, __shfl(my_id, pj, GL), emb, st);
+            const int32_t fid = __shfl(my_id, pj, GL);
+            table_rows(a, fid, emb, st);
             const int rank = __shfl(my_rank, pj, GL);
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
               const int q = l + GL * v;
-              if (q < nq) adagrad4<VEC>(a, emb, st, rank, 4 * q, acc[v], th[j][v], s0[j][v]);
+              if (q < nq) adagrad4<VEC>(a, fid, emb, st, rank, 4 * q, acc[v], th[j][v], s0[j][v]);
             }
           } else {
 #pragma unroll
@@ -714,11 +734,16 @@ __global__ void __launch_bounds__(256) k_reduce_apply(ReduceArgs a) {
   if (s_fin[grp]) {                                        // uniform over the lane group
     const int rank = __shfl(my_rank, 0, GL);               // the segment that ends in task grp is the one its first position belongs to
     float *emb, *st;
-    table_rows(a, __shfl(my_id, 0, GL), emb, st);
+    const int32_t fid = __shfl(my_id, 0, GL);
+    table_rows(a, fid, emb, st);
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
       const int qq = l + GL * v;
-      if (qq < nq) adagrad4<VEC>(a, emb, st, rank, 4 * qq, s_head[grp][qq], load_row4<VEC>(emb, 4 * qq, a.dim), load_row4<VEC>(st, 4 * qq, a.dim));
+      if (qq < nq) {
+        float4 th, s0;
+        load_old4<VEC>(a, fid, emb, st, 4 * qq, th, s0);
+        adagrad4<VEC>(a, fid, emb, st, rank, 4 * qq, s_head[grp][qq], th, s0);
+      }
     }
   }
 }
@@ -790,14 +815,122 @@ k_span_apply(ReduceArgs a, const float* __restrict__ loss_part, int n_loss_part,
     __syncthreads();
     if (wave == 0) {
       float *emb, *st;
-      table_rows(a, a.uniq[rank], emb, st);
+      const int32_t fid = a.uniq[rank];
+      table_rows(a, fid, emb, st);
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
         const int q = lane + 64 * v;
         if (q < nq) {
-          float4 s = part[0][q];
+          float4 s = part[0][q], th, s0;
           for (int w = 1; w < SPAN_WAVES; ++w) add4(s, part[w][q]);
-          adagrad4<VEC>(a, emb, st, rank, 4 * q, s, load_row4<VEC>(emb, 4 * q, a.dim), load_row4<VEC>(st, 4 * q, a.dim));
+          load_old4<VEC>(a, fid, emb, st, 4 * q, th, s0);
+          adagrad4<VEC>(a, fid, emb, st, rank, 4 * q, s, th, s0);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------ staging for out-of-memory training -----
+// Training with the node table outside device memory (Sec. 3: the table lives in CPU memory, batches move through
+// gather / transfer / compute / transfer / update stages).  Here the table is pinned host memory that the GPU reads
+// and writes directly; a batch's unique node rows are staged into a compact device table (row = rank of the node
+// among the batch's unique rows), the step runs on that table with ids replaced by ranks, and the summed node
+// gradients are applied to the host table afterwards.
+struct StageArgs {
+  const float* host_emb;     // [num_nodes][dim] pinned host memory, device-accessible
+  float* host_state;         // [num_nodes][dim] (k_stage_apply)
+  float* host_emb_rw;        // same table, writable (k_stage_apply)
+  float* compact;            // [unique rows][dim] device
+  const float* gsum;         // [unique rows][dk] summed gradients per unique row
+  const int32_t* uniq;       // ascending unified ids of the batch's rows: the node ids come first
+  const int32_t* scalars;    // [1] = number of unique nodes
+  const uint32_t* keys0;     // gradient row -> rank
+  int32_t *c_src, *c_dst, *c_neg_dst, *c_neg_src;   // ids replaced by ranks
+  int32_t n, cn, roles, sy2, dim, dk;
+  float lr, eps;
+};
+
+// Ranks in place of node ids, in the layout the step's entry arrays have.
+__global__ void __launch_bounds__(256) k_stage_ids(StageArgs a) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t n3 = (int64_t)a.roles * a.n;
+  if (i < a.n) { a.c_src[i] = (int32_t)a.keys0[i]; a.c_dst[i] = (int32_t)a.keys0[a.n + i]; }
+  if (i < a.cn) {
+    a.c_neg_dst[i] = (int32_t)a.keys0[n3 + i * a.sy2];
+    a.c_neg_src[i] = (int32_t)a.keys0[n3 + ((int64_t)a.cn + i) * a.sy2];
+  }
+}
+
+#define STAGE_ROWS 4   // rows in flight per lane group
+
+// compact[rank] = host table row of the rank-th unique node.  One lane group per STAGE_ROWS rows.
+template <int GL, int NV, bool VEC>
+__global__ void __launch_bounds__(256) k_stage_gather(StageArgs a) {
+  constexpr int GPB = 256 / GL;
+  const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
+  const int un = a.scalars[1];
+  const int r0 = (blockIdx.x * GPB + grp) * STAGE_ROWS;
+  if (r0 >= un) return;
+  float4 v4[STAGE_ROWS][NV];
+#pragma unroll
+  for (int j = 0; j < STAGE_ROWS; ++j) {
+    const float* row = a.host_emb + (size_t)a.uniq[min(r0 + j, un - 1)] * a.dim;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int k = 4 * (l + GL * v);
+      if (k < a.dim) v4[j][v] = load_row4<VEC>(row, k, a.dim);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < STAGE_ROWS; ++j) {
+    if (r0 + j < un) {
+      float* out = a.compact + (size_t)(r0 + j) * a.dim;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int k = 4 * (l + GL * v);
+        if (k < a.dim) store_row4<VEC>(out, k, a.dim, v4[j][v]);
+      }
+    }
+  }
+}
+
+// Adagrad on the host table rows of the batch's unique nodes with the summed gradients the step left in gsum
+// (Sec. 3, last stage: the update is applied to whatever the table holds now, in batch order).
+template <int GL, int NV, bool VEC>
+__global__ void __launch_bounds__(256) k_stage_apply(StageArgs a) {
+  constexpr int GPB = 256 / GL;
+  const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
+  const int un = a.scalars[1];
+  const int r0 = (blockIdx.x * GPB + grp) * STAGE_ROWS;
+  if (r0 >= un) return;
+  float4 th[STAGE_ROWS][NV], s0[STAGE_ROWS][NV], g[STAGE_ROWS][NV];
+  size_t off[STAGE_ROWS];
+#pragma unroll
+  for (int j = 0; j < STAGE_ROWS; ++j) {
+    const int r = min(r0 + j, un - 1);
+    off[j] = (size_t)a.uniq[r] * a.dim;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int k = 4 * (l + GL * v);
+      if (k < a.dim) {
+        th[j][v] = load_row4<VEC>(a.host_emb_rw + off[j], k, a.dim);
+        s0[j][v] = load_row4<VEC>(a.host_state + off[j], k, a.dim);
+        g[j][v] = *reinterpret_cast<const float4*>(a.gsum + (size_t)r * a.dk + k);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < STAGE_ROWS; ++j) {
+    if (r0 + j < un) {
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int k = 4 * (l + GL * v);
+        if (k < a.dim) {
+          float4 e1, s1;
+          adagrad_math(g[j][v], th[j][v], s0[j][v], a.lr, a.eps, e1, s1);
+          store_row4<VEC>(a.host_state + off[j], k, a.dim, s1);
+          store_row4<VEC>(a.host_emb_rw + off[j], k, a.dim, e1);
         }
       }
     }
@@ -884,13 +1017,13 @@ hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st)
   return hipGetLastError();
 }
 
-hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, hipStream_t st) {
+hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_out, float* dbg_grad, float* defer_grad, hipStream_t st) {
   const MarLayout& L = c->L;
   const MarDims& d = c->dm;
   ReduceArgs a;
   a.node_emb = c->node_emb; a.node_state = c->node_state; a.rel_emb = c->rel_emb; a.rel_state = c->rel_state;
   a.G = L.G; a.carry = L.carry; a.rank_sorted = L.rank_sorted; a.perm = L.perm; a.seg_off = L.seg_off; a.uniq = L.uniq;
-  a.scalars = L.scalars; a.owners = L.owners; a.dbg_grad = dbg_grad; a.n_rows = b.n_pos;
+  a.scalars = L.scalars; a.owners = L.owners; a.dbg_grad = dbg_grad; a.defer_grad = defer_grad; a.n_rows = b.n_pos;
   a.num_nodes = (int32_t)d.num_nodes; a.dim = d.dim; a.dk = d.dk; a.lr = c->cfg.lr; a.eps = c->cfg.eps;
   const int64_t blocks = (b.n_pos + MAR_REDUCE_BLOCK - 1) / MAR_REDUCE_BLOCK;
   const dim3 grid((unsigned)blocks), grids((unsigned)(blocks < 512 ? blocks : 512)), blk(256), blks(64 * SPAN_WAVES);
@@ -909,5 +1042,46 @@ hipError_t mar_launch_reduce(const mar_ctx* c, const MarBatch& b, float* loss_ou
     if (vec) hipLaunchKernelGGL((k_span_apply<2, true>), grids, blks, 0, st, a, L.loss_part, n_loss_part, loss_out);
     else hipLaunchKernelGGL((k_span_apply<2, false>), grids, blks, 0, st, a, L.loss_part, n_loss_part, loss_out);
   }
+  return hipGetLastError();
+}
+
+static StageArgs stage_args(const mar_ctx* c, const MarBatch& b, const MarStage& sg) {
+  const MarDims& d = c->dm;
+  StageArgs a;
+  a.host_emb = sg.host_emb; a.host_emb_rw = sg.host_emb; a.host_state = sg.host_state;
+  a.compact = sg.compact; a.gsum = sg.gsum; a.uniq = c->L.uniq; a.scalars = c->L.scalars; a.keys0 = c->L.keys0;
+  a.c_src = sg.c_src; a.c_dst = sg.c_dst; a.c_neg_dst = sg.c_neg_dst; a.c_neg_src = sg.c_neg_src;
+  a.n = b.n; a.cn = b.cn; a.roles = d.roles; a.sy2 = d.sy2; a.dim = d.dim; a.dk = d.dk;
+  a.lr = c->cfg.lr; a.eps = c->cfg.eps;
+  return a;
+}
+
+// most unique nodes a batch can have: the grids of the staging kernels are sized for it, the kernels read the count
+static int64_t stage_rows_max(const mar_ctx* c, const MarBatch& b) {
+  const int64_t occ = 2 * (int64_t)b.n + 2 * (int64_t)b.cn;
+  return occ < c->dm.num_nodes ? occ : c->dm.num_nodes;
+}
+
+#define STAGE_LAUNCH(KERNEL) do { \
+    const int GL = mar_lane_group(a.dk), gpb = 256 / GL; \
+    const dim3 grid((unsigned)((stage_rows_max(c, b) + gpb * STAGE_ROWS - 1) / (gpb * STAGE_ROWS))), blk(256); \
+    const bool vec = a.dim % 4 == 0; \
+    if (GL == 16) { if (vec) hipLaunchKernelGGL((KERNEL<16, 1, true>), grid, blk, 0, st, a); else hipLaunchKernelGGL((KERNEL<16, 1, false>), grid, blk, 0, st, a); } \
+    else if (GL == 32) { if (vec) hipLaunchKernelGGL((KERNEL<32, 1, true>), grid, blk, 0, st, a); else hipLaunchKernelGGL((KERNEL<32, 1, false>), grid, blk, 0, st, a); } \
+    else if (a.dk <= 256) { if (vec) hipLaunchKernelGGL((KERNEL<64, 1, true>), grid, blk, 0, st, a); else hipLaunchKernelGGL((KERNEL<64, 1, false>), grid, blk, 0, st, a); } \
+    else { if (vec) hipLaunchKernelGGL((KERNEL<64, 2, true>), grid, blk, 0, st, a); else hipLaunchKernelGGL((KERNEL<64, 2, false>), grid, blk, 0, st, a); } \
+  } while (0)
+
+hipError_t mar_launch_stage_in(const mar_ctx* c, const MarBatch& b, const MarStage& sg, hipStream_t st) {
+  StageArgs a = stage_args(c, b, sg);
+  const int64_t work = b.n > b.cn ? b.n : b.cn;
+  hipLaunchKernelGGL(k_stage_ids, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, st, a);
+  STAGE_LAUNCH(k_stage_gather);
+  return hipGetLastError();
+}
+
+hipError_t mar_launch_stage_out(const mar_ctx* c, const MarBatch& b, const MarStage& sg, hipStream_t st) {
+  StageArgs a = stage_args(c, b, sg);
+  STAGE_LAUNCH(k_stage_apply);
   return hipGetLastError();
 }
