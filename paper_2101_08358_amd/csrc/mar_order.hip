@@ -28,29 +28,43 @@ uint64_t philox_word01(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint6
   return (uint64_t)c0 | ((uint64_t)c1 << 32);
 }
 
-std::vector<std::vector<int32_t>> buffer_sequence(int p, int c) {
-  std::vector<std::vector<int32_t>> seq;
-  std::vector<int32_t> cur(c), disk;
-  for (int i = 0; i < c; ++i) cur[i] = i;
-  for (int i = c; i < p; ++i) disk.push_back(i);
-  seq.push_back(cur);
-  while (!disk.empty()) {
-    // the leading c-1 partitions stay; every partition on disk passes through the last slot
-    for (size_t i = 0; i < disk.size(); ++i) {
-      std::swap(cur[c - 1], disk[i]);
-      seq.push_back(cur);
-    }
-    // the leading partitions have met every other one: bring in fresh ones
-    size_t n = 0;
-    for (int i = 0; i < c - 1 && (size_t)i < disk.size(); ++i) {
-      cur[i] = disk[i];
-      seq.push_back(cur);
-      ++n;
-    }
-    disk.erase(disk.begin(), disk.begin() + n);
+// The BETA buffer sequence (Alg. 3) as a stream of swaps.  The walk keeps c - 1 "fixed" slots and one "cycling"
+// slot (the last).  A round over the m partitions still outside the buffer is a rotation: each of them passes
+// through the cycling slot in order (m swaps), which leaves the slot holding the last of them and the outside
+// pool holding [what the slot held before, then all but the last of them]; the fixed partitions have then met
+// everybody and the first min(c - 1, m) of the pool take their places one by one (they leave the pool; the
+// partitions they replace are done for good).  visit(slot, incoming) is called once per swap, in order.
+template <class Visit>
+void beta_walk(int p, int c, Visit visit) {
+  std::vector<int32_t> pool(p - c);
+  for (int i = 0; i < p - c; ++i) pool[i] = c + i;
+  int32_t cycling = c - 1;                                   // partition in the cycling slot
+  while (!pool.empty()) {
+    const size_t m = pool.size();
+    for (size_t i = 0; i < m; ++i) visit(c - 1, pool[i]);
+    const int32_t came_last = pool[m - 1];
+    for (size_t i = m - 1; i > 0; --i) pool[i] = pool[i - 1];   // rotate: the slot's old content heads the pool
+    pool[0] = cycling;
+    cycling = came_last;
+    const size_t n = std::min<size_t>((size_t)c - 1, m);
+    for (size_t i = 0; i < n; ++i) visit((int)i, pool[i]);
+    pool.erase(pool.begin(), pool.begin() + n);
   }
-  return seq;
 }
+
+// Who has shared a buffer with whom: one bit row per partition.
+struct MetMatrix {
+  int p; size_t words;
+  std::vector<uint64_t> bits;
+  explicit MetMatrix(int p_) : p(p_), words(((size_t)p_ + 63) / 64), bits(words * (size_t)p_, 0) {}
+  bool test_and_set(int i, int j) {
+    uint64_t& w = bits[(size_t)i * words + ((size_t)j >> 6)];
+    const uint64_t m = 1ull << (j & 63);
+    const bool was = (w & m) != 0;
+    w |= m;
+    return was;
+  }
+};
 
 }  // namespace
 
@@ -69,43 +83,61 @@ extern "C" int64_t mar_beta_swap_count(int32_t p, int32_t c) {
 extern "C" int mar_beta_buffer_sequence(int32_t p, int32_t c, int32_t* buffers, int64_t capacity_rows, int64_t* num_rows) {
   if (c < 2 || p < c) return order_fail(MAR_EINVAL, "need 2 <= c <= p");
   if (!num_rows) return order_fail(MAR_EINVAL, "num_rows is NULL");
-  const auto seq = buffer_sequence(p, c);
-  *num_rows = (int64_t)seq.size();
+  const int64_t rows = mar_beta_swap_count(p, c) + 1;        // one row per swap (Eq. 3) after the first buffer
+  *num_rows = rows;
   if (!buffers) return MAR_OK;                              // size query
-  if (capacity_rows < (int64_t)seq.size()) return order_fail(MAR_ENOMEM, "buffer sequence does not fit");
-  for (size_t r = 0; r < seq.size(); ++r)
-    for (int i = 0; i < c; ++i) buffers[r * c + i] = seq[r][i];
-  return MAR_OK;
+  if (capacity_rows < rows) return order_fail(MAR_ENOMEM, "buffer sequence does not fit");
+  for (int i = 0; i < c; ++i) buffers[i] = i;
+  int64_t r = 0;
+  beta_walk(p, c, [&](int slot, int32_t incoming) {          // row r + 1 = row r with one slot replaced
+    int32_t* next = buffers + (r + 1) * c;
+    std::copy(buffers + r * c, buffers + (r + 1) * c, next);
+    next[slot] = incoming;
+    ++r;
+  });
+  return r + 1 == rows ? MAR_OK : order_fail(MAR_ERANGE, "internal: swap count does not match Eq. 3");
 }
 
 extern "C" int mar_beta_edge_bucket_order(int32_t p, int32_t c, int32_t shuffle, uint64_t seed, int32_t* pairs) {
   if (c < 2 || p < c) return order_fail(MAR_EINVAL, "need 2 <= c <= p");
   if (!pairs) return order_fail(MAR_EINVAL, "pairs is NULL");
   if ((int64_t)p * p > ((int64_t)1 << 30)) return order_fail(MAR_ERANGE, "too many edge buckets");
-  const auto seq = buffer_sequence(p, c);
-  std::vector<uint8_t> seen((size_t)p * p, 0);
-  size_t out = 0;
-  for (size_t b = 0; b < seq.size(); ++b) {
-    const size_t first = out;
-    for (int i : seq[b])
-      for (int j : seq[b])
-        if (!seen[(size_t)i * p + j]) {
-          seen[(size_t)i * p + j] = 1;
-          pairs[2 * out] = i; pairs[2 * out + 1] = j;
-          ++out;
-        }
+  // Alg. 4 asks for every bucket (i, j) the first time both partitions are in the buffer.  After a swap the only
+  // new candidates involve the partition that came in, so each buffer's group is emitted from that partition's
+  // row of the who-met-whom matrix, in the order a row-major scan of the buffer's slots would find them: (x' , x)
+  // for the slots before the swapped one, then (x, .) for all slots, then (x', x) for the slots behind it.
+  MetMatrix met(p);
+  std::vector<int32_t> buf(c);
+  size_t out = 0, buffer_index = 0;
+  auto emit = [&](int32_t i, int32_t j) {
+    if (!met.test_and_set(i, j)) { pairs[2 * out] = i; pairs[2 * out + 1] = j; ++out; }
+  };
+  auto close_group = [&](size_t first) {
     if (shuffle) {
       // Fisher-Yates from the back, j = high 64 bits of x * (k + 1)
       const size_t m = out - first;
       for (size_t k = m; k-- > 1;) {
-        const uint64_t x = philox_word01((uint32_t)k, (uint32_t)b, 0u, 0x40000000u, seed);
+        const uint64_t x = philox_word01((uint32_t)k, (uint32_t)buffer_index, 0u, 0x40000000u, seed);
         const size_t j = (size_t)(((unsigned __int128)x * (k + 1)) >> 64);
         std::swap(pairs[2 * (first + k)], pairs[2 * (first + j)]);
         std::swap(pairs[2 * (first + k) + 1], pairs[2 * (first + j) + 1]);
       }
     }
-  }
-  return MAR_OK;
+    ++buffer_index;
+  };
+  for (int i = 0; i < c; ++i) buf[i] = i;
+  for (int i = 0; i < c; ++i)
+    for (int j = 0; j < c; ++j) emit(buf[i], buf[j]);
+  close_group(0);
+  beta_walk(p, c, [&](int slot, int32_t x) {
+    const size_t first = out;
+    buf[slot] = x;
+    for (int i = 0; i < slot; ++i) emit(buf[i], x);
+    for (int j = 0; j < c; ++j) emit(x, buf[j]);
+    for (int i = slot + 1; i < c; ++i) emit(buf[i], x);
+    close_group(first);
+  });
+  return out == (size_t)p * p ? MAR_OK : order_fail(MAR_ERANGE, "internal: not every bucket was emitted");
 }
 
 extern "C" int mar_buffer_simulate(int32_t p, int32_t c, const int32_t* pairs, int64_t n_pairs, int64_t* loads) {
