@@ -180,7 +180,22 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
     phases = {nm: round(per_step(ms) * 1e3, 2) for nm, ms in zip(mar.binding.PHASE_NAMES, phase_ms)}
     traffic = measured_traffic(w.name) if not nodes else {}          # per-launch bytes do not depend on the edge list
     flash_traffic = (traffic.get("k_flash", 0.0) + traffic.get("k_flash_bwd", 0.0)) or None
-    gbs = lambda b, ms: b / (per_step(ms) * 1e-3) / 1e9 if ms > 0 else None
+    # Bandwidth of the row phases two ways: algorithmic bytes (what the phase has to move) and the bytes the
+    # rocprofv3 FETCH_SIZE / WRITE_SIZE counters saw per launch (profiles/traffic_<workload>.md), both over the
+    # phase's time between HIP events on its stream.
+    def phase(kernels, algo_bytes, ms, **extra):
+        cb = sum(traffic.get(k, 0.0) for k in kernels) or None
+        t = per_step(ms) * 1e-3
+        d = {"kernel": " + ".join(kernels), "us": round(t * 1e6, 2), "bytes": algo_bytes,
+             "GB/s": algo_bytes / t / 1e9 if t > 0 else None, "frac": algo_bytes / t / 1e9 / PEAK_HBM_GBS if t > 0 else None,
+             "counter_bytes": cb, "counter_GB/s": cb / t / 1e9 if cb and t > 0 else None,
+             "counter_frac": cb / t / 1e9 / PEAK_HBM_GBS if cb and t > 0 else None}
+        d.update(extra)
+        return d
+    hbm_phases = {"gather": phase(("k_prep",), gather_bytes, phase_ms[1]),
+                  "chain_rule": phase(("k_chain",), chain_bytes, phase_ms[4], note="runs on the second stream beside the second contraction pass"),
+                  "reduce_adagrad": phase(("k_reduce_apply", "k_span_apply"), scatter_bytes, phase_ms[5], unique_rows=U),
+                  "peak_GB/s": PEAK_HBM_GBS}
     cfg = {"workload": w.name, "num_nodes": w.num_nodes, "num_rels": w.num_rels, "num_edges": w.num_edges,
            "score": ["DistMult", "ComplEx", "TransE", "Dot"][w.model], "dim": w.dim, "batch": w.batch_size,
            "chunks": w.num_chunks, "negs_per_chunk": w.negs_per_chunk, "deg_negs_per_chunk": w.deg_negs_per_chunk,
@@ -205,16 +220,7 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
                      "k_flash_bwd": {"us": round(per_launch(flash_phase[3]), 2), "flops": flops(4.0),
                                      "frac": tflops(flops(4.0), per_launch(flash_phase[3])) / PEAK_FP32_MFMA_TFLOPS}},
         "phases_us_per_step": phases,
-        "hbm_phases": {
-            "gather": {"kernel": "k_prep", "bytes": gather_bytes, "GB/s": gbs(gather_bytes, phase_ms[1]),
-                       "frac": (gbs(gather_bytes, phase_ms[1]) or 0.0) / PEAK_HBM_GBS, "counter_bytes": traffic.get("k_prep")},
-            "chain_rule": {"kernel": "k_chain", "bytes": chain_bytes, "GB/s": gbs(chain_bytes, phase_ms[4]),
-                           "frac": (gbs(chain_bytes, phase_ms[4]) or 0.0) / PEAK_HBM_GBS, "counter_bytes": traffic.get("k_chain")},
-            "reduce_adagrad": {"kernel": "k_reduce_apply + k_span_apply", "bytes": scatter_bytes, "unique_rows": U,
-                               "GB/s": gbs(scatter_bytes, phase_ms[5]),
-                               "frac": (gbs(scatter_bytes, phase_ms[5]) or 0.0) / PEAK_HBM_GBS,
-                               "counter_bytes": (traffic.get("k_reduce_apply", 0.0) + traffic.get("k_span_apply", 0.0)) or None},
-            "peak_GB/s": PEAK_HBM_GBS},
+        "hbm_phases": hbm_phases,
         "final_loss_per_edge": loss / last_batch_edges,
     }
     if cpu_baseline:
