@@ -135,6 +135,7 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.gQ = (float*)take((size_t)d.sy1 * 2 * B * dk * 4);
   l.ml = (float*)take((size_t)d.sy1 * 2 * B * 2 * 4);
   l.T = (float*)take(2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)((d.N + 127) & ~127) * 4);
+  l.R = (float*)take(2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)(((d.N + 127) & ~127) / 16) * 4);
   l.G = (float*)take(n_pos * dk * 4);
   l.carry = (float*)take(blocks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);

@@ -34,7 +34,9 @@ struct MarLayout {
   float*    lse;          // [2][batch] log-sum-exp per edge and side
   float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
   float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
-  float*    T;            // [2*chunks][S rounded up to 64][N rounded up to 128] raw score block, pass 1 -> pass 2
+  float*    T;            // [2*chunks][S rounded up to 64][N rounded up to 128] softmax weights exp(score - reference)
+                          // (TransE: divided by the distance), pass 1 -> pass 2
+  float*    R;            // [2*chunks][N rounded up to 128, / 16][S rounded up to 64] the reference each 16-negative block of T was written with
   float*    G;            // [roles*n + 2*cn*sy2][dk] gradient rows: edge-side occurrence k < roles*n at row k, part i
                           // of negative occurrence k at row roles*n + (k - roles*n)*sy2 + i
   float*    carry;        // [reduce blocks][2][dk] partial sums of segments that cross workgroup borders

@@ -12,10 +12,11 @@
 //     O^T[c][x] += sum_y K[y][c] W[y][x]             the accumulator layout of T is exactly the
 //                                                    B-operand layout the second product needs
 // so every per-x quantity (reference, running sum, rescale factor) is per lane and nothing is
-// transposed.  The raw scores T are also written out once (4 B per pair): fp32 matrix
-// throughput is ~20 flop per HBM byte on this chip while recomputing a score costs 2d flops,
-// so k_flash_bwd reads them back instead of multiplying again and runs only the second product,
-// with the roles of Q and K swapped.  Evaluation (PASS 3) only counts negatives scoring above
+// transposed.  The weights W are also written out once (4 B per pair) together with the reference
+// they were formed with (one float per edge and 16 negatives): fp32 matrix throughput is ~20 flop
+// per HBM byte on this chip while recomputing a score costs 2d flops, so k_flash_bwd reads them
+// back, scales them by exp(reference - lse) and runs only the second product, with the roles of Q
+// and K swapped.  Evaluation (PASS 3) only counts negatives scoring above
 // the positive.  TransE uses |q - n|^2 = |q|^2 + |n|^2 - 2 q.n for the scores (pairs for which that expansion
 // cancels are recomputed from the differences) and W = P / distance.
 #include <type_traits>
@@ -40,8 +41,10 @@ struct FlashArgs {
   int32_t tps;
   int32_t sy_ml;       // parts pass 1 was split into
   int32_t roles;       // edge-side occurrences per edge (3, or 2 for Dot)
-  float* T;            // [2*nchunks][trows][tpitch] raw scores of every (edge, negative) pair: written by
-                       // pass 1, read by the negatives' gradient pass (which then needs no score product)
+  float* T;            // [2*nchunks][trows][tpitch] softmax weight exp(score - reference) of every (edge, negative)
+                       // pair (TransE: divided by the distance): written by pass 1, read by the negatives' gradient
+                       // pass, which then needs no score product and no exponential
+  float* R;            // [2*nchunks][tpitch/16][trows] the reference pass 1 used for a 16-negative block of an edge
   int32_t tpitch;      // N rounded up to 128 (whole tiles of pass 1 and whole stripes of pass 2)
   int32_t trows;       // chunk size rounded up to 64
 };
@@ -49,6 +52,26 @@ struct FlashArgs {
 __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
+
+// Streamed operands are fetched with buffer loads: a descriptor (base, size in bytes) in scalar registers, a
+// per-lane byte offset that never changes and a scalar byte offset that moves from tile to tile, so the tile
+// loops hold no per-lane address arithmetic.  A load whose offset lies at or beyond the size returns 0 without
+// touching memory (the descriptor's range check), which stands in for every "row beyond the chunk" test.
+// Word 3 of the descriptor: 32-bit data format, linear addressing.
+typedef __amdgpu_buffer_rsrc_t BufRsrc;
+__device__ __forceinline__ BufRsrc buf_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ v4f buf_load4(BufRsrc r, int voff, int soff) {
+  return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+}
+__device__ __forceinline__ float2 buf_load2(BufRsrc r, int voff, int soff) {
+  return __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+}
+__device__ __forceinline__ float buf_load1(BufRsrc r, int voff, int soff) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+#define MAR_BUF_NOWHERE 0x40000000                        // a per-lane offset beyond every descriptor's size: loads 0
 
 
 // A operands of the second product O^T[c][x] += sum_y Y[y][c] W[y][x] for one streamed row y.
@@ -219,13 +242,14 @@ k_flash(FlashArgs a) {
   v4f oacc[XB][NC];
   float4 otail[XB];
   float mrun[XB], lrun[XB], wsum[XB];
+  float ref_blk[XB];                                      // lane group g: reference of block g of the current tile
   int cnt[XB];
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
 #pragma unroll
     for (int cb = 0; cb < NC; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
     otail[b] = make_float4(0.f, 0.f, 0.f, 0.f);
-    mrun[b] = -3.0e38f; lrun[b] = 0.f; wsum[b] = 0.f; cnt[b] = 0;
+    mrun[b] = -3.0e38f; lrun[b] = 0.f; wsum[b] = 0.f; cnt[b] = 0; ref_blk[b] = 0.f;
   }
 
   // ---- streamed tiles, register-staged prefetch of the next tile
@@ -238,35 +262,40 @@ k_flash(FlashArgs a) {
   float st_auy = 0.f;
   const int s_cu = threadIdx.x % SM::NKP, s_r0 = threadIdx.x / SM::NKP;   // narrow rows: this thread's column group and first row
   const int s_col = min(4 * s_cu, dk - 4);
-  const int s_lds = s_r0 * PITCH + 4 * s_cu;
-  auto slot_of = [&](int u, int& row, int& col, int& lofs) {
+  const int s_lds = s_r0 * (PITCH / 4) + s_cu;               // LDS offsets in float4 units: 16-byte stores
+  // slot u of this thread: byte offset of its float4 inside a tile of the streamed matrix, and its LDS offset
+  // in float4 units (-1: nothing to store)
+  auto slot_of = [&](int u, int& gofs, int& lofs) {
     if (SM::PO2) {
-      row = s_r0 + SM::RPS * u; col = s_col;
-      lofs = s_cu < NK ? s_lds + u * SM::RPS * PITCH : -1;
+      gofs = ((s_r0 + SM::RPS * u) * dk + s_col) * 4;
+      lofs = s_cu < NK ? s_lds + u * SM::RPS * (PITCH / 4) : -1;
     } else {
       const int unit = threadIdx.x + 256 * u;
       const int r = unit / NK, cu = unit % NK;
-      row = unit < TY * NK ? r : TY - 1;
-      col = min(4 * cu, dk - 4);
-      lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+      gofs = unit < TY * NK ? (r * dk + min(4 * cu, dk - 4)) * 4 : MAR_BUF_NOWHERE;
+      lofs = unit < TY * NK ? r * (PITCH / 4) + cu : -1;
     }
   };
-  // Every staging load is issued unconditionally from an address clamped into the chunk's rows (and into
-  // the row's dk columns): no branch, no zero fill.  A row beyond the chunk then holds a copy of the last
-  // valid row; its scores are masked to -inf, so it weighs nothing.  A column group beyond dk holds a copy of
-  // the row's last four columns; it meets zero fragments of the stationary rows in the score product and
-  // produces output columns that are never stored.
+  // Every staging load is issued unconditionally: a row beyond the chunk reads as zeros (its scores are masked
+  // to -inf, so it weighs nothing).  A column group beyond dk holds a copy of the row's last four columns; it
+  // meets zero fragments of the stationary rows in the score product and produces output columns that are
+  // never stored.
+  const BufRsrc ysrc = buf_rsrc(a.Y + y_base * dk, (uint32_t)n_y * dk * 4);
+  const BufRsrc yysrc = buf_rsrc(L2 ? a.yy + y_base : a.Y, L2 ? (uint32_t)n_y * 4 : 0u);
+  int s_gofs[SM::PO2 ? 1 : NU];                            // wide rows: one offset per slot, kept in registers
+  if (SM::PO2) s_gofs[0] = (s_r0 * dk + s_col) * 4;
+  else {
+#pragma unroll
+    for (int u = 0; u < NU; ++u) { int lofs; slot_of(u, s_gofs[u], lofs); }
+  }
   auto load_tile = [&](int t) {
-    const int y0 = t * TY;
-    const int last = n_y - y0 - 1;                        // last valid row of this tile (>= 0)
-    const float* __restrict__ src = a.Y + (y_base + y0) * dk;
+    const int tofs = t * TY * dk * 4;                      // scalar: byte offset of the tile
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, col, lofs;
-      slot_of(u, row, col, lofs);
-      stage[u] = *reinterpret_cast<const v4f*>(src + min(row, last) * dk + col);
+      if (SM::PO2) stage[u] = buf_load4(ysrc, s_gofs[0], tofs + u * SM::RPS * dk * 4);
+      else stage[u] = buf_load4(ysrc, s_gofs[u], tofs);
     }
-    if (L2 && threadIdx.x < TY) st_auy = a.yy[y_base + y0 + min((int)threadIdx.x, last)];
+    if (L2) st_auy = buf_load1(yysrc, (int)(threadIdx.x % TY) * 4, t * TY * 4);
   };
   if (t_begin < ntiles) load_tile(t_begin);
 
@@ -286,11 +315,11 @@ k_flash(FlashArgs a) {
   auto stage_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, col, lofs;
-      slot_of(u, row, col, lofs);
-      if (lofs >= 0) *reinterpret_cast<v4f*>(&tile[lofs]) = stage[u];
+      int gofs, lofs;
+      slot_of(u, gofs, lofs);
+      if (lofs >= 0) reinterpret_cast<v4f*>(tile)[lofs] = stage[u];
     }
-    if (L2 && threadIdx.x < TY) auy[threadIdx.x] = st_auy;
+    if (L2) auy[threadIdx.x % TY] = st_auy;                // threads that share a row write the same value
   };
   if (t_begin < ntiles) {
     stage_tile();
@@ -403,12 +432,6 @@ k_flash(FlashArgs a) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) { dist[r] = sqrtf(d2[r]); sc[r] = -dist[r]; }
         }
-        if (PASS == 1) {
-          // keep the raw scores for the negatives' gradient pass: row = edge, 4 consecutive negatives.  The
-          // buffer is padded to whole stripes and tiles, so the store needs no bounds test (a conditional
-          // store would hide from the compiler how many stores follow the prefetch loads).
-          *reinterpret_cast<float4*>(a.T + ((size_t)cs * a.trows + x[b]) * a.tpitch + y0 + yl) = make_float4(sc[0], sc[1], sc[2], sc[3]);
-        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           if (masked && y0 + yl + r >= n_y) sc[r] = -__builtin_inff();
@@ -442,6 +465,15 @@ k_flash(FlashArgs a) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) w[b][r] = dist[r] > 0.f ? w[b][r] / dist[r] : 0.f;
           wsum[b] += (w[b][0] + w[b][1]) + (w[b][2] + w[b][3]);
+        }
+        if (PASS == 1) {
+          // keep the weights for the negatives' gradient pass: row = edge, 4 consecutive negatives (0 for the
+          // columns beyond the chunk's negatives).  The buffer is padded to whole stripes and tiles, so the
+          // store needs no bounds test (a conditional store would hide from the compiler how many stores follow
+          // the prefetch loads).  Lane group g keeps the reference of block g of the tile for the store at the
+          // tile's end.
+          *reinterpret_cast<float4*>(a.T + ((size_t)cs * a.trows + x[b]) * a.tpitch + y0 + yl) = make_float4(w[b][0], w[b][1], w[b][2], w[b][3]);
+          if (yb == g % (TY / 16)) ref_blk[b] = mrun[b];
         }
       }
       // first fragments of the next block's score product, fetched under the second product (the fence keeps
@@ -479,6 +511,14 @@ k_flash(FlashArgs a) {
       const bool full = y0 + TY <= n_y;                    // full tile: no row masks
 #pragma unroll 1
       for (int yb = 0; yb < nblk; ++yb) process_block(yb, yb + 1 < nblk, !full);
+    }
+    if (PASS == 1) {
+      // references of this tile's blocks: lane (g, m) writes block g's (with fewer than 4 blocks per tile the
+      // surplus lane groups write a second copy of the same value)
+      static_assert(TY / 16 <= 4, "one lane group per block of a tile");
+#pragma unroll
+      for (int b = 0; b < XB; ++b)
+        a.R[((size_t)cs * (a.tpitch / 16) + (size_t)(t * (TY / 16) + g % (TY / 16))) * a.trows + x[b]] = ref_blk[b];
     }
     if (HAS_NEXT) {
       __syncthreads();                                     // every wave is done with this tile
@@ -529,11 +569,11 @@ k_flash(FlashArgs a) {
   }
 }
 
-// Gradient w.r.t. the negatives' rows from stored scores: gK[j] = sum_e exp(T[e][j] - lse[e]) Q[e]
-// (TransE: weights divided by the distance, minus n_j times their sum).  A workgroup owns 64*XB
+// Gradient w.r.t. the negatives' rows from the stored weights: gK[j] = sum_e T[e][j] exp(R[e][j / 16] - lse[e]) Q[e]
+// (TransE: T holds the weights divided by the distance; minus n_j times their sum).  A workgroup owns 64*XB
 // negatives (16*XB per wave; XB = 1 measured best: more, smaller workgroups fill the chip more evenly than
 // two blocks per wave save in LDS reads) and streams the chunk's edges in tiles of TY: the Q rows go through
-// LDS, the scores straight from memory into registers -- lane (g, m) takes T[e = 4g + r][j = m]
+// LDS, the weights straight from memory into registers -- lane (g, m) takes T[e = 4g + r][j = m]
 // of its 16-negative block, which is the B-operand layout of O^T[c][j] += sum_e Q[e][c] W[e][j] --
 // one tile ahead: as soon as a block's scores are consumed the same registers are refilled with
 // the next tile's.  Only the second product runs on the matrix cores.
@@ -549,7 +589,8 @@ k_flash_bwd(FlashArgs a) {
   constexpr int NB = TY / 16;                             // 16-row blocks per tile
   constexpr int NU = StageMap<NK, TY>::NU;                // float4 units of the Q tile staged per thread
   __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
-  __shared__ float aux[TY];                               // log-sum-exp of the streamed edges
+  static_assert(XB == 1 && 4 * TY <= 256, "one scale factor per thread: (wave's 16-negative block, streamed edge)");
+  __shared__ __attribute__((aligned(16))) float aux[4][TY];   // per wave: exp(reference - lse) of the streamed edges
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, m = lane & 15;
@@ -581,64 +622,74 @@ k_flash_bwd(FlashArgs a) {
   const int t_begin = part * a.tps;
   const int ntiles = min(ntiles_all, t_begin + a.tps);
 
-  // staging slots of the Q tile (see StageMap).  As in k_flash every load is unconditional, from a row clamped into the chunk: a row beyond the chunk is
-  // a copy of the last one and carries lse = +inf, so it weighs nothing.
+  // staging slots of the Q tile (see StageMap).  As in k_flash every load is unconditional: a row beyond the
+  // chunk reads as zeros and carries lse = +inf, so it weighs nothing.
   typedef StageMap<NK, TY> SM;
   v4f stage[NU];                                           // plain vectors: a struct copy from global memory would pin the array in memory
   float2 st_ml;                                           // softmax statistics (part 0) of this thread's streamed row
+  float st_ref;                                           // reference of (this thread's wave slot, streamed row)
+  const int a_row = threadIdx.x % TY, a_wave = (threadIdx.x / TY) % 4;   // the scale factor this thread prepares
   const int s_cu = threadIdx.x % SM::NKP, s_r0 = threadIdx.x / SM::NKP;   // narrow rows: this thread's column group and first row
   const int s_col = min(4 * s_cu, dk - 4);
-  const int s_lds = s_r0 * PITCH + 4 * s_cu;
-  auto slot_of = [&](int u, int& row, int& col, int& lofs) {
+  const int s_lds = s_r0 * (PITCH / 4) + s_cu;               // LDS offsets in float4 units: 16-byte stores
+  auto slot_of = [&](int u, int& gofs, int& lofs) {         // see k_flash
     if (SM::PO2) {
-      row = s_r0 + SM::RPS * u; col = s_col;
-      lofs = s_cu < NK ? s_lds + u * SM::RPS * PITCH : -1;
+      gofs = ((s_r0 + SM::RPS * u) * dk + s_col) * 4;
+      lofs = s_cu < NK ? s_lds + u * SM::RPS * (PITCH / 4) : -1;
     } else {
       const int unit = threadIdx.x + 256 * u;
       const int r = unit / NK, cu = unit % NK;
-      row = unit < TY * NK ? r : TY - 1;
-      col = min(4 * cu, dk - 4);
-      lofs = unit < TY * NK ? r * PITCH + 4 * cu : -1;
+      gofs = unit < TY * NK ? (r * dk + min(4 * cu, dk - 4)) * 4 : MAR_BUF_NOWHERE;
+      lofs = unit < TY * NK ? r * (PITCH / 4) + cu : -1;
     }
   };
-  // scores of the current tile: tr[yb][b][r] = T[e = y0 + 16 yb + 4g + r][j = stripe*SR + (wave*XB + b)*16 + m].
-  // The buffer is padded to whole tiles and stripes, so every address is valid, and pass 1 has written every
-  // row of a 64-row stripe that holds at least one edge (finite values); rows beyond the chunk carry
-  // lse = +inf and weigh nothing.
+  // weights of the current tile: tr[yb][b][r] = T[e = y0 + 16 yb + 4g + r][j = stripe*SR + (wave*XB + b)*16 + m].
+  // The buffer is padded to whole tiles and stripes, and pass 1 has written every row of a 64-row stripe that
+  // holds at least one edge (finite values); rows beyond the chunk get the scale factor 0 and weigh nothing.
   float tr[NB][XB][4];
-  const float* __restrict__ tcol = a.T + (size_t)cs * a.trows * a.tpitch + (size_t)(4 * g) * a.tpitch + stripe * SR + wave * XB * 16 + m;
+  const BufRsrc tsrc = buf_rsrc(a.T + (size_t)cs * a.trows * a.tpitch, (uint32_t)a.trows * a.tpitch * 4);
+  const int t_vofs = (4 * g * a.tpitch + stripe * SR + wave * XB * 16 + m) * 4;
   auto load_scores = [&](int t, int yb) {
-    const float* __restrict__ p = tcol + (size_t)(t * TY + yb * 16) * a.tpitch;
+    const int row0 = t * TY + yb * 16;                     // scalar
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
 #pragma unroll
-      for (int b = 0; b < XB; ++b) tr[yb][b][r] = p[(size_t)r * a.tpitch + 16 * b];
+      for (int b = 0; b < XB; ++b) tr[yb][b][r] = buf_load1(tsrc, t_vofs, ((row0 + r) * a.tpitch + 16 * b) * 4);
     }
   };
   const size_t ml_stride = (size_t)2 * a.B;               // rows per part of pass 1's statistics
+  // Q rows and statistics of the streamed edges: loads beyond the chunk's edges return zeros
+  const BufRsrc ysrc = buf_rsrc(a.Y + y_base * dk, (uint32_t)n_y * dk * 4);
+  const BufRsrc mlsrc = buf_rsrc(a.ml + y_base * 2, (uint32_t)n_y * 8);
+  const BufRsrc rsrc = buf_rsrc(a.R + (size_t)cs * (a.tpitch / 16) * a.trows, (uint32_t)(a.tpitch / 16) * a.trows * 4);
+  const int r_vofs = ((stripe * (SR / 16) + a_wave) * a.trows + a_row) * 4;
+  int s_gofs[SM::PO2 ? 1 : NU];
+  if (SM::PO2) s_gofs[0] = (s_r0 * dk + s_col) * 4;
+  else {
+#pragma unroll
+    for (int u = 0; u < NU; ++u) { int lofs; slot_of(u, s_gofs[u], lofs); }
+  }
   auto load_tile = [&](int t) {
-    const int y0 = t * TY;
-    const int last = n_y - y0 - 1;                        // last valid row of this tile (>= 0)
-    const float* __restrict__ src = a.Y + (y_base + y0) * dk;
+    const int tofs = t * TY * dk * 4;                      // scalar: byte offset of the tile
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, col, lofs;
-      slot_of(u, row, col, lofs);
-      stage[u] = *reinterpret_cast<const v4f*>(src + min(row, last) * dk + col);
+      if (SM::PO2) stage[u] = buf_load4(ysrc, s_gofs[0], tofs + u * SM::RPS * dk * 4);
+      else stage[u] = buf_load4(ysrc, s_gofs[u], tofs);
     }
     // statistics of streamed row threadIdx.x % TY (part 0 of pass 1); the log-sum-exp is formed from them only
     // when the tile is staged, so that nothing waits for this load here
-    st_ml = reinterpret_cast<const float2*>(a.ml)[y_base + y0 + min((int)(threadIdx.x % TY), last)];
+    st_ml = buf_load2(mlsrc, a_row * 8, t * TY * 8);
+    st_ref = buf_load1(rsrc, r_vofs, t * TY * 4);
   };
   auto stage_tile = [&](int t) {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      int row, col, lofs;
-      slot_of(u, row, col, lofs);
-      if (lofs >= 0) *reinterpret_cast<v4f*>(&tile[lofs]) = stage[u];
+      int gofs, lofs;
+      slot_of(u, gofs, lofs);
+      if (lofs >= 0) reinterpret_cast<v4f*>(tile)[lofs] = stage[u];
     }
-    {                                                      // every thread holds row threadIdx.x % TY: threads that share a
-      const int yr = t * TY + (int)(threadIdx.x % TY);     // row write the same value, and no wave takes a branch of its own
+    {                                                      // every thread prepares one (wave slot, row) factor; threads beyond
+      const int yr = t * TY + a_row;                       // 4 TY write a second copy, and no wave takes a branch of its own
       float mm = st_ml.x, ll = st_ml.y;
       if (a.sy_ml > 1 && yr < n_y) {                       // pass 1 was split (small batches): merge the parts
         const float2* __restrict__ mlp = reinterpret_cast<const float2*>(a.ml) + y_base + yr;
@@ -646,7 +697,8 @@ k_flash_bwd(FlashArgs a) {
         ll *= __expf(st_ml.x - mm);
         for (int p = 1; p < a.sy_ml; ++p) { const float2 v = mlp[p * ml_stride]; ll += v.y * __expf(v.x - mm); }
       }
-      aux[threadIdx.x % TY] = yr < n_y ? mm + logf(ll) : __builtin_inff();
+      // stored weight = exp(score - reference): times exp(reference - lse) it is the softmax probability
+      aux[a_wave][a_row] = yr < n_y ? __expf(st_ref - (mm + logf(ll))) : 0.f;
     }
   };
   if (t_begin < ntiles) {
@@ -666,7 +718,7 @@ k_flash_bwd(FlashArgs a) {
     // through) instead of keeping values alive across the main loop, which has no registers to spare
     int tid_l = threadIdx.x;
     if (!HAS_NEXT) asm volatile("" : "+v"(tid_l));
-    const int g = (tid_l & 63) >> 4, m = tid_l & 15;
+    const int g = (tid_l & 63) >> 4, m = tid_l & 15, wave_l = tid_l >> 6;
     if (HAS_NEXT) load_tile(t + 1);
     const int y0 = t * TY;
     const int nblk = HAS_NEXT ? NB : min(NB, (n_y - y0 + 15) / 16);
@@ -680,14 +732,9 @@ k_flash_bwd(FlashArgs a) {
         float w[XB][4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float ls = aux[yl + r];
+          const float fs = aux[wave_l][yl + r];            // 0 for rows beyond the chunk
 #pragma unroll
-          for (int b = 0; b < XB; ++b) {
-            const float sc = tr[yb][b][r];
-            float v = __expf(sc - ls);                     // 0 for rows beyond the chunk (lse = +inf)
-            if (L2) v = sc < 0.f ? v / -sc : 0.f;          // score = -distance
-            w[b][r] = v;
-          }
+          for (int b = 0; b < XB; ++b) w[b][r] = tr[yb][b][r] * fs;
         }
         if (HAS_NEXT) load_scores(t + 1, yb);              // refill the registers just consumed
         if (L2) {
@@ -795,7 +842,7 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.X = pass == 2 ? L.Km : L.Q;  a.Y = pass == 2 ? L.Q : L.Km;   // stationary / streamed matrix
   a.xx = L.qq; a.yy = L.kk;
   a.ml = L.ml; a.pos = L.pos;
-  a.T = L.T; a.tpitch = (d.N + 127) & ~127; a.trows = (d.S + 63) & ~63;
+  a.T = L.T; a.R = L.R; a.tpitch = (d.N + 127) & ~127; a.trows = (d.S + 63) & ~63;
   a.out = pass == 1 ? L.gQ : L.G;
   a.rank_dst = rank_dst; a.rank_src = rank_src;
   a.n = b.n; a.B = d.B; a.C = d.C; a.N = d.N; a.S = d.S; a.cn = b.cn; a.nchunks = b.nchunks; a.dk = d.dk;
