@@ -271,12 +271,22 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   MARK(2, 0, st);
   HIP_TRY(mar_launch_flash(c, b, 1, nullptr, nullptr, st), "score/softmax kernel");
   MARK(2, 1, st);
-  HIP_TRY(hipEventRecord(c->ev_pass1, st), "fork");
-  HIP_TRY(hipStreamWaitEvent(ax, c->ev_pass1, 0), "fork");
-  MARK(4, 0, ax);
-  HIP_TRY(mar_launch_chain(c, b, ax), "chain-rule kernel");
-  MARK(4, 1, ax);
-  HIP_TRY(hipEventRecord(c->ev_chain, ax), "join");
+  // The chain rule needs pass 1 only.  Large batches run it on `aux` beside pass 2, which leaves memory bandwidth
+  // unused; for small batches `aux` is the longer path to the reduce (the index build), so it stays on the
+  // caller's stream.
+  if (c->dm.index_after_gather) {
+    HIP_TRY(hipEventRecord(c->ev_pass1, st), "fork");
+    HIP_TRY(hipStreamWaitEvent(ax, c->ev_pass1, 0), "fork");
+    MARK(4, 0, ax);
+    HIP_TRY(mar_launch_chain(c, b, ax), "chain-rule kernel");
+    MARK(4, 1, ax);
+    HIP_TRY(hipEventRecord(c->ev_chain, ax), "join");
+  } else {
+    MARK(4, 0, st);
+    HIP_TRY(mar_launch_chain(c, b, st), "chain-rule kernel");
+    MARK(4, 1, st);
+    HIP_TRY(hipEventRecord(c->ev_chain, st), "join");
+  }
   MARK(3, 0, st);
   HIP_TRY(mar_launch_flash(c, b, 2, nullptr, nullptr, st), "negative-gradient kernel");
   MARK(3, 1, st);

@@ -52,6 +52,13 @@ struct FlashArgs {
 __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
+// Sixteen 4x4 outer products, one per group of 4 consecutive lanes: lane 4q + j, register i gets
+// a(lane 4q + i) * b(lane 4q + j) added.  Used for the last 4 output columns of the second product when the
+// width leaves 4 columns over the 16-wide blocks: with a = Y[y][16 NC + (lane & 3)] and b = W[y][x] of the
+// lane's own (y, x), register i accumulates column 16 NC + i of O^T[.][x] over the lane's own streamed rows.
+__device__ __forceinline__ v4f mfma4(float a, float b, v4f c) {
+  return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0);
+}
 
 // Streamed operands are fetched with buffer loads: a descriptor (base, size in bytes) in scalar registers, a
 // per-lane byte offset that never changes and a scalar byte offset that moves from tile to tile, so the tile
@@ -235,12 +242,12 @@ k_flash(FlashArgs a) {
     if (PASS == 3) posx[b] = xv[b] ? a.pos[(size_t)c * a.S + x[b]] : 0.f;
   }
 
-  // Output columns [0, 16*NC) of the second product go through the matrix cores; with VT the last
-  // 4 columns [16*NC, 16*NC + 4) are accumulated on the vector ALU instead (per lane over its own 4
-  // streamed rows, summed over the 4 lane groups at the end): a 16-wide block for 4 columns would
-  // waste 3/4 of its matrix instructions.
+  // Output columns [0, 16*NC) of the second product go through 16x16 matrix blocks; with VT the last
+  // 4 columns [16*NC, 16*NC + 4) go through the 4x4 outer-product instruction instead (per lane over its
+  // own 4 streamed rows, summed over the 4 lane groups at the end): a 16-wide block for 4 columns would
+  // waste 3/4 of its matrix instructions, and the vector ALU cannot run beside the fp32 matrix pipe.
   v4f oacc[XB][NC];
-  float4 otail[XB];
+  v4f otail[XB];                                          // last 4 output columns (VT), per lane over its own streamed rows
   float mrun[XB], lrun[XB], wsum[XB];
   float ref_blk[XB];                                      // lane group g: reference of block g of the current tile
   int cnt[XB];
@@ -248,7 +255,7 @@ k_flash(FlashArgs a) {
   for (int b = 0; b < XB; ++b) {
 #pragma unroll
     for (int cb = 0; cb < NC; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
-    otail[b] = make_float4(0.f, 0.f, 0.f, 0.f);
+    otail[b] = (v4f){0.f, 0.f, 0.f, 0.f};
     mrun[b] = -3.0e38f; lrun[b] = 0.f; wsum[b] = 0.f; cnt[b] = 0; ref_blk[b] = 0.f;
   }
 
@@ -453,7 +460,7 @@ k_flash(FlashArgs a) {
             lrun[b] *= alpha;
 #pragma unroll
             for (int cb = 0; cb < NC; ++cb) oacc[b][cb] *= alpha;
-            if (VT) { otail[b].x *= alpha; otail[b].y *= alpha; otail[b].z *= alpha; otail[b].w *= alpha; }
+            if (VT) otail[b] *= alpha;
             if (L2) wsum[b] *= alpha;
             mrun[b] = mnew;
           }
@@ -494,12 +501,9 @@ k_flash(FlashArgs a) {
             for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
           }
           if (VT) {
-            const float4 yt = *reinterpret_cast<const float4*>(&tile[(yl + r) * PITCH + 16 * NC]);
+            const float yt = tile[(yl + r) * PITCH + 16 * NC + (m & 3)];
 #pragma unroll
-            for (int b = 0; b < XB; ++b) {
-              otail[b].x += yt.x * w[b][r]; otail[b].y += yt.y * w[b][r];
-              otail[b].z += yt.z * w[b][r]; otail[b].w += yt.w * w[b][r];
-            }
+            for (int b = 0; b < XB; ++b) otail[b] = mfma4(yt, w[b][r], otail[b]);
           }
         }
       }
@@ -550,7 +554,7 @@ k_flash(FlashArgs a) {
       ws += __shfl_xor(ws, 16);
       ws += __shfl_xor(ws, 32);
     }
-    float4 ot = otail[b];
+    float4 ot = make_float4(otail[b][0], otail[b][1], otail[b][2], otail[b][3]);
     if (VT) {
       ot.x += __shfl_xor(ot.x, 16); ot.y += __shfl_xor(ot.y, 16); ot.z += __shfl_xor(ot.z, 16); ot.w += __shfl_xor(ot.w, 16);
       ot.x += __shfl_xor(ot.x, 32); ot.y += __shfl_xor(ot.y, 32); ot.z += __shfl_xor(ot.z, 32); ot.w += __shfl_xor(ot.w, 32);
@@ -578,7 +582,7 @@ k_flash(FlashArgs a) {
 // one tile ahead: as soon as a block's scores are consumed the same registers are refilled with
 // the next tile's.  Only the second product runs on the matrix cores.
 #ifndef MAR_BWD_WAVES
-#define MAR_BWD_WAVES 2
+#define MAR_BWD_WAVES 3
 #endif
 template <int NK, int NC, int VT, int TY, int XB, int L2>
 __global__ void __launch_bounds__(256) MAR_WAVES_PER_SIMD((NK * XB <= 32 ? MAR_BWD_WAVES : 2))
@@ -596,9 +600,15 @@ k_flash_bwd(FlashArgs a) {
   const int g = lane >> 4, m = lane & 15;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int part = slot % a.sy, slot2 = slot / a.sy;
+#ifdef MAR_BWD_FORWARD_ORDER
   const int cs = (slot2 / a.nstripes) * 8 + xcd;
+#else
+  // Chunk-sides are taken in the reverse of pass 1's order: the weights pass 1 wrote last are still in the
+  // memory-side cache when this pass starts, and it reads them first.
+  const int cs = 2 * a.nchunks - 1 - ((slot2 / a.nstripes) * 8 + xcd);
+#endif
   const int stripe = slot2 % a.nstripes;
-  if (cs >= 2 * a.nchunks) return;
+  if (cs < 0 || cs >= 2 * a.nchunks) return;
   const int side = cs & 1, c = cs >> 1;
   const int n_y = min(a.S, a.n - c * a.S);                // edges in this chunk (streamed)
   const int n_x = a.N;                                    // negatives (stationary)
@@ -608,13 +618,13 @@ k_flash_bwd(FlashArgs a) {
   const int dk = a.dk;
 
   v4f oacc[XB][NC];
-  float4 otail[XB];                                       // last 4 output columns on the vector ALU (see k_flash)
+  v4f otail[XB];                                          // last 4 output columns (see k_flash)
   float wsum[XB];
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
 #pragma unroll
     for (int cb = 0; cb < NC; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
-    otail[b] = make_float4(0.f, 0.f, 0.f, 0.f);
+    otail[b] = (v4f){0.f, 0.f, 0.f, 0.f};
     wsum[b] = 0.f;
   }
 
@@ -753,12 +763,9 @@ k_flash_bwd(FlashArgs a) {
             for (int b = 0; b < XB; ++b) oacc[b][cb] = mfma16(cur[cb], w[b][r], oacc[b][cb]);
           }
           if (VT) {
-            const float4 yt = *reinterpret_cast<const float4*>(&tile[(yl + r) * PITCH + 16 * NC]);
+            const float yt = tile[(yl + r) * PITCH + 16 * NC + (m & 3)];
 #pragma unroll
-            for (int b = 0; b < XB; ++b) {
-              otail[b].x += yt.x * w[b][r]; otail[b].y += yt.y * w[b][r];
-              otail[b].z += yt.z * w[b][r]; otail[b].w += yt.w * w[b][r];
-            }
+            for (int b = 0; b < XB; ++b) otail[b] = mfma4(yt, w[b][r], otail[b]);
           }
         }
         __builtin_amdgcn_sched_barrier(0);                 // blocks are scheduled one by one: hoisting the next block's
@@ -785,7 +792,7 @@ k_flash_bwd(FlashArgs a) {
       ws += __shfl_xor(ws, 16);
       ws += __shfl_xor(ws, 32);
     }
-    float4 ot = otail[b];
+    float4 ot = make_float4(otail[b][0], otail[b][1], otail[b][2], otail[b][3]);
     if (VT) {
       ot.x += __shfl_xor(ot.x, 16); ot.y += __shfl_xor(ot.y, 16); ot.z += __shfl_xor(ot.z, 16); ot.w += __shfl_xor(ot.w, 16);
       ot.x += __shfl_xor(ot.x, 32); ot.y += __shfl_xor(ot.y, 32); ot.z += __shfl_xor(ot.z, 32); ot.w += __shfl_xor(ot.w, 32);
@@ -812,7 +819,10 @@ k_flash_bwd(FlashArgs a) {
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
 // Streamed rows per tile of the instantiation that serves dk: pass 1 / 3, and pass 2 (whose widest
 // instantiation takes 16-row tiles so that two workgroups fit in a CU's registers).
-int mar_flash_tile_rows(int dk, int pass) { return dk / 4 <= 32 ? 64 : (pass == 2 && dk / 4 > 64 ? 16 : 32); }
+#ifndef MAR_BWD_WIDE_TY
+#define MAR_BWD_WIDE_TY 32
+#endif
+int mar_flash_tile_rows(int dk, int pass) { return dk / 4 <= 32 ? 64 : (pass == 2 && dk / 4 > 64 ? MAR_BWD_WIDE_TY : 32); }
 
 // Stationary rows per workgroup (64 per x-block of the instantiation that serves dk): pass 1 / 3 and pass 2.
 #ifndef MAR_BWD_XB
@@ -864,5 +874,5 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   if (nk <= 25) return launch_sized<25, 6, 1, 64, 1, 6 + (1 - BV), BV, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
   if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, 8, 0, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
   if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 16, 0, 1, 32>(a, pass, l2, grid, st);
-  return launch_sized<100, 25, 0, 32, 1, 25, 0, 1, 16>(a, pass, l2, grid, st);
+  return launch_sized<100, 25, 0, 32, 1, 25, 0, 1, MAR_BWD_WIDE_TY>(a, pass, l2, grid, st);
 }
