@@ -86,6 +86,31 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   };
   split(1, d->S, d->N, &d->sy1, &d->tps1);
   split(2, d->N, d->S, &d->sy2, &d->tps2);
+  // Large batches: the (chunk-side, stripe) units of pass 1 rarely fill a whole number of rounds of the chip's
+  // workgroup slots (256 CUs x workgroups per CU), and the last, partly filled round costs as much time as a full
+  // one.  Chunk-sides are dealt to the 8 XCDs in groups of 8; the groups beyond the last whole round have every
+  // stripe split into rem_k parts (each streaming rem_tps tiles), so that the last round is short.
+  d->rem_cs0 = 2 * d->C; d->rem_k = 1; d->rem_tps = 0; d->rem_rows = 0;
+  if (d->sy1 == 1) {
+    const long slots = 256L * mar_flash_wgs_per_cu(d->dk, 1);
+    const long nstripes = (d->S + 63) / 64, groups = (2L * d->C + 7) / 8, per_group = 8 * nstripes;
+    const int ty = mar_flash_tile_rows(d->dk, 1);
+    const long ntiles = (d->N + ty - 1) / ty;
+    const long full_rounds = groups * per_group / slots;
+    const long whole_groups = full_rounds * slots / per_group;
+    if (full_rounds >= 1 && whole_groups < groups) {
+      const long rem_units = (2L * d->C - 8 * whole_groups) * nstripes;
+      long k = slots / rem_units;
+      if (k > MAR_MAX_PARTS) k = MAR_MAX_PARTS;
+      if (k > ntiles) k = ntiles;
+      if (k >= 2) {
+        d->rem_cs0 = (int32_t)(8 * whole_groups);
+        d->rem_tps = (int32_t)((ntiles + k - 1) / k);
+        d->rem_k = (int32_t)((ntiles + d->rem_tps - 1) / d->rem_tps);
+        d->rem_rows = (int64_t)(2 * d->C - d->rem_cs0) * ((d->S + 63) & ~63);
+      }
+    }
+  }
   d->n_pos_max = roles * (int64_t)cfg->batch_size + 2 * cn * d->sy2;
   // Sort keys are ranks below u_max: as few passes as digits of at most MAR_SORT_MAX_BITS bits allow.
   int nbits = 1;
@@ -134,6 +159,8 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.lse = (float*)take(2 * B * 4);
   l.gQ = (float*)take((size_t)d.sy1 * 2 * B * dk * 4);
   l.ml = (float*)take((size_t)d.sy1 * 2 * B * 2 * 4);
+  l.gQx = (float*)take((size_t)(d.rem_k - 1) * (size_t)d.rem_rows * dk * 4);
+  l.mlx = (float*)take((size_t)(d.rem_k - 1) * (size_t)d.rem_rows * 2 * 4);
   l.T = (float*)take(2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)((d.N + 127) & ~127) * 4);
   l.R = (float*)take(2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)(((d.N + 127) & ~127) / 16) * 4);
   l.G = (float*)take(n_pos * dk * 4);
@@ -271,6 +298,7 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   MARK(2, 0, st);
   HIP_TRY(mar_launch_flash(c, b, 1, nullptr, nullptr, st), "score/softmax kernel");
   MARK(2, 1, st);
+  HIP_TRY(mar_launch_flash_merge(c, b, st), "stripe merge kernel");
   // The chain rule needs pass 1 only.  Large batches run it on `aux` beside pass 2, which leaves memory bandwidth
   // unused; for small batches `aux` is the longer path to the reduce (the index build), so it stays on the
   // caller's stream.

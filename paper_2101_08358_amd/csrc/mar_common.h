@@ -34,6 +34,8 @@ struct MarLayout {
   float*    lse;          // [2][batch] log-sum-exp per edge and side
   float*    gQ;           // [sy1][2][batch][dk] per-part unnormalised gradient w.r.t. Q rows
   float*    ml;           // [sy1][2][batch][2] per-part softmax reference and sum
+  float*    gQx;          // [rem_k - 1][rem_rows][dk] parts 1.. of the chunk-sides whose stripes are split to fill the last round
+  float*    mlx;          // [rem_k - 1][rem_rows][2]
   float*    T;            // [2*chunks][S rounded up to 64][N rounded up to 128] softmax weights exp(score - reference)
                           // (TransE: divided by the distance), pass 1 -> pass 2
   float*    R;            // [2*chunks][N rounded up to 128, / 16][S rounded up to 64] the reference each 16-negative block of T was written with
@@ -53,6 +55,10 @@ struct MarDims {
   int64_t n_pos_max;               // roles*B + 2CN*sy2: gradient rows per step
   int32_t sy1, sy2;                // how many workgroups share the streamed rows of one stripe (pass 1 / 2)
   int32_t tps1, tps2;              // streamed tiles per workgroup
+  // Pass 1 of a full batch: (chunk-side, stripe) units beyond the last whole round of workgroups -- all stripes of the
+  // chunk-sides from rem_cs0 on -- are each split into rem_k parts of rem_tps tiles, which a small kernel merges.
+  int32_t rem_cs0, rem_k, rem_tps;
+  int64_t rem_rows;                // (2C - rem_cs0) * (S rounded up to 64)
   int64_t u_max;                   // min(num_nodes + num_rels, n_occ_max)
   int64_t nwords;                  // words of the touched-id map
   int32_t ipw_log2;                // ids per word: 5 = one bit per id (atomic marks), 2 = one byte per id (plain stores)
@@ -60,6 +66,7 @@ struct MarDims {
   int32_t index_after_gather;      // launch order of a step: gather first, index build behind it (large batches)
 };
 
+#define MAR_MAX_PARTS 8                   // most parts a stripe of pass 1 is split into
 #define MAR_MAX_PROFILE_STEPS 4096
 
 struct mar_ctx {
@@ -135,3 +142,5 @@ hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_
 int mar_flash_supported(int dk);
 int mar_flash_tile_rows(int dk, int pass);
 int mar_flash_stripe_rows(int dk, int pass);
+int mar_flash_wgs_per_cu(int dk, int pass);        // workgroups of a pass that a CU holds at once
+hipError_t mar_launch_flash_merge(const mar_ctx* c, const MarBatch& b, hipStream_t st);   // after pass 1: merges split stripes

@@ -40,6 +40,11 @@ struct FlashArgs {
   int32_t sy;          // workgroups sharing one stripe, each streaming `tps` tiles
   int32_t tps;
   int32_t sy_ml;       // parts pass 1 was split into
+  // pass 1 of a full batch: workgroup slots (per XCD) from whole_slots on take the stripes of chunk-sides
+  // rem_cs0.. in rem_k parts of rem_tps tiles each; parts 1.. write to mlx / outx [part - 1][rem_rows]
+  int32_t whole_slots, rem_cs0, rem_k, rem_tps;
+  int64_t rem_rows;
+  float* mlx; float* outx;
   int32_t roles;       // edge-side occurrences per edge (3, or 2 for Dot)
   float* T;            // [2*nchunks][trows][tpitch] softmax weight exp(score - reference) of every (edge, negative)
                        // pair (TransE: divided by the distance): written by pass 1, read by the negatives' gradient
@@ -202,9 +207,20 @@ k_flash(FlashArgs a) {
   // workgroup -> (chunk-side, stripe, part); consecutive workgroup ids rotate over the 8 XCDs, so
   // all workgroups of one chunk-side are given ids with the same residue and share one L2.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int part = slot % a.sy, slot2 = slot / a.sy;
-  const int cs = (slot2 / a.nstripes) * 8 + xcd;
-  const int stripe = slot2 % a.nstripes;
+  int part, cs, stripe, tps = a.tps;
+  if (slot < a.whole_slots) {
+    part = slot % a.sy;
+    const int slot2 = slot / a.sy;
+    cs = (slot2 / a.nstripes) * 8 + xcd;
+    stripe = slot2 % a.nstripes;
+  } else {                                                // a part of a split stripe: these go round all XCDs
+    const int r = (slot - a.whole_slots) * 8 + xcd;
+    const int unit = r / a.rem_k;
+    part = r % a.rem_k;
+    cs = a.rem_cs0 + unit / a.nstripes;
+    stripe = unit % a.nstripes;
+    tps = a.rem_tps;
+  }
   if (cs >= 2 * a.nchunks) return;
   const int side = cs & 1, c = cs >> 1;
   const int ne = min(a.S, a.n - c * a.S);                 // edges in this chunk
@@ -261,8 +277,8 @@ k_flash(FlashArgs a) {
 
   // ---- streamed tiles, register-staged prefetch of the next tile
   const int ntiles_all = (n_y + TY - 1) / TY;
-  const int t_begin = part * a.tps;
-  const int ntiles = min(ntiles_all, t_begin + a.tps);     // this part streams tiles [t_begin, ntiles); may be empty
+  const int t_begin = part * tps;
+  const int ntiles = min(ntiles_all, t_begin + tps);       // this part streams tiles [t_begin, ntiles); may be empty
   // Per-thread staging slots: which row / float4 of a tile this thread moves (see StageMap).
   typedef StageMap<NK, TY> SM;
   v4f stage[NU];                                           // plain vectors: a struct copy from global memory would pin the array in memory
@@ -533,7 +549,17 @@ k_flash(FlashArgs a) {
   for (int t = t_begin; t + 1 < ntiles; ++t) do_tile(t, std::true_type());
   if (t_begin < ntiles) do_tile(ntiles - 1, std::false_type());
 
-  // ---- epilogue
+  // ---- epilogue: the part's statistics and unnormalised gradient rows (row x of the chunk-side at index x)
+  float* ml_out = a.ml + ((size_t)part * 2 * a.B + x_base) * 2;
+  float* o_out = a.out + ((size_t)part * 2 * a.B + x_base) * dk;
+  if (slot >= a.whole_slots && part > 0) {                // parts 1.. of a split stripe
+    const size_t xr = (size_t)(part - 1) * a.rem_rows + (size_t)(cs - a.rem_cs0) * a.trows;
+    ml_out = a.mlx + xr * 2;
+    o_out = a.outx + xr * dk;
+  } else if (slot >= a.whole_slots) {                     // part 0 of a split stripe: the regular place
+    ml_out = a.ml + x_base * 2;
+    o_out = a.out + x_base * dk;
+  }
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
     if (PASS == 3) {
@@ -546,8 +572,7 @@ k_flash(FlashArgs a) {
     if (PASS == 1) {
       float ltot = lrun[b] + __shfl_xor(lrun[b], 16);
       ltot += __shfl_xor(ltot, 32);
-      if (g == 0 && xv[b])
-        *reinterpret_cast<float2*>(a.ml + (((size_t)part * 2 * a.B) + x_base + x[b]) * 2) = make_float2(mrun[b], ltot);
+      if (g == 0 && xv[b]) *reinterpret_cast<float2*>(ml_out + (size_t)x[b] * 2) = make_float2(mrun[b], ltot);
     }
     float ws = wsum[b];
     if (L2) {
@@ -560,7 +585,7 @@ k_flash(FlashArgs a) {
       ot.x += __shfl_xor(ot.x, 32); ot.y += __shfl_xor(ot.y, 32); ot.z += __shfl_xor(ot.z, 32); ot.w += __shfl_xor(ot.w, 32);
     }
     if (!xv[b]) continue;
-    float* orow = a.out + ((size_t)part * 2 * a.B + x_base + x[b]) * dk;
+    float* orow = o_out + (size_t)x[b] * dk;
     store_orow<NC, L2 != 0>(orow, xrow[b], ws, dk, g, oacc[b]);
     if (VT && g == 0 && 16 * NC < dk) {
       float4 o = ot;
@@ -815,6 +840,41 @@ k_flash_bwd(FlashArgs a) {
   }
 }
 
+// Merges the parts of the split stripes of pass 1 into the regular place, so that every later kernel sees one
+// part: m = max_p m_p, l = sum_p l_p exp(m_p - m), O = sum_p O_p exp(m_p - m), parts in their order.  One group of
+// 32 lanes per row; the group reads every part's statistics before its first lane overwrites part 0's.
+__global__ void __launch_bounds__(256) k_flash_merge(FlashArgs a) {
+  const int grp = threadIdx.x >> 5, l = threadIdx.x & 31;
+  const long rrow = (long)blockIdx.x * 8 + grp;
+  if (rrow >= a.rem_rows) return;
+  const int cs = a.rem_cs0 + (int)(rrow / a.trows), x = (int)(rrow % a.trows);
+  const int side = cs & 1, c = cs >> 1;
+  if (x >= min(a.S, a.n - c * a.S)) return;
+  const size_t row = (size_t)side * a.B + (size_t)c * a.S + x;
+  float2 v[MAR_MAX_PARTS];
+  v[0] = reinterpret_cast<const float2*>(a.ml)[row];
+#pragma unroll
+  for (int p = 1; p < MAR_MAX_PARTS; ++p)
+    v[p] = p < a.rem_k ? reinterpret_cast<const float2*>(a.mlx)[(size_t)(p - 1) * a.rem_rows + rrow] : make_float2(-3.0e38f, 0.f);
+  float mx = v[0].x;
+#pragma unroll
+  for (int p = 1; p < MAR_MAX_PARTS; ++p) mx = fmaxf(mx, v[p].x);
+  float fac[MAR_MAX_PARTS], ls = 0.f;
+#pragma unroll
+  for (int p = 0; p < MAR_MAX_PARTS; ++p) { fac[p] = __expf(v[p].x - mx); ls += fac[p] * v[p].y; }
+  float* o0 = a.out + row * a.dk;
+  for (int k = 4 * l; k < a.dk; k += 128) {
+    float4 o = *reinterpret_cast<const float4*>(o0 + k);
+    o.x *= fac[0]; o.y *= fac[0]; o.z *= fac[0]; o.w *= fac[0];
+    for (int p = 1; p < a.rem_k; ++p) {
+      const float4 q = *reinterpret_cast<const float4*>(a.outx + ((size_t)(p - 1) * a.rem_rows + rrow) * a.dk + k);
+      o.x += fac[p] * q.x; o.y += fac[p] * q.y; o.z += fac[p] * q.z; o.w += fac[p] * q.w;
+    }
+    *reinterpret_cast<float4*>(o0 + k) = o;
+  }
+  if (l == 0) reinterpret_cast<float2*>(a.ml)[row] = make_float2(mx, ls);
+}
+
 // ------------------------------------------------------------------- launchers -----
 int mar_flash_supported(int dk) { return dk >= 4 && dk <= 400; }
 // Streamed rows per tile of the instantiation that serves dk: pass 1 / 3, and pass 2 (whose widest
@@ -863,7 +923,15 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   a.sy = pass == 1 ? d.sy1 : (pass == 2 ? d.sy2 : 1);
   a.tps = pass == 1 ? d.tps1 : (pass == 2 ? d.tps2 : (1 << 30));
   a.sy_ml = d.sy1; a.roles = d.roles;
-  const dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
+  dim3 grid((unsigned)(8 * ((ncs + 7) / 8) * a.nstripes * a.sy));
+  a.whole_slots = 0x7fffffff; a.rem_cs0 = ncs; a.rem_k = 1; a.rem_tps = 0; a.rem_rows = 0; a.mlx = nullptr; a.outx = nullptr;
+  if (pass == 1 && d.rem_k > 1 && b.n == d.B) {            // full batch: split the stripes beyond the last whole round
+    a.whole_slots = d.rem_cs0 / 8 * a.nstripes;
+    a.rem_cs0 = d.rem_cs0; a.rem_k = d.rem_k; a.rem_tps = d.rem_tps; a.rem_rows = d.rem_rows;
+    a.mlx = L.mlx; a.outx = L.gQx;
+    const int rem_wgs = (ncs - d.rem_cs0) * a.nstripes * d.rem_k;
+    grid = dim3((unsigned)(8 * (a.whole_slots + (rem_wgs + 7) / 8)));
+  }
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;
 #ifndef MAR_BWD_TAIL_MFMA
@@ -875,4 +943,17 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   if (nk <= 32) return launch_sized<32, 8, 0, 64, 1, 8, 0, MAR_BWD_XB, 64>(a, pass, l2, grid, st);
   if (nk <= 64) return launch_sized<64, 16, 0, 32, 1, 16, 0, 1, 32>(a, pass, l2, grid, st);
   return launch_sized<100, 25, 0, 32, 1, 25, 0, 1, MAR_BWD_WIDE_TY>(a, pass, l2, grid, st);
+}
+
+int mar_flash_wgs_per_cu(int dk, int pass) { return pass == 2 ? (dk / 4 <= 32 ? MAR_BWD_WAVES : 2) : (dk / 4 <= 64 ? 2 : 1); }
+
+hipError_t mar_launch_flash_merge(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
+  const MarDims& d = c->dm;
+  if (d.rem_k <= 1 || b.n != d.B) return hipSuccess;
+  FlashArgs a = {};
+  a.ml = c->L.ml; a.mlx = c->L.mlx; a.out = c->L.gQ; a.outx = c->L.gQx;
+  a.n = b.n; a.B = d.B; a.S = d.S; a.dk = d.dk; a.trows = (d.S + 63) & ~63;
+  a.rem_cs0 = d.rem_cs0; a.rem_k = d.rem_k; a.rem_rows = d.rem_rows;
+  hipLaunchKernelGGL(k_flash_merge, dim3((unsigned)((d.rem_rows + 7) / 8)), dim3(256), 0, st, a);
+  return hipGetLastError();
 }

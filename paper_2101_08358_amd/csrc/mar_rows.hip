@@ -249,7 +249,6 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
 // Pass 1 leaves, per part p of a stripe, the softmax reference m_p, the sum l_p and the unnormalised
 // O_p = sum_j exp(a_j - m_p) n_j.  merge_parts turns them into the log-sum-exp and one factor per part,
 // fac_p = exp(m_p - m) / l with m = max m_p and l = sum_p l_p exp(m_p - m), so that gq = sum_p fac_p O_p.
-#define MAR_MAX_PARTS 8
 
 __device__ __forceinline__ float merge_parts(const float* __restrict__ ml, size_t row, size_t part_rows, int sy1,
                                              float (&fac)[MAR_MAX_PARTS]) {
