@@ -193,6 +193,7 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
   if (!workspace || ((uintptr_t)workspace & 255)) return fail(MAR_EINVAL, "workspace must be non-NULL and 256-byte aligned");
   const size_t need = carve(d, nullptr, nullptr);
   if (workspace_bytes < need) return fail(MAR_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  { const hipError_t e_ = mar_flash_prepare(); if (e_ != hipSuccess) return hip_fail(e_, "kernel attributes"); }
   mar_ctx* c = new (std::nothrow) mar_ctx();
   if (!c) return fail(MAR_ENOMEM, "out of host memory");
   c->cfg = *cfg; c->dm = d;

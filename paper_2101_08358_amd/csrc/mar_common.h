@@ -142,5 +142,6 @@ hipError_t mar_launch_rank_metrics(const int32_t* ranks, int64_t n, const int32_
 int mar_flash_supported(int dk);
 int mar_flash_tile_rows(int dk, int pass);
 int mar_flash_stripe_rows(int dk, int pass);
+hipError_t mar_flash_prepare();   // once per process and device before the first contraction launch (LDS size limits)
 int mar_flash_wgs_per_cu(int dk, int pass);        // workgroups of a pass that a CU holds at once
 hipError_t mar_launch_flash_merge(const mar_ctx* c, const MarBatch& b, hipStream_t st);   // after pass 1: merges split stripes

@@ -84,6 +84,23 @@ __device__ __forceinline__ float buf_load1(BufRsrc r, int voff, int soff) {
   return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
 }
 #define MAR_BUF_NOWHERE 0x40000000                        // a per-lane offset beyond every descriptor's size: loads 0
+// The same load with LDS as its destination: lane i's 16 bytes land at LDS byte address lds_addr + 16 i, without
+// passing through registers (zeros beyond the descriptor's size).  Written as an instruction so that the compiler
+// does not make every later LDS read wait for it; its completion is observed through a register load issued
+// behind it (memory operations of a wave complete in order).  The descriptor is given as its four words.
+typedef int v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4i buf_words(const void* base, uint32_t bytes) {
+  const unsigned long long b = (unsigned long long)base;
+  return (v4i){(int)(unsigned)b, (int)((unsigned)(b >> 32) & 0xffffu), (int)bytes, 0x00020000};
+}
+// `token` ties later code to the instruction: a value that passes through it unchanged.
+__device__ __forceinline__ void buf_load4_to_lds(v4i words, unsigned lds_addr, int voff, int soff, int& token) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, %4 offen lds"
+               : "+v"(token) : "s"(lds_addr), "v"(voff), "s"(words), "s"(soff));
+}
+__device__ __forceinline__ unsigned lds_address(const float* p) {
+  return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const float*)p;
+}
 
 
 // A operands of the second product O^T[c][x] += sum_y Y[y][c] W[y][x] for one streamed row y.
@@ -189,17 +206,34 @@ struct StageMap {
 // that this occupancy leaves to a wave, and does not trade spills for a higher occupancy.
 #define MAR_WAVES_PER_SIMD(n) __attribute__((amdgpu_waves_per_eu(n, n)))
 
-template <int NK, int NC, int VT, int TY, int XB, int PASS, int L2>
+// LDS of k_flash: one tile of the streamed matrix (DMA: two, unpadded) and, behind them, the streamed rows' squared
+// norms (TransE), one set per tile buffer.
+template <int NK, int TY, int DMA>
+struct FwdGeom {
+  static constexpr int PITCH = DMA ? FlashGeom<NK>::KW : FlashGeom<NK>::PITCH;
+  static constexpr int TILE = TY * PITCH + 32;                          // floats per tile buffer
+  static constexpr int NBUF = DMA ? 2 : 1;
+  static constexpr size_t LDS_BYTES = (size_t)NBUF * (TILE + TY) * 4;
+};
+
+// DMA (compile time): the row width is exactly 4 NK floats, so a tile is one contiguous block of memory and is
+// copied into LDS by buffer loads that write LDS directly (16 bytes per lane, 1 KB per wave instruction, zeros
+// beyond the chunk's rows), two tiles ahead of their use in two alternating buffers: no staging registers, no
+// LDS stores, one barrier per tile.  Otherwise tiles pass through registers into one padded LDS buffer.
+template <int NK, int NC, int VT, int TY, int XB, int PASS, int L2, int DMA>
 __global__ void __launch_bounds__(256) MAR_WAVES_PER_SIMD((NK * XB <= 64 ? 2 : 1))
 k_flash(FlashArgs a) {
   typedef FlashGeom<NK> GM;
-  constexpr int PITCH = GM::PITCH;
+  typedef FwdGeom<NK, TY, DMA> FG;
+  constexpr int PITCH = FG::PITCH;
   constexpr int N16 = GM::N16, NT = GM::NT;
   constexpr int PD = N16 <= 8 ? N16 : 4;                  // float4 fragments of the score product kept in flight
-  constexpr int NU = StageMap<NK, TY>::NU;                // float4 units staged per thread
+  constexpr int NU = DMA ? 1 : StageMap<NK, TY>::NU;      // float4 units staged per thread
   constexpr int SR = 64 * XB;                             // stationary rows per workgroup
-  __shared__ __attribute__((aligned(16))) float tile[TY * PITCH + 32];
-  __shared__ float auy[TY];                               // per streamed row: squared norm (TransE)
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  const float* tile = (const float*)__builtin_assume_aligned(smem, 16);   // the tile being read
+  float* const auy_all = smem + FG::NBUF * FG::TILE;      // [NBUF][TY] per streamed row: squared norm (TransE)
+  const float* auy = auy_all;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, m = lane & 15;
@@ -320,7 +354,36 @@ k_flash(FlashArgs a) {
     }
     if (L2) st_auy = buf_load1(yysrc, (int)(threadIdx.x % TY) * 4, t * TY * 4);
   };
-  if (t_begin < ntiles) load_tile(t_begin);
+  // DMA path: wave w copies the tile's 1 KB pieces w, w + 4, ... ; a register load issued behind them is the
+  // fence: memory operations complete in order, so once its value is there the pieces are in LDS.
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const v4i ywords = buf_words(a.Y + y_base * dk, (uint32_t)n_y * dk * 4);
+  float fence = 0.f;
+  int token = 0;
+  constexpr int NCH = TY * NK / 64;                        // 1 KB pieces per tile
+  constexpr int NCW = (NCH + 3) / 4;                       // pieces per wave
+  static_assert(!DMA || (TY * NK) % 64 == 0, "a tile is a whole number of 1 KB pieces");
+  // piece q of this wave (0 <= q < NCW) of tile t into buffer `buf`; after its last piece the wave issues the fence load
+  auto dma_piece = [&](int t, int buf, int q) {
+    const int tofs = t * TY * dk * 4;
+    const int c = 4 * q + wave_s;
+    if (c < NCH) buf_load4_to_lds(ywords, lds_address(smem) + (buf * FG::TILE + c * 256) * 4, lane * 16, tofs + c * 1024, token);
+    if (q == NCW - 1) {
+      // the fence load's offset passes through the copies, so it is issued behind them
+      if (L2) st_auy = buf_load1(yysrc, (int)(threadIdx.x % TY) * 4 + token, t * TY * 4);
+      else fence = buf_load1(ysrc, token, tofs);
+    }
+  };
+  auto dma_tile = [&](int t, int buf) {
+#pragma unroll
+    for (int q = 0; q < NCW; ++q) dma_piece(t, buf, q);
+  };
+  // the fence value is consumed (for TransE: stored) before the barrier that publishes tile t in buffer `buf`
+  auto dma_land = [&](int buf) {
+    if (L2) auy_all[buf * TY + threadIdx.x % TY] = st_auy;
+    else asm volatile("" : : "v"(fence));
+  };
+  if (t_begin < ntiles) { if (DMA) dma_tile(t_begin, 0); else load_tile(t_begin); }
 
   // fragments of the score product: q16[s] = Y[yb*16 + m][16s + 4g .. +3], q1[j] the tail columns
   float4 q16[PD];
@@ -340,12 +403,12 @@ k_flash(FlashArgs a) {
     for (int u = 0; u < NU; ++u) {
       int gofs, lofs;
       slot_of(u, gofs, lofs);
-      if (lofs >= 0) reinterpret_cast<v4f*>(tile)[lofs] = stage[u];
+      if (lofs >= 0) reinterpret_cast<v4f*>(smem)[lofs] = stage[u];
     }
-    if (L2) auy[threadIdx.x % TY] = st_auy;                // threads that share a row write the same value
+    if (L2) auy_all[threadIdx.x % TY] = st_auy;            // threads that share a row write the same value
   };
   if (t_begin < ntiles) {
-    stage_tile();
+    if (DMA) dma_land(0); else stage_tile();
     __syncthreads();
   }
 
@@ -356,7 +419,15 @@ k_flash(FlashArgs a) {
   // join.
   auto do_tile = [&](const int t, auto has_next_c) __attribute__((always_inline)) {
     constexpr bool HAS_NEXT = decltype(has_next_c)::value;
-    if (HAS_NEXT) load_tile(t + 1);
+    const int buf = DMA ? (t - t_begin) & 1 : 0;
+    if (DMA) {
+      tile = (const float*)__builtin_assume_aligned(smem + buf * FG::TILE, 16);
+      auy = auy_all + buf * TY;
+    }
+    constexpr int CPB = (NCW + TY / 16 - 1) / (TY / 16);   // DMA: pieces per wave issued inside one block,
+    constexpr int DSTEP = N16 / CPB > 0 ? N16 / CPB : 1;   // one every DSTEP steps of its score product
+    static_assert(!DMA || CPB <= N16, "more pieces per block than steps to put them in");
+    if (HAS_NEXT && !DMA) load_tile(t + 1);
     const int y0 = t * TY;
     const int nblk = HAS_NEXT ? TY / 16 : min(TY / 16, (n_y - y0 + 15) / 16);
     load_head(0);
@@ -386,6 +457,12 @@ k_flash(FlashArgs a) {
         for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.z, xf[b][4 * s + 2], tacc[b]);
 #pragma unroll
         for (int b = 0; b < XB; ++b) tacc[b] = mfma16(yv.w, xf[b][4 * s + 3], tacc[b]);
+        // the next tile's pieces are issued a few at a time between the matrix instructions: a burst of them would
+        // hold the wave at the memory pipeline's queue
+        if (DMA && HAS_NEXT && s % DSTEP == 0 && s / DSTEP < CPB) {
+          const int q = yb * CPB + s / DSTEP;
+          if (q < NCW) dma_piece(t + 1, buf ^ 1, q);
+        }
         if (N16 > PD) __builtin_amdgcn_sched_barrier(0);    // keeps the read PD fragments ahead of its use
       }
 #pragma unroll
@@ -541,9 +618,14 @@ k_flash(FlashArgs a) {
         a.R[((size_t)cs * (a.tpitch / 16) + (size_t)(t * (TY / 16) + g % (TY / 16))) * a.trows + x[b]] = ref_blk[b];
     }
     if (HAS_NEXT) {
-      __syncthreads();                                     // every wave is done with this tile
-      stage_tile();
-      __syncthreads();
+      if (DMA) {
+        dma_land(buf ^ 1);
+        __syncthreads();                                   // tile t + 1 is in LDS; every wave is done with tile t
+      } else {
+        __syncthreads();                                   // every wave is done with this tile
+        stage_tile();
+        __syncthreads();
+      }
     }
   };
   for (int t = t_begin; t + 1 < ntiles; ++t) do_tile(t, std::true_type());
@@ -893,7 +975,15 @@ int mar_flash_stripe_rows(int dk, int pass) { return pass == 2 && dk / 4 <= 32 ?
 // NK, NC, VT, TY, XB: pass 1 / 3 instantiation; BNC, BVT, BXB, BTY: pass 2's.
 template <int NK, int NC, int VT, int TY, int XB, int BNC, int BVT, int BXB, int BTY>
 static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, hipStream_t st) {
-#define FL(P, L) hipLaunchKernelGGL((k_flash<NK, NC, VT, TY, XB, P, L>), grid, dim3(256), 0, st, a)
+  // rows of exactly 4 NK floats take the direct-to-LDS copy (widths whose unpadded pitch is a multiple of 64 floats
+  // would put every row of a block in the same LDS banks and stay on the padded register path)
+  constexpr bool CAN_DMA = (4 * NK) % 64 != 0;
+  constexpr int DM = CAN_DMA ? 1 : 0;
+  constexpr size_t lds_dma = FwdGeom<NK, TY, DM>::LDS_BYTES, lds_reg = FwdGeom<NK, TY, 0>::LDS_BYTES;
+  const bool dma = CAN_DMA && a.dk == 4 * NK;
+#define FL(P, L) do { \
+    if (dma) hipLaunchKernelGGL((k_flash<NK, NC, VT, TY, XB, P, L, DM>), grid, dim3(256), lds_dma, st, a); \
+    else hipLaunchKernelGGL((k_flash<NK, NC, VT, TY, XB, P, L, 0>), grid, dim3(256), lds_reg, st, a); } while (0)
   if (pass == 1) { if (l2) FL(1, 1); else FL(1, 0); }
   else if (pass == 2) {
     if (l2) hipLaunchKernelGGL((k_flash_bwd<NK, BNC, BVT, BTY, BXB, 1>), grid, dim3(256), 0, st, a);
@@ -903,6 +993,19 @@ static hipError_t launch_sized(const FlashArgs& a, int pass, int l2, dim3 grid, 
 #undef FL
   return hipGetLastError();
 }
+
+// Kernels whose LDS exceeds the default limit of a launch must be told so once per process and device.
+template <int NK, int NC, int VT, int TY, int XB>
+static hipError_t prepare_sized() {
+  constexpr size_t lds = FwdGeom<NK, TY, 1>::LDS_BYTES;
+  if (lds <= 64 * 1024) return hipSuccess;
+  hipError_t e = hipSuccess;
+#define PREP(P, L) if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_flash<NK, NC, VT, TY, XB, P, L, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+  PREP(1, 0); PREP(1, 1); PREP(3, 0); PREP(3, 1);
+#undef PREP
+  return e;
+}
+hipError_t mar_flash_prepare() { return prepare_sized<100, 25, 0, 32, 1>(); }
 
 hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32_t* rank_dst, int32_t* rank_src,
                             hipStream_t st) {
