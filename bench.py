@@ -232,6 +232,67 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
     return rec
 
 
+def run_host_tables(name, depth, steps, warmup, nodes, edges):
+    """Out-of-memory training (Sec. 3): node table and accumulators in pinned host memory, `depth` batches in
+    flight.  Returns the record; the host link is what bounds it."""
+    import torch
+    import synth
+    import paper_2101_08358_amd as mar
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(name)
+    w = w.scaled(num_nodes=nodes or min(w.num_nodes, 10_000_000), num_edges=edges or min(w.num_edges, 20_000_000))
+    src, rel, dst = synth.make_graph(w.num_nodes, w.num_rels, w.num_edges, w.node_zipf, w.rel_zipf, seed=w.seed, device=dev)
+    t0 = time.perf_counter()
+    h_ne = torch.empty((w.num_nodes, w.dim), dtype=torch.float32, pin_memory=True)
+    h_ns = torch.zeros((w.num_nodes, w.dim), dtype=torch.float32, pin_memory=True)
+    step_rows = 1 << 20                                          # filled on the device, copied out in slices
+    g = torch.Generator(device=dev); g.manual_seed(w.seed)
+    for lo in range(0, w.num_nodes, step_rows):
+        hi = min(lo + step_rows, w.num_nodes)
+        h_ne[lo:hi].copy_(torch.randn((hi - lo, w.dim), device=dev, generator=g) * w.init_std)
+    d_re = torch.randn((w.num_rels, w.dim), device=dev, generator=g) * w.init_std
+    d_rs = torch.zeros((w.num_rels, w.dim), device=dev)
+    cfg = mar.MarConfig(w.num_nodes, w.num_rels, w.dim, w.model, w.batch_size, w.num_chunks, w.negs_per_chunk,
+                        w.deg_negs_per_chunk, w.lr, w.eps, w.init_std, w.seed)
+    nbytes = mar.mar_pipe_workspace_bytes(cfg, depth)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    pipe = mar.mar_pipe_create(cfg, h_ne, h_ns, d_re, d_rs, ws, nbytes, depth)
+    cn = w.num_chunks * w.negs_per_chunk
+    negs = [[torch.empty(cn, dtype=torch.int32, device=dev) for _ in range(2)] for _ in range(depth + 1)]
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    note("%s, host tables: %.1f GB pinned in %.1f s, workspace %.2f GB, depth %d" % (w.name, 8e-9 * w.dim * w.num_nodes,
+                                                                                   time.perf_counter() - t0, nbytes / 1e9, depth))
+    nb = w.num_edges // w.batch_size
+
+    def step(i):
+        lo = (i % nb) * w.batch_size
+        ns_, nd_ = negs[i % (depth + 1)]                         # fresh uniform negatives; the buffers of the batches in flight stay untouched
+        ns_.random_(0, w.num_nodes, generator=g); nd_.random_(0, w.num_nodes, generator=g)
+        mar.mar_pipe_submit(pipe, src[lo:lo + w.batch_size], rel[lo:lo + w.batch_size], dst[lo:lo + w.batch_size], w.batch_size,
+                            ns_, nd_, loss)
+
+    for i in range(warmup):
+        step(i)
+    mar.mar_pipe_drain(pipe)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(warmup, warmup + steps):
+        step(i)
+    mar.mar_pipe_drain(pipe)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    final = float(loss.item()) / w.batch_size
+    mar.mar_pipe_destroy(pipe)
+    return {"value": steps * w.batch_size / dt, "unit": "edges/s", "ms_per_step": dt / steps * 1e3,
+            "config": {"workload": "%s, node table and accumulators in pinned host memory, %d batches in flight" % (w.name, depth),
+                       "num_nodes": w.num_nodes, "dim": w.dim, "batch": w.batch_size, "chunks": w.num_chunks,
+                       "negs_per_chunk": w.negs_per_chunk, "negatives": "uniform ids (torch) drawn per step",
+                       "host_table_bytes": 8 * w.dim * w.num_nodes},
+            "final_loss_per_edge": final}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -244,6 +305,8 @@ def main():
     ap.add_argument("--other-edges", type=int, default=100_000_000, help="edge-list length of the other workloads' records")
     ap.add_argument("--nodes", type=int, default=0, help="shrink the node table (row width and batch geometry are unchanged)")
     ap.add_argument("--no-phase-events", action="store_true", help="time the steps without the per-phase HIP events")
+    ap.add_argument("--host-tables", type=int, default=0, metavar="DEPTH",
+                    help="measure out-of-memory training instead: node table in pinned host memory, DEPTH batches in flight")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -255,6 +318,15 @@ def main():
         from paper_2101_08358_amd import build
         build.build()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.host_tables:
+        name = args.workload or "social"
+        steps, warmup = args.steps or 60, args.warmup or 8
+        rec = run_host_tables(name, args.host_tables, steps, warmup, args.nodes, args.edges)
+        out = {"metric": "training edges/sec per MI355X, node table in host memory", "n_gpus": 1, "steps": steps, "warmup": warmup,
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
+        out.update(rec)
+        print(json.dumps(out))
+        return
     name = args.workload or "wide"
     steps, warmup = DEFAULT_STEPS.get(name, (100, 10))
     steps, warmup = args.steps or steps, args.warmup or warmup

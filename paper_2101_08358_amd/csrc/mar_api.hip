@@ -562,6 +562,7 @@ extern "C" int mar_pipe_submit(mar_pipe* p, const int32_t* src, const int32_t* r
   PIPE_TRY(hipStreamWaitEvent(st, ps.ev_in, 0), "step");
   PIPE_TRY(mar_launch_prep(c, ps.b_rank, nullptr, st), "gather kernel");
   PIPE_TRY(mar_launch_flash(c, ps.b_rank, 1, nullptr, nullptr, st), "score/softmax kernel");
+  PIPE_TRY(mar_launch_flash_merge(c, ps.b_rank, st), "stripe merge kernel");
   PIPE_TRY(mar_launch_chain(c, ps.b_rank, st), "chain-rule kernel");
   PIPE_TRY(mar_launch_flash(c, ps.b_rank, 2, nullptr, nullptr, st), "negative-gradient kernel");
   PIPE_TRY(mar_launch_reduce(c, ps.b_ids, loss_sum_out, nullptr, ps.sg.gsum, st), "reduce kernels");

@@ -76,6 +76,21 @@ def test_depth_one_is_the_resident_step_bit_for_bit(model, dim):
         assert np.array_equal(g, w), name
 
 
+def test_depth_one_is_the_resident_step_when_pass_one_splits_its_last_round():
+    """A batch large enough for the first contraction pass to split the stripes beyond its last whole round of
+    workgroups (96 chunk-sides x 7 stripes = 672 units on 512 slots): the merge of the parts belongs to the step
+    wherever the step is launched from."""
+    model, V, R, dim, B, C, N = mar.MODEL_DISTMULT, 30000, 3, 100, 21504, 48, 128
+    ne, ns, re_, rs, batches = _setup(model, V, R, dim, B, C, N, nb=3, seed=7, hot=0.05)
+    batches = [bt if bt[0].shape[0] == B else tuple(np.resize(x, B) if i < 3 else x for i, x in enumerate(bt)) for bt in batches]
+    got = _run_pipe(model, V, R, dim, B, C, N, 1, (ne, ns, re_, rs), batches)
+    want = _run_resident(model, V, R, dim, B, C, N, (ne, ns, re_, rs), batches)
+    for g, w, name in zip(got, want, ("node_emb", "node_state", "rel_emb", "rel_state", "loss")):
+        assert np.array_equal(g, w), name
+    # the first step's loss from tables of size 0.05: near 2 log N per edge, and the same number both ways
+    assert abs(want[4][0] / B - 2 * np.log(N)) < 0.5
+
+
 @pytest.mark.parametrize("depth", (2, 4))
 def test_depth_k_follows_the_oracle_with_staleness_k_minus_one(depth):
     """Warm accumulators (of the size of the squared gradients) make the update smooth in the gradient, so tables can

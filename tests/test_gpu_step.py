@@ -32,6 +32,15 @@ def test_one_step_other_widths(model, dim):
     print(check_step(out), flush=True)
 
 
+@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE))
+def test_one_step_when_pass_one_splits_its_last_round(model):
+    """96 chunk-sides x 7 stripes = 672 units of the first contraction pass on 512 workgroup slots: the stripes of
+    the last 24 chunk-sides are split into two parts over the negatives' tiles and merged afterwards."""
+    print("case", model, flush=True)
+    out = run_step_both(model, 30000, 3, 100, 21504, 48, 128, 21504, seed=40 + model)
+    print(check_step(out), flush=True)
+
+
 @pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE, DOT))
 def test_one_step_from_warm_state(model):
     """With accumulators of the size of G^2 the update is smooth in G: every element is compared."""
