@@ -69,7 +69,8 @@ def _tolerant(got, exp, S):
 
 
 @pytest.mark.parametrize("model", (0, 1, 2, 3))
-@pytest.mark.parametrize("shape", ((5000, 9, 100, 2000, 2, 1000, 1700), (300, 2, 50, 100, 10, 100, 100)))
+@pytest.mark.parametrize("shape", ((5000, 9, 100, 2000, 2, 1000, 1700), (300, 2, 50, 100, 10, 100, 100),
+                                   (2000, 3, 400, 512, 2, 300, 500), (2000, 3, 128, 512, 2, 300, 500)))
 def test_ranks_within_rounding_of_oracle(model, shape):
     V, R, dim, B, C, N, n = shape
     got, exp = _run(model, V, R, dim, B, C, N, n, seed=10 + model)

@@ -41,6 +41,12 @@ def test_one_step_when_pass_one_splits_its_last_round(model):
     print(check_step(out), flush=True)
 
 
+def test_short_batch_on_a_configuration_that_splits_full_batches():
+    """The same configuration with 20,000 of its 21,504 edges: short batches take no split (and leave the split's
+    buffers alone)."""
+    print(check_step(run_step_both(DISTMULT, 30000, 3, 100, 21504, 48, 128, 20000, seed=44)), flush=True)
+
+
 @pytest.mark.parametrize("model", (DISTMULT, COMPLEX, TRANSE, DOT))
 def test_one_step_from_warm_state(model):
     """With accumulators of the size of G^2 the update is smooth in G: every element is compared."""
