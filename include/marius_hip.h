@@ -47,6 +47,13 @@ extern "C" {
 #define MAR_MODEL_DOT      3   /* theta_s . theta_d (Sec. 5.1, "Embedding Models"): no relation parameters; */
                                /* rel ids are ignored (may be NULL) and relation rows are never touched  */
 
+/* Arithmetic of the two training contractions (scores with softmax and the edge-side gradient; the negatives'
+ * gradient).  The paper trains in fp32 (Sec. 5.1).  SPLIT_BF16 writes every fp32 operand as the sum of two bf16
+ * numbers and takes each product as three bf16 matrix products accumulated in fp32 (relative error of a product
+ * about 2^-16); it serves the bilinear models (DistMult, ComplEx, Dot) only, and evaluation always runs in fp32. */
+#define MAR_PRECISION_FP32        0
+#define MAR_PRECISION_SPLIT_BF16  1
+
 #define MAR_MAX_DIM 400        /* largest supported row width in floats                              */
 
 /* Problem statement (Sec. 2.1; hyperparameters of Table 1). */
@@ -64,6 +71,8 @@ typedef struct mar_config {
   float    eps;                 /* Adagrad epsilon, added outside the square root                    */
   float    init_std;            /* standard deviation of the N(0, std^2) initialisation              */
   uint64_t seed;                /* key of the counter-based generator                                */
+  int32_t  precision;           /* MAR_PRECISION_*: arithmetic of the two training contractions      */
+  int32_t  reserved;            /* must be 0                                                         */
 } mar_config;
 
 typedef struct mar_ctx mar_ctx;  /* opaque: host-side metadata only */

@@ -2,7 +2,7 @@
 
 The library is loaded on first use; importing the package needs no GPU.
 """
-from .binding import (MarConfig, MarDebugOut, MODEL_DISTMULT, MODEL_COMPLEX, MODEL_TRANSE, MODEL_DOT, NUM_PHASES,   # noqa: F401
+from .binding import (MarConfig, MarDebugOut, MODEL_DISTMULT, MODEL_COMPLEX, MODEL_TRANSE, MODEL_DOT, PRECISION_FP32, PRECISION_SPLIT_BF16, NUM_PHASES,   # noqa: F401
                       MarError, load_library, library_path, mar_workspace_bytes, mar_init_tables,
                       mar_sample_negatives, mar_train_batch, mar_eval_scores, mar_eval_filter, mar_rank_metrics, mar_rank_metrics_static,
                       mar_beta_buffer_sequence,

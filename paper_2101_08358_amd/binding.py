@@ -12,6 +12,7 @@ _LIB_PATH = os.environ.get("MARIUS_HIP_LIB") or os.path.join(_HERE, "libmarius_h
 _lib = None
 
 MODEL_DISTMULT, MODEL_COMPLEX, MODEL_TRANSE, MODEL_DOT = 0, 1, 2, 3
+PRECISION_FP32, PRECISION_SPLIT_BF16 = 0, 1
 NUM_PHASES = 6
 PHASE_NAMES = ("index", "gather", "score_softmax_gq", "neg_grad", "chain_rule", "reduce_adagrad")
 
@@ -27,7 +28,7 @@ class MarConfig(ctypes.Structure):
                 ("model", ctypes.c_int32), ("batch_size", ctypes.c_int32), ("num_chunks", ctypes.c_int32),
                 ("negs_per_chunk", ctypes.c_int32), ("deg_negs_per_chunk", ctypes.c_int32),
                 ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("init_std", ctypes.c_float),
-                ("seed", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("precision", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class MarDebugOut(ctypes.Structure):
@@ -246,12 +247,12 @@ class Trainer:
 
     def __init__(self, num_nodes, num_rels, dim, model, batch_size, num_chunks, negs_per_chunk, deg_negs_per_chunk=0,
                  lr=0.1, eps=1e-10, init_std=0.001, seed=0, device="cuda:0", node_emb=None, rel_emb=None,
-                 node_state=None, rel_state=None):
+                 node_state=None, rel_state=None, precision=0):
         import torch
         self.torch = torch
         self.device = torch.device(device)
         self.cfg = MarConfig(num_nodes, num_rels, dim, model, batch_size, num_chunks, negs_per_chunk,
-                             deg_negs_per_chunk, lr, eps, init_std, seed)
+                             deg_negs_per_chunk, lr, eps, init_std, seed, precision, 0)
         fill = node_emb is None
         f32 = dict(dtype=torch.float32, device=self.device)
 

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmarius_hip.so")
-SOURCES = ["mar_api.hip", "mar_index.hip", "mar_rows.hip", "mar_flash.hip", "mar_order.hip", "mar_metrics.hip"]
+SOURCES = ["mar_api.hip", "mar_index.hip", "mar_rows.hip", "mar_flash.hip", "mar_split.hip", "mar_order.hip", "mar_metrics.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

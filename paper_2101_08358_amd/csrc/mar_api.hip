@@ -46,6 +46,10 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   if (cfg->model < MAR_MODEL_DISTMULT || cfg->model > MAR_MODEL_DOT) return fail(MAR_EINVAL, "unknown model %d", cfg->model);
   if (cfg->dim < 1 || cfg->dim > MAR_MAX_DIM) return fail(MAR_ERANGE, "dim %d outside 1..%d", cfg->dim, MAR_MAX_DIM);
   if (cfg->model == MAR_MODEL_COMPLEX && (cfg->dim & 1)) return fail(MAR_EINVAL, "ComplEx needs an even dim");
+  if (cfg->precision != MAR_PRECISION_FP32 && cfg->precision != MAR_PRECISION_SPLIT_BF16) return fail(MAR_EINVAL, "unknown precision %d", cfg->precision);
+  if (cfg->precision == MAR_PRECISION_SPLIT_BF16 && cfg->model == MAR_MODEL_TRANSE)
+    return fail(MAR_EINVAL, "the split-precision contraction serves the bilinear models (DistMult, ComplEx, Dot) only");
+  if (cfg->reserved != 0) return fail(MAR_EINVAL, "reserved must be 0");
   if (cfg->batch_size < 1 || cfg->num_chunks < 1 || cfg->negs_per_chunk < 1)
     return fail(MAR_EINVAL, "batch_size, num_chunks and negs_per_chunk must be >= 1");
   if (cfg->batch_size % cfg->num_chunks) return fail(MAR_ERANGE, "batch_size must be a multiple of num_chunks");
@@ -67,15 +71,21 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   d->ipw_log2 = ids <= ((int64_t)1 << 22) ? 2 : 5;       // small id spaces: one byte per id, no atomics
   d->nwords = (ids + (1 << d->ipw_log2) - 1) >> d->ipw_log2;
   if (!mar_flash_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the contraction kernels", d->dk);
+  d->split = cfg->precision == MAR_PRECISION_SPLIT_BF16;
+  if (d->split && !mar_split_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the split-precision kernels", d->dk);
+  const int sp = d->split;
+  auto stripe_rows = [&](int pass) { return sp ? mar_split_stripe_rows(d->dk, pass) : mar_flash_stripe_rows(d->dk, pass); };
+  auto tile_rows = [&](int pass) { return sp ? mar_split_tile_rows() : mar_flash_tile_rows(d->dk, pass); };
+  auto wgs_per_cu = [&](int pass) { return sp ? mar_split_wgs_per_cu(d->dk, pass) : mar_flash_wgs_per_cu(d->dk, pass); };
   // Small batches give too few (chunk-side, 64-row stripe) workgroups to fill 256 CUs: let several
   // workgroups share a stripe, each streaming a slice of the other matrix, until a pass has at least
   // MAR_FLASH_TARGET_WGS workgroups (measured best for a 10,000-edge batch; the 50,000-edge shapes have
   // enough stripes and are not split).
   auto split = [&](int pass, int n_x, int n_y, int32_t* sy, int32_t* tps) {
     const long target = pass == 1 ? MAR_FLASH_TARGET_WGS1 : MAR_FLASH_TARGET_WGS2;
-    const int sr = mar_flash_stripe_rows(d->dk, pass);
+    const int sr = stripe_rows(pass);
     const long wgs = 2L * d->C * ((n_x + sr - 1) / sr);
-    const int ty = mar_flash_tile_rows(d->dk, pass);
+    const int ty = tile_rows(pass);
     const int ntiles = (n_y + ty - 1) / ty;
     long want = (target + wgs - 1) / wgs;
     if (want > 8) want = 8;
@@ -92,9 +102,10 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   // stripe split into rem_k parts (each streaming rem_tps tiles), so that the last round is short.
   d->rem_cs0 = 2 * d->C; d->rem_k = 1; d->rem_tps = 0; d->rem_rows = 0;
   if (d->sy1 == 1) {
-    const long slots = 256L * mar_flash_wgs_per_cu(d->dk, 1);
-    const long nstripes = (d->S + 63) / 64, groups = (2L * d->C + 7) / 8, per_group = 8 * nstripes;
-    const int ty = mar_flash_tile_rows(d->dk, 1);
+    const long slots = 256L * wgs_per_cu(1);
+    const int sr1 = stripe_rows(1);
+    const long nstripes = (d->S + sr1 - 1) / sr1, groups = (2L * d->C + 7) / 8, per_group = 8 * nstripes;
+    const int ty = tile_rows(1);
     const long ntiles = (d->N + ty - 1) / ty;
     const long full_rounds = groups * per_group / slots;
     const long whole_groups = full_rounds * slots / per_group;
@@ -103,6 +114,15 @@ static int check_config(const mar_config* cfg, MarDims* d) {
       long k = slots / rem_units;
       if (k > MAR_MAX_PARTS) k = MAR_MAX_PARTS;
       if (k > ntiles) k = ntiles;
+      if (sp) {
+        // the split-precision units are fewer and longer, and the remainder often exceeds half a round: take the
+        // number of parts whose last, partly filled round of parts is shortest
+        double best = 1e30;
+        for (long kk = 1; kk <= MAR_MAX_PARTS && kk <= ntiles; ++kk) {
+          const double cost = (double)((rem_units * kk + slots - 1) / slots) / (double)kk + 0.02 * (double)(kk - 1);
+          if (cost < best) { best = cost; k = kk; }
+        }
+      }
       if (k >= 2) {
         d->rem_cs0 = (int32_t)(8 * whole_groups);
         d->rem_tps = (int32_t)((ntiles + k - 1) / k);
@@ -161,8 +181,11 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.ml = (float*)take((size_t)d.sy1 * 2 * B * 2 * 4);
   l.gQx = (float*)take((size_t)(d.rem_k - 1) * (size_t)d.rem_rows * dk * 4);
   l.mlx = (float*)take((size_t)(d.rem_k - 1) * (size_t)d.rem_rows * 2 * 4);
-  l.T = (float*)take(2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)((d.N + 127) & ~127) * 4);
-  l.R = (float*)take(2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)(((d.N + 127) & ~127) / 16) * 4);
+  // the split-precision passes keep no weights: pass 2 computes the scores again
+  l.T = (float*)take(d.split ? 0 : 2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)((d.N + 127) & ~127) * 4);
+  l.R = (float*)take(d.split ? 0 : 2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)(((d.N + 127) & ~127) / 16) * 4);
+  l.Kimg = (char*)take(d.split ? 2 * (size_t)d.C * (size_t)((d.N + 31) / 32) * mar_split_image_bytes(d.dk) : 0);
+  l.Qimg = (char*)take(d.split ? 2 * (size_t)d.C * (size_t)((d.S + 31) / 32) * mar_split_image_bytes(d.dk) : 0);
   l.G = (float*)take(n_pos * dk * 4);
   l.carry = (float*)take(blocks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);
@@ -194,6 +217,7 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
   const size_t need = carve(d, nullptr, nullptr);
   if (workspace_bytes < need) return fail(MAR_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
   { const hipError_t e_ = mar_flash_prepare(); if (e_ != hipSuccess) return hip_fail(e_, "kernel attributes"); }
+  { const hipError_t e_ = mar_split_prepare(); if (e_ != hipSuccess) return hip_fail(e_, "kernel attributes"); }
   mar_ctx* c = new (std::nothrow) mar_ctx();
   if (!c) return fail(MAR_ENOMEM, "out of host memory");
   c->cfg = *cfg; c->dm = d;

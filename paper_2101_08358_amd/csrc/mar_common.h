@@ -39,6 +39,8 @@ struct MarLayout {
   float*    T;            // [2*chunks][S rounded up to 64][N rounded up to 128] softmax weights exp(score - reference)
                           // (TransE: divided by the distance), pass 1 -> pass 2
   float*    R;            // [2*chunks][N rounded up to 128, / 16][S rounded up to 64] the reference each 16-negative block of T was written with
+  char*     Kimg;         // split precision: [2*chunks][N / 32 rounded up][image] bf16 hi/lo planes of Km's rows
+  char*     Qimg;         // split precision: [2*chunks][S / 32 rounded up][image] the same of Q's rows
   float*    G;            // [roles*n + 2*cn*sy2][dk] gradient rows: edge-side occurrence k < roles*n at row k, part i
                           // of negative occurrence k at row roles*n + (k - roles*n)*sy2 + i
   float*    carry;        // [reduce blocks][2][dk] partial sums of segments that cross workgroup borders
@@ -63,6 +65,7 @@ struct MarDims {
   int64_t nwords;                  // words of the touched-id map
   int32_t ipw_log2;                // ids per word: 5 = one bit per id (atomic marks), 2 = one byte per id (plain stores)
   int32_t sort_passes, sort_bits;  // radix sort of the gradient rows by rank: passes, bits per pass
+  int32_t split;                   // the contraction passes run in split precision (bf16 hi + lo operands)
   int32_t index_after_gather;      // launch order of a step: gather first, index build behind it (large batches)
 };
 
@@ -145,3 +148,11 @@ int mar_flash_stripe_rows(int dk, int pass);
 hipError_t mar_flash_prepare();   // once per process and device before the first contraction launch (LDS size limits)
 int mar_flash_wgs_per_cu(int dk, int pass);        // workgroups of a pass that a CU holds at once
 hipError_t mar_launch_flash_merge(const mar_ctx* c, const MarBatch& b, hipStream_t st);   // after pass 1: merges split stripes
+// Split-precision passes (mar_split.hip): geometry for the planning of a configuration, and the launches.
+int mar_split_supported(int dk);
+int mar_split_stripe_rows(int dk, int pass);
+int mar_split_tile_rows();
+int mar_split_wgs_per_cu(int dk, int pass);
+size_t mar_split_image_bytes(int dk);
+hipError_t mar_split_prepare();
+hipError_t mar_launch_split_images(const mar_ctx* c, const MarBatch& b, hipStream_t st);

@@ -969,7 +969,9 @@ hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, 
   }
 #undef PREP
 #undef PREP3
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && c->dm.split) e = mar_launch_split_images(c, b, st);
+  return e;
 }
 
 hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t* dst_off, const int32_t* dst_ids,

@@ -1,0 +1,475 @@
+// Split-precision variant of the two contraction passes for the bilinear models (gfx950).
+//
+// Every fp32 operand is written as the sum of two bf16 numbers, v = hi + lo with hi = bf16(v) and
+// lo = bf16(v - hi) (v - hi is exact in fp32), and every product a b is taken as
+//     a_hi b_hi + a_lo b_hi + a_hi b_lo
+// on the bf16 matrix pipe (v_mfma_f32_16x16x32_bf16, fp32 accumulation), which runs at 16 times the fp32 matrix
+// rate.  The dropped term a_lo b_lo and the rounding of the lo parts are of relative size 2^-16 .. 2^-17 per
+// product, far inside the 1e-4 bars of the step.  The passes compute what k_flash / k_flash_bwd compute, in the
+// same formats (softmax statistics, weights T, references R, gradient rows), so everything around them is shared.
+//
+// Operand images.  The streamed matrix of a pass (pass 1: the chunk's negatives, pass 2: the chunk's edge-side
+// operands) is prepared once per step as "images": per chunk-side and tile of 32 rows a hi plane and a lo plane,
+// [32][PA bytes] each, row = 32 NS bf16 values (the row padded with zeros to a multiple of 32 columns) at a pitch
+// PA chosen so that both kinds of LDS read below are free of bank conflicts.  An image is one contiguous block
+// and is copied into LDS by buffer loads that write LDS directly, one tile ahead, in two alternating buffers.
+//
+// Lane layouts (lane = 16 g + m):
+//   v_mfma_f32_16x16x32_bf16: A lane holds row m, contraction slots 8g .. 8g+7; B lane holds column m, the same
+//   slots; D lane holds column m, rows 4g .. 4g+3.  Which contraction index a slot stands for is free as long as A
+//   and B agree.
+//   Score product S^T[y][x] = sum_c Y[y][c] X[x][c]: A = Y from LDS (16-byte read of row y = m, columns 32 s + 8g ..),
+//   B = X fragments held in registers.  D: lane (g, m) gets S^T[4g + r][x = m], for the two 16-row blocks of a tile.
+//   Second product O^T[c][x] += sum_y Y[y][c] W[y][x] over the tile's 32 rows: B = W built from the lane's own 8
+//   score registers, slot kk <-> y = 4g + kk (kk < 4), 16 + 4g + kk - 4 (kk >= 4).  A = Y^T: lane (g, m) needs
+//   Y[y of slot kk][16 cb + m] -- a column access of a row-major plane, which the LDS transpose read
+//   (ds_read_b64_tr_b16) provides: within a group of 16 lanes, lane i passes the address of 4 consecutive 16-bit
+//   values and receives, as its j-th value, value (i % 4) of lane 4j + i / 4.  With lane i pointing at row
+//   4g + i / 4 (+ 16 for the second block), columns 16 cb + 4 (i % 4) .. +3, lane m receives Y[4g + j][16 cb + m].
+#include <type_traits>
+
+#include "mar_common.h"
+#include "mar_flash.h"
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4f mfma_bf(v8bf a, v8bf b, v4f c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// v = hi + lo, both bf16 (round to nearest even)
+__device__ __forceinline__ void split8(const float (&v)[8], v8bf& hi, v8bf& lo) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const __bf16 h = (__bf16)v[i];
+    hi[i] = h;
+    lo[i] = (__bf16)(v[i] - (float)h);
+  }
+}
+
+// Row pitch in bytes of a plane whose rows hold `rowb` bytes: the pitch in 4-byte banks, mod 64, must be one of
+// 12, 28, 36, 52 -- then the 16 rows of a 16-byte fragment read fall into 16 different groups of 4 banks, and the 4
+// rows of a transpose read into 4 different groups of 8 banks.
+constexpr int sp_pitch(int rowb) {
+  for (int pad = 16; pad <= 256; pad += 16) {
+    const int p = ((rowb + pad) / 4) % 64;
+    if (p == 12 || p == 28 || p == 36 || p == 52) return rowb + pad;
+  }
+  return rowb + 16;
+}
+constexpr int SP_TY = 32;                                  // rows per image
+constexpr int sp_plane(int ns) { return SP_TY * sp_pitch(64 * ns); }
+constexpr int sp_image(int ns) { return (2 * sp_plane(ns) + 1023) / 1024 * 1024; }
+
+template <int NS>
+struct SplitGeom {
+  static constexpr int PA = sp_pitch(64 * NS);
+  static constexpr int PLANE = sp_plane(NS);
+  static constexpr int IMG = sp_image(NS);
+  static constexpr int NCH = IMG / 1024;                   // 1 KB pieces of an image
+  static constexpr int NCW = (NCH + 3) / 4;                // pieces per wave
+  static constexpr size_t LDS_BYTES = 2 * (size_t)IMG;
+};
+
+// Contraction steps of 32 columns and 16-column output blocks that serve dk, and the instantiation's x-blocks per wave.
+static inline int sp_ns(int dk) { return dk <= 64 ? 2 : (dk <= 128 ? 4 : (dk <= 256 ? 8 : 13)); }
+static inline int sp_ncb(int dk) { return dk <= 64 ? 4 : (dk <= 112 ? 7 : (dk <= 128 ? 8 : (dk <= 208 ? 13 : (dk <= 256 ? 16 : 25)))); }
+
+__device__ __forceinline__ unsigned lds_address_b(const char* p) {
+  return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
+}
+__device__ __forceinline__ v4s lds_read_tr(const char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p);
+}
+__device__ __forceinline__ v8bf join8(v4s a, v4s b) {
+  return __builtin_bit_cast(v8bf, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// O^T[c][x] += sum over the tile's 32 rows of Y[y][c] W[y][x], all NCB 16-column blocks; W is given split.  Blocks
+// are taken a few at a time so that consecutive matrix instructions write different accumulators.
+template <int NCB, int XB, int PA>
+__device__ __forceinline__ void second_product(const char* hi, const char* lo, int trofs, const v8bf (&wh)[XB],
+                                               const v8bf (&wl)[XB], v4f (&oacc)[XB][NCB]) {
+  constexpr int CG = XB >= 2 ? 2 : 4;
+#pragma unroll
+  for (int cb0 = 0; cb0 < NCB; cb0 += CG) {
+    v8bf ah[CG], al[CG];
+#pragma unroll
+    for (int j = 0; j < CG; ++j) {
+      if (cb0 + j < NCB) {
+        ah[j] = join8(lds_read_tr(hi + trofs + 32 * (cb0 + j)), lds_read_tr(hi + trofs + 16 * PA + 32 * (cb0 + j)));
+        al[j] = join8(lds_read_tr(lo + trofs + 32 * (cb0 + j)), lds_read_tr(lo + trofs + 16 * PA + 32 * (cb0 + j)));
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+#pragma unroll
+      for (int j = 0; j < CG; ++j) {
+        if (cb0 + j < NCB) {
+#pragma unroll
+          for (int b = 0; b < XB; ++b) oacc[b][cb0 + j] = mfma_bf(k == 1 ? al[j] : ah[j], k == 2 ? wl[b] : wh[b], oacc[b][cb0 + j]);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ operand images -----
+// One workgroup per (chunk-side, tile): splits 32 rows of an fp32 matrix into the hi and lo planes of an image.
+// Rows at or beyond the chunk-side's valid rows, and columns at or beyond dk, are written as zeros.
+struct ImageArgs {
+  const float* src;     // rows of dk floats; chunk-side cs starts at row (cs & 1) * side_rows + (cs >> 1) * cs_rows
+  char* img;            // [2 * nchunks][tiles][IMG]
+  int32_t dk, ns, tiles, cs_rows, last_rows, nchunks;
+  int64_t side_rows;
+};
+__global__ void __launch_bounds__(256) k_split_images(ImageArgs a) {
+  const int cs = blockIdx.x / a.tiles, t = blockIdx.x % a.tiles;
+  const int side = cs & 1, c = cs >> 1;
+  const int valid = c == a.nchunks - 1 ? a.last_rows : a.cs_rows;
+  const int pa = sp_pitch(64 * a.ns), plane = SP_TY * pa;
+  char* img = a.img + ((size_t)cs * a.tiles + t) * sp_image(a.ns);
+  const float* src = a.src + ((size_t)side * a.side_rows + (size_t)c * a.cs_rows) * a.dk;
+  const int groups = 4 * a.ns;                             // 8-column groups per row
+  for (int u = threadIdx.x; u < SP_TY * groups; u += 256) {
+    const int r = u / groups, q = u % groups;
+    const int row = t * SP_TY + r, col = 8 * q;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = 0.f;
+    if (row < valid) {
+      const float* p = src + (size_t)row * a.dk + col;
+      if (col < a.dk) { const float4 f = *reinterpret_cast<const float4*>(p); v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w; }
+      if (col + 4 < a.dk) { const float4 f = *reinterpret_cast<const float4*>(p + 4); v[4] = f.x; v[5] = f.y; v[6] = f.z; v[7] = f.w; }
+    }
+    v8bf hi, lo;
+    split8(v, hi, lo);
+    *reinterpret_cast<v8bf*>(img + r * pa + col * 2) = hi;
+    *reinterpret_cast<v8bf*>(img + plane + r * pa + col * 2) = lo;
+  }
+}
+
+// ------------------------------------------------------------------- the two passes -----
+// PASS 1: scores, online softmax and gQ = P K for 64 XB edges of one chunk-side against the chunk's negatives; the
+// unit numbering, the split of the last round's stripes and the lazily updated softmax reference are k_flash's, and
+// so are the statistics and gradient rows written.  No weights are kept for pass 2:
+// PASS 2: gK = P^T Q for 64 XB negatives of one chunk-side against the chunk's edges, with the scores computed again
+// (the same three bf16 products) and P = exp(score - lse) from the finished log-sum-exp.  Writing the weights out
+// and reading them back costs 8 bytes of memory traffic per pair, computing a score again 6 d bf16 flops: at this
+// matrix rate the second is several times cheaper (the fp32 passes, whose matrix rate is 16 times lower, store them).
+// The unit numbering and the gradient rows written are k_flash_bwd's.
+template <int NS, int NCB, int XB, int PASS>
+__global__ void __launch_bounds__(256) MAR_WAVES_PER_SIMD((NS <= 8 ? 2 : 1))
+k_split(FlashArgs a) {
+  typedef SplitGeom<NS> SG;
+  constexpr int PA = SG::PA, PLANE = SG::PLANE, IMG = SG::IMG;
+  constexpr int TY = SP_TY;
+  constexpr int SR = 64 * XB;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  float* const aux_all = reinterpret_cast<float*>(smem + 2 * IMG);   // PASS 2: [2][TY] log-sum-exp of the tile's edges
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, m = lane & 15;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  int part, cs, stripe, tps = a.tps;
+  if (slot < a.whole_slots) {
+    part = slot % a.sy;
+    const int slot2 = slot / a.sy;
+    cs = (slot2 / a.nstripes) * 8 + xcd;
+    stripe = slot2 % a.nstripes;
+  } else {                                                // a part of a split stripe (see k_flash)
+    const int r = (slot - a.whole_slots) * 8 + xcd;
+    const int unit = r / a.rem_k;
+    part = r % a.rem_k;
+    cs = a.rem_cs0 + unit / a.nstripes;
+    stripe = unit % a.nstripes;
+    tps = a.rem_tps;
+  }
+  if (PASS == 2) cs = 2 * a.nchunks - 1 - cs;              // reverse of pass 1's order (see k_flash_bwd)
+  if (cs < 0 || cs >= 2 * a.nchunks) return;
+  const int side = cs & 1, c = cs >> 1;
+  const int ne = min(a.S, a.n - c * a.S);                 // edges in this chunk
+  const int n_x = PASS == 1 ? ne : a.N;                   // stationary rows
+  const int n_y = PASS == 1 ? a.N : ne;                   // streamed rows
+  if (stripe * SR >= n_x) return;
+  const size_t q_base = (size_t)side * a.B + (size_t)c * a.S;        // first Q row of the chunk
+  const size_t k_base = (size_t)side * a.C * a.N + (size_t)c * a.N;  // first K row of the chunk
+  const size_t x_base = PASS == 1 ? q_base : k_base;
+  const int dk = a.dk;
+
+  // ---- stationary fragments: slots of step s = columns 32 s + 8g .. +7 of row x
+  int x[XB]; bool xv[XB];
+  v8bf xh[XB][NS], xl[XB][NS];
+#pragma unroll
+  for (int b = 0; b < XB; ++b) {
+    x[b] = stripe * SR + (wave * XB + b) * 16 + m;
+    xv[b] = x[b] < n_x;
+    const float* xrow = a.X + (x_base + (xv[b] ? x[b] : 0)) * dk;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int col = 32 * s + 8 * g;
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = 0.f;
+      if (xv[b] && col < dk) { const float4 f = *reinterpret_cast<const float4*>(xrow + col); v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w; }
+      if (xv[b] && col + 4 < dk) { const float4 f = *reinterpret_cast<const float4*>(xrow + col + 4); v[4] = f.x; v[5] = f.y; v[6] = f.z; v[7] = f.w; }
+      // the stationary rows carry the factor log2(e): the scores come out in units of ln 2 and the weights are
+      // plain powers of two of score differences
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] *= 1.44269504088896341f;
+      split8(v, xh[b][s], xl[b][s]);
+    }
+  }
+
+  v4f oacc[XB][NCB];
+  float mrun[XB], lrun[XB];
+#pragma unroll
+  for (int b = 0; b < XB; ++b) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+    mrun[b] = -3.0e38f; lrun[b] = 0.f;
+  }
+
+  const int ntiles_all = (n_y + TY - 1) / TY;
+  const int t_begin = part * tps;
+  const int ntiles = min(ntiles_all, t_begin + tps);
+
+  // ---- images of the streamed rows, copied into LDS one tile ahead (see k_flash's DMA path); a register load issued
+  // behind the copies is the fence: once its value is there the image is in LDS.  PASS 2's fence is the load of the
+  // softmax statistics of streamed edge threadIdx % TY.
+  const char* ybase = a.yimg + (size_t)cs * a.yimg_tiles * IMG;
+  const uint32_t ybytes = (uint32_t)a.yimg_tiles * IMG;
+  const v4i ywords = buf_words(ybase, ybytes);
+  const BufRsrc ysrc = buf_rsrc(ybase, ybytes);
+  const BufRsrc mlsrc = buf_rsrc(a.ml + q_base * 2, PASS == 2 ? (uint32_t)ne * 8 : 0u);
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int f_row = threadIdx.x % TY;
+  const size_t ml_stride = (size_t)2 * a.B;               // rows per part of pass 1's statistics
+  float fence = 0.f;
+  float2 st_ml = make_float2(0.f, 0.f);
+  int token = 0;
+  auto dma_tile = [&](int t, int buf) {
+    const int tofs = t * IMG;
+#pragma unroll
+    for (int q = 0; q < SG::NCW; ++q) {
+      const int pc = 4 * q + wave_s;
+      if (pc < SG::NCH) buf_load4_to_lds(ywords, lds_address_b(smem) + buf * IMG + pc * 1024, lane * 16, tofs + pc * 1024, token);
+    }
+    if (PASS == 2) st_ml = buf_load2(mlsrc, f_row * 8 + token, t * TY * 8);
+    else fence = buf_load1(ysrc, token, tofs);
+  };
+  auto dma_land = [&](int t, int buf) {
+    if (PASS == 2) {
+      const int yr = t * TY + f_row;
+      float mm = st_ml.x, ll = st_ml.y;
+      if (a.sy_ml > 1 && yr < n_y) {                       // pass 1 was split (small batches): merge the parts
+        const float2* __restrict__ mlp = reinterpret_cast<const float2*>(a.ml) + q_base + yr;
+        for (int p = 1; p < a.sy_ml; ++p) mm = fmaxf(mm, mlp[p * ml_stride].x);
+        ll *= __expf(st_ml.x - mm);
+        for (int p = 1; p < a.sy_ml; ++p) { const float2 v = mlp[p * ml_stride]; ll += v.y * __expf(v.x - mm); }
+      }
+      // rows beyond the chunk: +inf, so that their weights are exp(-inf) = 0
+      // (in units of ln 2, like the scores; threads that share a row write the same value)
+      aux_all[buf * TY + f_row] = yr < n_y ? (mm + logf(ll)) * 1.44269504088896341f : __builtin_inff();
+    } else {
+      asm volatile("" : : "v"(fence));
+    }
+  };
+  if (t_begin < ntiles) {
+    dma_tile(t_begin, 0);
+    dma_land(t_begin, 0);
+    __syncthreads();
+  }
+
+  const int trofs = (4 * g + (m >> 2)) * PA + 8 * (m & 3);
+  for (int t = t_begin; t < ntiles; ++t) {
+    const int buf = (t - t_begin) & 1;
+    const char* hi = smem + buf * IMG;
+    const char* lo = hi + PLANE;
+    const bool has_next = t + 1 < ntiles;                  // uniform
+    if (has_next) dma_tile(t + 1, buf ^ 1);
+    const int y0 = t * TY;
+    const bool masked = PASS == 1 && y0 + TY > n_y;
+
+    // -- scores of the tile's two 16-row blocks.  The fragments of the streamed rows are read PD groups (one group =
+    // one contraction step of one block) ahead of the matrix instructions that consume them.
+    v4f sacc[2][XB];
+#pragma unroll
+    for (int yb = 0; yb < 2; ++yb) {
+#pragma unroll
+      for (int b = 0; b < XB; ++b) sacc[yb][b] = (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+    {
+      constexpr int NG = 2 * NS, PD = 4;
+      const int fofs = m * PA + 16 * g;
+      v8bf fh[PD], fl[PD];
+#pragma unroll
+      for (int q = 0; q < PD; ++q) {                       // group q: step q / 2, block q % 2
+        fh[q] = *reinterpret_cast<const v8bf*>(hi + fofs + (q % 2) * 16 * PA + (q / 2) * 64);
+        fl[q] = *reinterpret_cast<const v8bf*>(lo + fofs + (q % 2) * 16 * PA + (q / 2) * 64);
+      }
+#pragma unroll
+      for (int q = 0; q < NG; ++q) {
+        const int s = q / 2, yb = q % 2;
+        const v8bf ah = fh[q % PD], al = fl[q % PD];
+        if (q + PD < NG) {
+          fh[q % PD] = *reinterpret_cast<const v8bf*>(hi + fofs + ((q + PD) % 2) * 16 * PA + ((q + PD) / 2) * 64);
+          fl[q % PD] = *reinterpret_cast<const v8bf*>(lo + fofs + ((q + PD) % 2) * 16 * PA + ((q + PD) / 2) * 64);
+        }
+#pragma unroll
+        for (int b = 0; b < XB; ++b) sacc[yb][b] = mfma_bf(ah, xh[b][s], sacc[yb][b]);
+#pragma unroll
+        for (int b = 0; b < XB; ++b) sacc[yb][b] = mfma_bf(al, xh[b][s], sacc[yb][b]);
+#pragma unroll
+        for (int b = 0; b < XB; ++b) sacc[yb][b] = mfma_bf(ah, xl[b][s], sacc[yb][b]);
+        __builtin_amdgcn_sched_barrier(0);                 // keeps the reads PD groups ahead of their use
+      }
+    }
+    // -- weights of the lane's 8 pairs per x-block: slot kk <-> y = y0 + (kk < 4 ? 4g + kk : 16 + 4g + kk - 4)
+    float lse8[8];
+    if (PASS == 2) {
+      const float4 l0 = *reinterpret_cast<const float4*>(aux_all + buf * TY + 4 * g);
+      const float4 l1 = *reinterpret_cast<const float4*>(aux_all + buf * TY + 16 + 4 * g);
+      lse8[0] = l0.x; lse8[1] = l0.y; lse8[2] = l0.z; lse8[3] = l0.w; lse8[4] = l1.x; lse8[5] = l1.y; lse8[6] = l1.z; lse8[7] = l1.w;
+    }
+    v8bf wh[XB], wl[XB];
+#pragma unroll
+    for (int b = 0; b < XB; ++b) {
+      float sc[8], w[8];
+#pragma unroll
+      for (int yb = 0; yb < 2; ++yb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          sc[4 * yb + r] = sacc[yb][b][r];
+          if (masked && y0 + 16 * yb + 4 * g + r >= n_y) sc[4 * yb + r] = -__builtin_inff();
+        }
+      }
+      if (PASS == 1) {
+        const float mloc = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+        if (__any(mloc > mrun[b] + 23.f)) {               // 2^23 < e^16
+          float mall = fmaxf(mloc, __shfl_xor(mloc, 16));
+          mall = fmaxf(mall, __shfl_xor(mall, 32));
+          const float mnew = fmaxf(mrun[b], mall);
+          float alpha = __builtin_amdgcn_exp2f(mrun[b] - mnew);
+          asm volatile("" : "+v"(alpha));                  // a real branch: keeps the rescale from being executed speculatively
+          lrun[b] *= alpha;
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) oacc[b][cb] *= alpha;
+          mrun[b] = mnew;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = __builtin_amdgcn_exp2f(sc[k] - mrun[b]);
+        lrun[b] += ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = __builtin_amdgcn_exp2f(sc[k] - lse8[k]);
+      }
+      split8(w, wh[b], wl[b]);
+    }
+    // -- O^T[c][x] += sum_y Y[y][c] W[y][x]
+    second_product<NCB, XB, PA>(hi, lo, trofs, wh, wl, oacc);
+    if (has_next) {
+      dma_land(t + 1, buf ^ 1);
+      __syncthreads();                                     // tile t + 1 is in LDS; every wave is done with tile t
+    }
+  }
+
+  // ---- epilogue
+  if (PASS == 1) {                                         // the part's statistics and unnormalised gradient rows
+    float* ml_out = a.ml + ((size_t)part * 2 * a.B + x_base) * 2;
+    float* o_out = a.out + ((size_t)part * 2 * a.B + x_base) * dk;
+    if (slot >= a.whole_slots && part > 0) {
+      const size_t xr = (size_t)(part - 1) * a.rem_rows + (size_t)(cs - a.rem_cs0) * a.trows;
+      ml_out = a.mlx + xr * 2;
+      o_out = a.outx + xr * dk;
+    } else if (slot >= a.whole_slots) {
+      ml_out = a.ml + x_base * 2;
+      o_out = a.out + x_base * dk;
+    }
+#pragma unroll
+    for (int b = 0; b < XB; ++b) {
+      float ltot = lrun[b] + __shfl_xor(lrun[b], 16);
+      ltot += __shfl_xor(ltot, 32);
+      if (!xv[b]) continue;
+      if (g == 0) *reinterpret_cast<float2*>(ml_out + (size_t)x[b] * 2) = make_float2(mrun[b] * 0.693147180559945309f, ltot);
+      float* orow = o_out + (size_t)x[b] * dk;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const int col = 16 * cb + 4 * g;
+        if (col < dk) *reinterpret_cast<float4*>(orow + col) = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
+      }
+    }
+  } else {                                                 // gradient row of part `part` of each negative's occurrence
+#pragma unroll
+    for (int b = 0; b < XB; ++b) {
+      if (!xv[b]) continue;
+      float* orow = a.out + (a.roles * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x[b]) * a.sy + part) * dk;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const int col = 16 * cb + 4 * g;
+        if (col < dk) *reinterpret_cast<float4*>(orow + col) = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------- launchers -----
+int mar_split_supported(int dk) { return dk >= 4 && dk <= 400; }
+int mar_split_stripe_rows(int dk, int pass) { (void)pass; return sp_ns(dk) <= 4 ? 128 : 64; }
+int mar_split_tile_rows() { return SP_TY; }
+int mar_split_wgs_per_cu(int dk, int pass) { (void)pass; return sp_ns(dk) <= 8 ? 2 : 1; }
+size_t mar_split_image_bytes(int dk) { return (size_t)sp_image(sp_ns(dk)); }
+
+template <int NS, int NCB, int XB>
+static hipError_t sp_prepare() {
+  constexpr size_t lds = SplitGeom<NS>::LDS_BYTES + 2 * SP_TY * 4;
+  hipError_t e = hipSuccess;
+  if (lds > 64 * 1024) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  }
+  return e;
+}
+hipError_t mar_split_prepare() {
+  hipError_t e = sp_prepare<8, 13, 1>();
+  if (e == hipSuccess) e = sp_prepare<8, 16, 1>();
+  if (e == hipSuccess) e = sp_prepare<13, 25, 1>();
+  return e;
+}
+
+template <int NS, int NCB, int XB>
+static hipError_t sp_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
+  constexpr size_t lds = SplitGeom<NS>::LDS_BYTES + 2 * SP_TY * 4;
+  if (pass == 1) hipLaunchKernelGGL((k_split<NS, NCB, XB, 1>), grid, dim3(256), lds, st, a);
+  else hipLaunchKernelGGL((k_split<NS, NCB, XB, 2>), grid, dim3(256), lds, st, a);
+  return hipGetLastError();
+}
+
+// `a` is filled by mar_launch_flash (units, parts, buffers); this picks the instantiation for a.dk.
+hipError_t mar_split_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
+  const int ns = sp_ns(a.dk), ncb = sp_ncb(a.dk);
+  if (ns == 2) return sp_launch<2, 4, 2>(a, pass, grid, st);
+  if (ns == 4) return ncb == 7 ? sp_launch<4, 7, 2>(a, pass, grid, st) : sp_launch<4, 8, 2>(a, pass, grid, st);
+  if (ns == 8) return ncb == 13 ? sp_launch<8, 13, 1>(a, pass, grid, st) : sp_launch<8, 16, 1>(a, pass, grid, st);
+  return sp_launch<13, 25, 1>(a, pass, grid, st);
+}
+
+// Images of the gathered operands of one batch: the negatives' rows (streamed by pass 1) and the edge-side operands
+// (streamed by pass 2).
+hipError_t mar_launch_split_images(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
+  const MarDims& d = c->dm;
+  if (b.n == 0) return hipSuccess;
+  ImageArgs k;
+  k.dk = d.dk; k.ns = sp_ns(d.dk); k.nchunks = b.nchunks;
+  k.src = c->L.Km; k.img = c->L.Kimg; k.tiles = (d.N + SP_TY - 1) / SP_TY; k.cs_rows = d.N; k.last_rows = d.N;
+  k.side_rows = (int64_t)d.C * d.N;
+  hipLaunchKernelGGL(k_split_images, dim3((unsigned)(2 * b.nchunks * k.tiles)), dim3(256), 0, st, k);
+  ImageArgs q = k;
+  q.src = c->L.Q; q.img = c->L.Qimg; q.tiles = (d.S + SP_TY - 1) / SP_TY; q.cs_rows = d.S;
+  q.last_rows = b.n - (b.nchunks - 1) * d.S; q.side_rows = d.B;
+  hipLaunchKernelGGL(k_split_images, dim3((unsigned)(2 * b.nchunks * q.tiles)), dim3(256), 0, st, q);
+  return hipGetLastError();
+}

@@ -30,7 +30,7 @@ def make_tables(rng, num_nodes, num_rels, dim, std):
 
 
 def run_step_both(model, num_nodes, num_rels, dim, B, C, N, n_edges, seed, std=0.001, lr=0.1, eps=1e-10,
-                  node_state=None, rel_state=None, ids=None, tables=None):
+                  node_state=None, rel_state=None, ids=None, tables=None, precision=0):
     """One training step on the GPU and in the oracle.  Returns a dict with both sides' outputs."""
     rng = np.random.default_rng(seed)
     if tables is None:
@@ -49,7 +49,7 @@ def run_step_both(model, num_nodes, num_rels, dim, B, C, N, n_edges, seed, std=0
     rs0 = np.zeros_like(re_) if rel_state is None else rel_state
 
     tr = mar.Trainer(num_nodes, num_rels, dim, model, B, C, N, 0, lr, eps, std, 0,
-                     node_emb=ne, rel_emb=re_, node_state=ns0, rel_state=rs0)
+                     node_emb=ne, rel_emb=re_, node_state=ns0, rel_state=rs0, precision=precision)
     dev = tr.device
     tr.neg_src.copy_(torch.from_numpy(neg_src.reshape(-1)))
     tr.neg_dst.copy_(torch.from_numpy(neg_dst.reshape(-1)))

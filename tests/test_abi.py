@@ -35,8 +35,9 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_struct_layouts_match_header():
-    assert ctypes.sizeof(mar.MarConfig) == 56
+    assert ctypes.sizeof(mar.MarConfig) == 64
     assert mar.MarConfig.seed.offset == 48 and mar.MarConfig.lr.offset == 36
+    assert mar.MarConfig.precision.offset == 56 and mar.MarConfig.reserved.offset == 60
     assert ctypes.sizeof(mar.MarDebugOut) == 7 * 8
 
 
@@ -54,11 +55,24 @@ def test_workspace_bytes_scales_and_validates(lib):
     assert small % 256 == 0
     for bad, code in ((dict(dim=0), -2), (dict(dim=401), -2), (dict(model=4), -1), (dict(model=1, dim=51), -1),
                       (dict(batch_size=101), -2), (dict(num_chunks=0), -1), (dict(deg_negs_per_chunk=21), -1),
-                      (dict(num_nodes=(1 << 31) - 2), -2), (dict(lr=0.0), -1), (dict(num_rels=0), -1)):
+                      (dict(num_nodes=(1 << 31) - 2), -2), (dict(lr=0.0), -1), (dict(num_rels=0), -1),
+                      (dict(precision=2), -1), (dict(precision=-1), -1), (dict(precision=1, model=2), -1),
+                      (dict(reserved=1), -1)):
         with pytest.raises(mar.MarError) as e:
             mar.mar_workspace_bytes(_cfg(**bad))
         assert e.value.code == code, bad
         assert mar.mar_last_error() != ""
+
+
+def test_split_precision_is_a_configuration_of_its_own(lib):
+    """The split-precision passes keep operand images instead of stored weights: another workspace size, and the
+    bilinear models only."""
+    for model in (0, 1, 3):
+        a = mar.mar_workspace_bytes(_cfg(model=model, dim=52))
+        b = mar.mar_workspace_bytes(_cfg(model=model, dim=52, precision=mar.PRECISION_SPLIT_BF16))
+        assert a > 0 and b > 0 and a != b
+    for dim in (4, 17, 100, 128, 200, 256, 400):
+        assert mar.mar_workspace_bytes(_cfg(dim=dim, precision=1)) % 256 == 0
 
 
 def test_argument_checks_need_no_gpu(lib):

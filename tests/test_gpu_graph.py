@@ -30,14 +30,16 @@ def _tables(tr):
     return [t.clone() for t in (tr.node_emb, tr.node_state, tr.rel_emb, tr.rel_state)]
 
 
-@pytest.mark.parametrize("model,dim,B,C,N", ((mar.MODEL_COMPLEX, 100, 2000, 4, 500), (mar.MODEL_DISTMULT, 400, 3000, 3, 700),
-                                             (mar.MODEL_DISTMULT, 50, 1000, 10, 100), (mar.MODEL_TRANSE, 36, 1500, 5, 300)))
-def test_same_step_twice_gives_the_same_bits(model, dim, B, C, N):
+@pytest.mark.parametrize("model,dim,B,C,N,precision", (
+    (mar.MODEL_COMPLEX, 100, 2000, 4, 500, 0), (mar.MODEL_DISTMULT, 400, 3000, 3, 700, 0),
+    (mar.MODEL_DISTMULT, 50, 1000, 10, 100, 0), (mar.MODEL_TRANSE, 36, 1500, 5, 300, 0),
+    (mar.MODEL_COMPLEX, 100, 2000, 4, 500, 1), (mar.MODEL_DISTMULT, 400, 3000, 3, 700, 1)))
+def test_same_step_twice_gives_the_same_bits(model, dim, B, C, N, precision):
     V, R = 3000, 6
     ne, re_, ids = _inputs(V, R, dim, B, seed=dim)
     results = []
     for run in range(3):
-        tr = mar.Trainer(V, R, dim, model, B, C, N, N // 10, seed=5, node_emb=ne, rel_emb=re_)     # accumulators: zero
+        tr = mar.Trainer(V, R, dim, model, B, C, N, N // 10, seed=5, node_emb=ne, rel_emb=re_, precision=precision)     # accumulators: zero
         for step in range(2):
             tr.sample_negatives(step, ids[0], ids[2])
             tr.train_batch(*ids)
@@ -50,12 +52,13 @@ def test_same_step_twice_gives_the_same_bits(model, dim, B, C, N):
             assert torch.equal(t, w)
 
 
-def test_captured_step_replays_like_the_eager_step():
+@pytest.mark.parametrize("precision", (0, 1))
+def test_captured_step_replays_like_the_eager_step(precision):
     V, R, dim, B, C, N = 3000, 6, 100, 2000, 4, 500
     ne, re_, ids = _inputs(V, R, dim, B, seed=0)
 
     def trainer():
-        tr = mar.Trainer(V, R, dim, mar.MODEL_COMPLEX, B, C, N, 50, seed=5, node_emb=ne, rel_emb=re_)   # accumulators: zero
+        tr = mar.Trainer(V, R, dim, mar.MODEL_COMPLEX, B, C, N, 50, seed=5, node_emb=ne, rel_emb=re_, precision=precision)   # accumulators: zero
         tr.sample_negatives(3, ids[0], ids[2])
         return tr
 

@@ -26,14 +26,14 @@ def _setup(model, V, R, dim, B, C, N, nb, seed, hot=0.3, state0=0.0):
     return ne, ns, re_, rs, batches
 
 
-def _run_pipe(model, V, R, dim, B, C, N, depth, tables, batches, side_stream=True):
+def _run_pipe(model, V, R, dim, B, C, N, depth, tables, batches, side_stream=True, precision=0):
     ne, ns, re_, rs = tables
     dev = torch.device("cuda:0")
     h_ne = torch.from_numpy(ne.copy()).pin_memory()
     h_ns = torch.from_numpy(ns.copy()).pin_memory()
     d_re = torch.from_numpy(re_.copy()).to(dev)
     d_rs = torch.from_numpy(rs.copy()).to(dev)
-    cfg = mar.MarConfig(V, R, dim, model, B, C, N, 0, 0.1, 1e-10, 0.001, 0)
+    cfg = mar.MarConfig(V, R, dim, model, B, C, N, 0, 0.1, 1e-10, 0.001, 0, precision, 0)
     nbytes = mar.mar_pipe_workspace_bytes(cfg, depth)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     pipe = mar.mar_pipe_create(cfg, h_ne, h_ns, d_re, d_rs, ws, nbytes, depth)
@@ -51,9 +51,10 @@ def _run_pipe(model, V, R, dim, B, C, N, depth, tables, batches, side_stream=Tru
     return out
 
 
-def _run_resident(model, V, R, dim, B, C, N, tables, batches):
+def _run_resident(model, V, R, dim, B, C, N, tables, batches, precision=0):
     ne, ns, re_, rs = tables
-    tr = mar.Trainer(V, R, dim, model, B, C, N, 0, 0.1, 1e-10, 0.001, 0, node_emb=ne, rel_emb=re_, node_state=ns, rel_state=rs)
+    tr = mar.Trainer(V, R, dim, model, B, C, N, 0, 0.1, 1e-10, 0.001, 0, node_emb=ne, rel_emb=re_, node_state=ns, rel_state=rs,
+                     precision=precision)
     losses = []
     for bt in batches:
         tr.neg_src.copy_(torch.from_numpy(bt[3].reshape(-1))); tr.neg_dst.copy_(torch.from_numpy(bt[4].reshape(-1)))
@@ -72,6 +73,15 @@ def test_depth_one_is_the_resident_step_bit_for_bit(model, dim):
     ne, ns, re_, rs, batches = _setup(model, V, R, dim, B, C, N, nb=5, seed=dim)
     got = _run_pipe(model, V, R, dim, B, C, N, 1, (ne, ns, re_, rs), batches)
     want = _run_resident(model, V, R, dim, B, C, N, (ne, ns, re_, rs), batches)
+    for g, w, name in zip(got, want, ("node_emb", "node_state", "rel_emb", "rel_state", "loss")):
+        assert np.array_equal(g, w), name
+
+
+def test_depth_one_is_the_resident_step_in_split_precision():
+    model, dim, V, R, B, C, N = mar.MODEL_COMPLEX, 100, 5000, 6, 600, 3, 200
+    ne, ns, re_, rs, batches = _setup(model, V, R, dim, B, C, N, nb=4, seed=11)
+    got = _run_pipe(model, V, R, dim, B, C, N, 1, (ne, ns, re_, rs), batches, precision=1)
+    want = _run_resident(model, V, R, dim, B, C, N, (ne, ns, re_, rs), batches, precision=1)
     for g, w, name in zip(got, want, ("node_emb", "node_state", "rel_emb", "rel_state", "loss")):
         assert np.array_equal(g, w), name
 

@@ -1,0 +1,70 @@
+"""GPU parity of the split-precision contraction (each fp32 operand as bf16 hi + lo, three bf16 matrix products per
+product): one training step through the C ABI against the fp64 oracle, at the bars of the fp32 path."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2101_08358_amd as mar
+
+from parity_util import run_step_both, check_step
+
+pytestmark = pytest.mark.gpu
+
+DISTMULT, COMPLEX, TRANSE, DOT = 0, 1, 2, 3
+SPLIT = 1
+
+
+@pytest.mark.parametrize("model", (DISTMULT, COMPLEX, DOT))
+@pytest.mark.parametrize("shape", (
+    # (V, R, dim, B, C, N, n_edges)
+    (500, 7, 50, 1000, 10, 100, 1000),        # config-1 geometry on a small graph (heavy row reuse)
+    (20000, 30, 100, 2000, 2, 1000, 2000),    # config-2/3/4 chunk geometry: several stripes, ragged tails
+    (3000, 5, 100, 600, 3, 130, 470),         # ragged everything: short last chunk, N not a multiple of 16
+))
+def test_one_step_matches_oracle(model, shape):
+    V, R, dim, B, C, N, n = shape
+    print("case", model, shape, flush=True)
+    out = run_step_both(model, V, R, dim, B, C, N, n, seed=100 + model, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
+@pytest.mark.parametrize("model,dim", ((DISTMULT, 400), (COMPLEX, 200), (DISTMULT, 36), (DISTMULT, 17), (COMPLEX, 128), (DOT, 100), (DISTMULT, 256)))
+def test_one_step_other_widths(model, dim):
+    print("case", model, dim, flush=True)
+    out = run_step_both(model, 4000, 11, dim, 512, 4, 200, 512, seed=7 + dim, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
+def test_one_step_with_trained_scale_embeddings():
+    """Rows of the size a trained table has (std 0.3): scores of order 10, softmax far from uniform."""
+    out = run_step_both(DISTMULT, 3000, 5, 100, 1024, 4, 500, 1024, seed=3, std=0.3, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
+def test_one_step_when_pass_one_splits_its_last_round():
+    """80 chunk-sides x 8 stripes of 128 edges = 640 units of the first pass on 512 workgroup slots: the stripes of the
+    last 16 chunk-sides are split into parts over the negatives' tiles and merged afterwards."""
+    out = run_step_both(DISTMULT, 50000, 3, 100, 40000, 40, 256, 40000, seed=12, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
+def test_evaluation_in_a_split_precision_context_is_the_fp32_one():
+    """Ranks are always computed in fp32: a context created for split-precision training ranks like any other."""
+    rng = np.random.default_rng(9)
+    V, R, dim, B, C, N = 2000, 3, 100, 512, 2, 300
+    ne = (rng.standard_normal((V, dim)) * 0.3).astype(np.float32)
+    re_ = (rng.standard_normal((R, dim)) * 0.3).astype(np.float32)
+    ids = [torch.from_numpy(rng.integers(0, hi, B).astype(np.int32)).cuda() for hi in (V, R, V)]
+    got = []
+    for precision in (0, 1):
+        tr = mar.Trainer(V, R, dim, mar.MODEL_COMPLEX, B, C, N, 0, node_emb=ne, rel_emb=re_, precision=precision)
+        tr.sample_negatives(0)
+        got.append([t.clone() for t in tr.eval_scores(*ids)])
+        tr.close()
+    for a, b in zip(*got):
+        assert torch.equal(a, b)
+
+
+def test_transe_is_refused():
+    with pytest.raises(mar.MarError):
+        mar.mar_workspace_bytes(mar.MarConfig(1000, 3, 50, mar.MODEL_TRANSE, 100, 10, 20, 0, 0.1, 1e-10, 0.001, 0, SPLIT, 0))
