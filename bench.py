@@ -24,9 +24,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3       # MI355X dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 DEFAULT_STEPS = {"tiny": (300, 30), "kg_small": (500, 50), "social": (150, 15), "social_dot": (150, 15),
                  "kg_large": (150, 15), "wide": (100, 10)}
+
+
+SPLIT_DTYPE = "bf16x3 (fp32 operands as bf16 hi + lo, three bf16 matrix products per product, fp32 accumulation)"
 
 
 def note(msg):
@@ -92,8 +96,10 @@ def oracle_baseline(w, es, er, ed, budget_s=15.0):
                 sample="%d whole steps of workload %s (batch %d) after 1 warm-up step, numpy fp64%s" % (steps, w.name, w.batch_size, extra))
 
 
-def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_baseline=False):
-    """Builds the workload's inputs on the device, times `steps` training steps and returns the record."""
+def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_baseline=False, precision=0, with_split=False):
+    """Builds the workload's inputs on the device, times `steps` training steps and returns the record.
+    precision 1: the split-precision contraction (config `precision`); with_split: after the fp32 measurement the
+    same steps are timed again in split precision on the same tables and reported under "split_bf16"."""
     import torch
     import synth
     import paper_2101_08358_amd as mar
@@ -110,18 +116,44 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
                                      device=dev if w.num_edges > 10_000_000 else "cpu")
     d_src, d_rel, d_dst = src.to(dev), rel.to(dev), dst.to(dev)
     tr = mar.Trainer(w.num_nodes, w.num_rels, w.dim, w.model, w.batch_size, w.num_chunks, w.negs_per_chunk,
-                     w.deg_negs_per_chunk, w.lr, w.eps, w.init_std, w.seed, device=dev)
+                     w.deg_negs_per_chunk, w.lr, w.eps, w.init_std, w.seed, device=dev, precision=precision)
     torch.cuda.synchronize()
     note("%s: %d edges, %.1f GB of tables built in %.1f s" % (w.name, w.num_edges, 2 * 4e-9 * w.dim * (w.num_nodes + w.num_rels),
                                                            time.perf_counter() - t_build))
     nb = (w.num_edges + w.batch_size - 1) // w.batch_size
     bounds = lambda b: (b * w.batch_size, min((b + 1) * w.batch_size, w.num_edges))
 
-    def step(i):
+    def step(i, tr=tr):
         lo, hi = bounds(i % nb)
         mar.mar_sample_negatives(tr.ctx, i, d_src, d_dst, w.num_edges, tr.neg_src, tr.neg_dst)
         mar.mar_train_batch(tr.ctx, d_src[lo:hi], d_rel[lo:hi], d_dst[lo:hi], hi - lo, tr.neg_src, tr.neg_dst, tr.loss, None)
         return hi - lo
+
+    def contraction_roofline(flash_phase, prof_steps, prof_edges, split):
+        """Roofline record of the two contraction launches from their HIP-event times.  fp32: the algorithmic flops
+        (3 contractions x 2 sides x 2 n N d) against the fp32 matrix peak.  Split precision: the bf16 flops executed
+        (each pass computes the scores and one more product, every product as three bf16 products: 2 x 3 x 8 n N d)
+        against the bf16 matrix peak; `fp32_equivalent` is the algorithmic rate."""
+        per_launch = lambda ms: ms / max(prof_steps, 1) * 1e3                     # us per launch
+        flops = lambda k: k * prof_edges * w.negs_per_chunk * w.dim / max(prof_steps, 1)
+        tflops = lambda fl, us: fl / (us * 1e-6) / 1e12 if us > 0 else 0.0
+        us1, us2 = per_launch(flash_phase[2]), per_launch(flash_phase[3])
+        if not split:
+            peak, k1, k2, names = PEAK_FP32_MFMA_TFLOPS, 8.0, 4.0, ("k_flash", "k_flash_bwd")
+            kernel = "k_flash + k_flash_bwd (the two contraction launches of every step)"
+        else:
+            peak, k1, k2, names = PEAK_BF16_MFMA_TFLOPS, 24.0, 24.0, ("k_split_pass1", "k_split_pass2")
+            kernel = "k_split<.., 1> + k_split<.., 2> (the two contraction launches of every step, split precision)"
+        achieved = tflops(flops(k1 + k2), us1 + us2)
+        r = {"bound": "mfma", "kernel": kernel, "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+             "traffic": None, "us_per_step": round(us1 + us2, 2),
+             "algorithmic_flops_per_step": 12.0 * w.batch_size * w.negs_per_chunk * w.dim,
+             names[0]: {"us": round(us1, 2), "flops": flops(k1), "frac": tflops(flops(k1), us1) / peak},
+             names[1]: {"us": round(us2, 2), "flops": flops(k2), "frac": tflops(flops(k2), us2) / peak}}
+        if split:
+            r["executed_flops_per_step"] = 48.0 * w.batch_size * w.negs_per_chunk * w.dim
+            r["fp32_equivalent_TFLOP/s"] = tflops(flops(12.0), us1 + us2)
+        return r
 
     for i in range(warmup):
         step(i)
@@ -147,11 +179,7 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
 
     # edges covered by the profiled steps (the first prof_steps of the timed region)
     prof_edges = sum(bounds(i % nb)[1] - bounds(i % nb)[0] for i in range(warmup, warmup + prof_steps))
-    per_launch = lambda ms: ms / max(prof_steps, 1) * 1e3                     # us per launch
-    flops = lambda k: k * prof_edges * w.negs_per_chunk * w.dim / max(prof_steps, 1)
-    tflops = lambda fl, us: fl / (us * 1e-6) / 1e12 if us > 0 else 0.0
-    flash_us = per_launch(flash_phase[2] + flash_phase[3])
-    achieved = tflops(flops(12.0), flash_us)                                  # 3 contractions x 2 sides x 2 n N d
+    roof = contraction_roofline(flash_phase, prof_steps, prof_edges, bool(precision))
 
     # A second, untimed pass with events on every phase for the per-phase report.
     all_steps = min(steps, 100)
@@ -179,7 +207,10 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
     chain_bytes = n * (2 * dk + 2 * roles * w.dim) * 4                               # operand gradients + s/r/d read, gradient rows written
     phases = {nm: round(per_step(ms) * 1e3, 2) for nm, ms in zip(mar.binding.PHASE_NAMES, phase_ms)}
     traffic = measured_traffic(w.name) if not nodes else {}          # per-launch bytes do not depend on the edge list
-    flash_traffic = (traffic.get("k_flash", 0.0) + traffic.get("k_flash_bwd", 0.0)) or None
+    if not precision:
+        roof["traffic"] = (traffic.get("k_flash", 0.0) + traffic.get("k_flash_bwd", 0.0)) or None
+    else:
+        roof["traffic"] = traffic.get("k_split", 0.0) or None
     # Bandwidth of the row phases two ways: algorithmic bytes (what the phase has to move) and the bytes the
     # rocprofv3 FETCH_SIZE / WRITE_SIZE counters saw per launch (profiles/traffic_<workload>.md), both over the
     # phase's time between HIP events on its stream.
@@ -208,21 +239,44 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
         "steps": steps,
         "warmup": warmup,
         "ms_per_step": elapsed / steps * 1e3,
-        "dtype": "f32",
+        "dtype": SPLIT_DTYPE if precision else "f32",
         "config": cfg,
-        "roofline": {"bound": "mfma", "kernel": "k_flash + k_flash_bwd (the two contraction launches of every step)",
-                     "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": flash_traffic,
-                     "us_per_step": round(flash_us, 2),
-                     "algorithmic_flops_per_step": 12.0 * w.batch_size * w.negs_per_chunk * w.dim,
-                     "k_flash": {"us": round(per_launch(flash_phase[2]), 2), "flops": flops(8.0),
-                                 "frac": tflops(flops(8.0), per_launch(flash_phase[2])) / PEAK_FP32_MFMA_TFLOPS},
-                     "k_flash_bwd": {"us": round(per_launch(flash_phase[3]), 2), "flops": flops(4.0),
-                                     "frac": tflops(flops(4.0), per_launch(flash_phase[3])) / PEAK_FP32_MFMA_TFLOPS}},
+        "roofline": roof,
         "phases_us_per_step": phases,
         "hbm_phases": hbm_phases,
         "final_loss_per_edge": loss / last_batch_edges,
     }
+    if with_split and not precision and w.model != 2:
+        # the same steps in split precision, on the same tables (a second context over them)
+        tr2 = mar.Trainer(w.num_nodes, w.num_rels, w.dim, w.model, w.batch_size, w.num_chunks, w.negs_per_chunk,
+                          w.deg_negs_per_chunk, w.lr, w.eps, w.init_std, w.seed, device=dev, node_emb=tr.node_emb,
+                          rel_emb=tr.rel_emb, node_state=tr.node_state, rel_state=tr.rel_state, precision=1)
+        for i in range(warmup):
+            step(i, tr2)
+        torch.cuda.synchronize()
+        mar.mar_profile_enable(tr2.ctx, min(steps, 4096), FLASH)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        done2 = 0
+        for i in range(warmup, warmup + steps):
+            done2 += step(i, tr2)
+        torch.cuda.synchronize()
+        el2 = time.perf_counter() - t0
+        fp2, ps2 = mar.mar_profile_read(tr2.ctx)
+        pe2 = sum(bounds(i % nb)[1] - bounds(i % nb)[0] for i in range(warmup, warmup + ps2))
+        mar.mar_profile_enable(tr2.ctx, all_steps, (1 << mar.NUM_PHASES) - 1)
+        for i in range(warmup + steps, warmup + steps + all_steps):
+            step(i, tr2)
+        torch.cuda.synchronize()
+        pm2, pst2 = mar.mar_profile_read(tr2.ctx)
+        mar.mar_profile_enable(tr2.ctx, 0, 0)
+        rec["split_bf16"] = {"value": done2 / el2, "unit": "edges/s", "steps": steps, "ms_per_step": el2 / steps * 1e3,
+                             "dtype": SPLIT_DTYPE, "roofline": contraction_roofline(fp2, ps2, pe2, True),
+                             "phases_us_per_step": {nm: round(ms / max(pst2, 1) * 1e3, 2) for nm, ms in zip(mar.binding.PHASE_NAMES, pm2)},
+                             "final_loss_per_edge": float(tr2.loss.item()) / last_batch_edges,
+                             "speedup_over_f32": (done2 / el2) / (edges_done / elapsed)}
+        tr2.close()
+        del tr2
     if cpu_baseline:
         m = min(w.num_edges, 64 * w.batch_size)          # the oracle only walks the first batches
         rec["cpu_baseline"] = oracle_baseline(w, src[:m].cpu().numpy(), rel[:m].cpu().numpy(), dst[:m].cpu().numpy())
@@ -305,6 +359,9 @@ def main():
     ap.add_argument("--other-edges", type=int, default=100_000_000, help="edge-list length of the other workloads' records")
     ap.add_argument("--nodes", type=int, default=0, help="shrink the node table (row width and batch geometry are unchanged)")
     ap.add_argument("--no-phase-events", action="store_true", help="time the steps without the per-phase HIP events")
+    ap.add_argument("--precision", choices=("f32", "split"), default="f32",
+                    help="arithmetic of the two contraction passes of the measured record (default f32, the paper's)")
+    ap.add_argument("--no-split", action="store_true", help="skip the split-precision record that rides along with every f32 record")
     ap.add_argument("--host-tables", type=int, default=0, metavar="DEPTH",
                     help="measure out-of-memory training instead: node table in pinned host memory, DEPTH batches in flight")
     args = ap.parse_args()
@@ -330,19 +387,21 @@ def main():
     name = args.workload or "wide"
     steps, warmup = DEFAULT_STEPS.get(name, (100, 10))
     steps, warmup = args.steps or steps, args.warmup or warmup
-    rec = run_workload(name, steps, warmup, args.edges, args.nodes, not args.no_phase_events, not args.no_cpu_baseline)
+    prec = 1 if args.precision == "split" else 0
+    rec = run_workload(name, steps, warmup, args.edges, args.nodes, not args.no_phase_events, not args.no_cpu_baseline,
+                       precision=prec, with_split=not args.no_split)
     out = {"metric": "training edges/sec per MI355X; achieved HBM GB/s + MFMA util vs peak",
            "value": rec["value"], "unit": "edges/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
            "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f32", "data": "synthetic"}
-    for k in ("config", "roofline", "cpu_baseline", "phases_us_per_step", "hbm_phases", "final_loss_per_edge"):
+           "dtype": rec["dtype"], "data": "synthetic"}
+    for k in ("config", "roofline", "cpu_baseline", "phases_us_per_step", "hbm_phases", "final_loss_per_edge", "split_bf16"):
         if k in rec:
             out[k] = rec[k]
     if not args.workload and not args.no_others:
         out["other_workloads"] = {}
         for other in ("social", "kg_large"):
             s, wu = DEFAULT_STEPS[other]
-            out["other_workloads"][other] = run_workload(other, s, wu, args.other_edges)
+            out["other_workloads"][other] = run_workload(other, s, wu, args.other_edges, precision=prec, with_split=not args.no_split)
     print(json.dumps(out))
 
 

@@ -230,6 +230,13 @@ extern "C" int mar_init_tables(const mar_config* cfg, float* node_emb, float* no
   hipEvent_t* evs[4] = {&c->ev_fork, &c->ev_index, &c->ev_pass1, &c->ev_chain};
   for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(evs[i], hipEventDisableTiming);
   if (e == hipSuccess) e = mar_launch_init(c, fill, (hipStream_t)hip_stream);
+  if (e == hipSuccess && d.split) {
+    // the images' padding rows (beyond a chunk's rows, up to whole tiles of 32) are never written again: zeros
+    const size_t kb = 2 * (size_t)d.C * (size_t)((d.N + 31) / 32) * mar_split_image_bytes(d.dk);
+    const size_t qb = 2 * (size_t)d.C * (size_t)((d.S + 31) / 32) * mar_split_image_bytes(d.dk);
+    e = mar_launch_fill_u32((uint32_t*)c->L.Kimg, (int64_t)(kb / 4), 0u, (hipStream_t)hip_stream);
+    if (e == hipSuccess) e = mar_launch_fill_u32((uint32_t*)c->L.Qimg, (int64_t)(qb / 4), 0u, (hipStream_t)hip_stream);
+  }
   if (e != hipSuccess) { mar_destroy(c); return hip_fail(e, "context set-up"); }
   *out = c;
   return MAR_OK;
@@ -305,7 +312,7 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   // longer path to the reduce, so it starts first and the gather runs beside it.
   if (c->dm.index_after_gather) {
     MARK(1, 0, st);
-    HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, st), "gather kernel");
+    HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, c->dm.split, st), "gather kernel");
     MARK(1, 1, st);
   }
   HIP_TRY(hipEventRecord(c->ev_fork, st), "fork");
@@ -317,7 +324,7 @@ extern "C" int mar_train_batch(mar_ctx* c, const int32_t* src, const int32_t* re
   HIP_TRY(hipEventRecord(c->ev_index, ax), "join");
   if (!c->dm.index_after_gather) {
     MARK(1, 0, st);
-    HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, st), "gather kernel");
+    HIP_TRY(mar_launch_prep(c, b, dbg ? dbg->pos : nullptr, c->dm.split, st), "gather kernel");
     MARK(1, 1, st);
   }
   MARK(2, 0, st);
@@ -367,7 +374,7 @@ extern "C" int mar_eval_scores(mar_ctx* c, const int32_t* src, const int32_t* re
   if (!rank_dst || !rank_src) return fail(MAR_EINVAL, "a rank output pointer is NULL");
   if (n_edges == 0) return MAR_OK;
   hipStream_t st = (hipStream_t)hip_stream;
-  HIP_TRY(mar_launch_prep(c, b, pos_scores, st), "gather kernel");
+  HIP_TRY(mar_launch_prep(c, b, pos_scores, 0, st), "gather kernel");
   HIP_TRY(mar_launch_flash(c, b, 3, rank_dst, rank_src, st), "rank kernel");
   return MAR_OK;
 }
@@ -584,7 +591,7 @@ extern "C" int mar_pipe_submit(mar_pipe* p, const int32_t* src, const int32_t* r
   PIPE_TRY(hipEventRecord(ps.ev_in, p->s_in), "stage in");
   // ---- step on the caller's stream: staged rows, ranks as ids; node gradients are left in gsum, relation rows updated
   PIPE_TRY(hipStreamWaitEvent(st, ps.ev_in, 0), "step");
-  PIPE_TRY(mar_launch_prep(c, ps.b_rank, nullptr, st), "gather kernel");
+  PIPE_TRY(mar_launch_prep(c, ps.b_rank, nullptr, c->dm.split, st), "gather kernel");
   PIPE_TRY(mar_launch_flash(c, ps.b_rank, 1, nullptr, nullptr, st), "score/softmax kernel");
   PIPE_TRY(mar_launch_flash_merge(c, ps.b_rank, st), "stripe merge kernel");
   PIPE_TRY(mar_launch_chain(c, ps.b_rank, st), "chain-rule kernel");

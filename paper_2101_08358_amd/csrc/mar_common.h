@@ -122,7 +122,8 @@ struct MarBatch {
 };
 
 hipError_t mar_launch_index(const mar_ctx* c, const MarBatch& b, hipStream_t st);
-hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, hipStream_t st);
+// images != 0 (split-precision training): the operands are written as bf16 hi/lo images instead of fp32 rows
+hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, int images, hipStream_t st);
 hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32_t* rank_dst, int32_t* rank_src,
                             hipStream_t st);
 hipError_t mar_launch_chain(const mar_ctx* c, const MarBatch& b, hipStream_t st);
@@ -155,4 +156,3 @@ int mar_split_tile_rows();
 int mar_split_wgs_per_cu(int dk, int pass);
 size_t mar_split_image_bytes(int dk);
 hipError_t mar_split_prepare();
-hipError_t mar_launch_split_images(const mar_ctx* c, const MarBatch& b, hipStream_t st);

@@ -34,6 +34,7 @@ struct FlashArgs {
   int32_t trows;       // chunk size rounded up to 64
   // split-precision passes: bf16 hi/lo images of the streamed matrix, [2*nchunks][yimg_tiles][image bytes]
   const char* yimg; int32_t yimg_tiles;
+  const char* ximg; int32_t ximg_tiles;   // the same of the stationary matrix
 };
 
 __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {

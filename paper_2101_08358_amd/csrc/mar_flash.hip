@@ -942,6 +942,8 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
   const int sr = split ? mar_split_stripe_rows(d.dk, pass) : mar_flash_stripe_rows(d.dk, pass);
   a.yimg = pass == 1 ? L.Kimg : L.Qimg;
   a.yimg_tiles = ((pass == 1 ? d.N : d.S) + 31) / 32;
+  a.ximg = pass == 1 ? L.Qimg : L.Kimg;
+  a.ximg_tiles = ((pass == 1 ? d.S : d.N) + 31) / 32;
   a.nstripes = (max_nx + sr - 1) / sr;
   const int ncs = 2 * b.nchunks;
   a.sy = pass == 1 ? d.sy1 : (pass == 2 ? d.sy2 : 1);

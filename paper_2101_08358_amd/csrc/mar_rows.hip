@@ -3,6 +3,7 @@
 // source / relation / destination rows, the per-row gradient reduction over the row-sorted
 // order, and the sparse Adagrad scatter.
 #include "mar_common.h"
+#include "mar_split.h"
 
 struct RowArgs {
   const float *node_emb, *rel_emb;
@@ -41,7 +42,7 @@ template <int GL> __device__ __forceinline__ float group_sum(float v) {
 template <int GL, int NV, bool VEC, int MODEL>
 __global__ void __launch_bounds__(256)
 k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float* __restrict__ qq,
-       float* __restrict__ kk, float* __restrict__ pos, float* __restrict__ pos_user) {
+       float* __restrict__ kk, float* __restrict__ pos, float* __restrict__ pos_user, SplitImages qi, SplitImages ki) {
   const int blk = blockIdx.x;
   constexpr int GPB = 256 / GL;                  // lane groups per block
   const int grp = threadIdx.x / GL, l = threadIdx.x % GL;
@@ -80,6 +81,14 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
         if (e0 + j < a.n) {
           float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e0 + j) * dk;
           float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e0 + j) * dk;
+          char* id_ = nullptr; char* is_ = nullptr;          // split precision: the rows' places in the images
+          if (qi.base) {
+            const int ch = (e0 + j) / a.S, er = (e0 + j) % a.S;
+            id_ = sp_row(qi, 2 * ch + MAR_SIDE_DST, er); is_ = sp_row(qi, 2 * ch + MAR_SIDE_SRC, er);
+            for (int k = dim + 4 * l; k < qi.dkp; k += 4 * GL) {        // zero columns up to the images' width
+              sp_store4(id_, qi.plane, k, make_float4(0.f, 0.f, 0.f, 0.f)); sp_store4(is_, qi.plane, k, make_float4(0.f, 0.f, 0.f, 0.f));
+            }
+          }
 #pragma unroll
           for (int v = 0; v < NV; ++v) {
             const int k = 2 * (l + GL * v);
@@ -89,8 +98,13 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
               const float2 wre = make_float2(rr[j][v].x * dr[j][v].x + ri[j][v].x * di[j][v].x, rr[j][v].y * dr[j][v].y + ri[j][v].y * di[j][v].y);
               const float2 wim = make_float2(rr[j][v].x * di[j][v].x - ri[j][v].x * dr[j][v].x, rr[j][v].y * di[j][v].y - ri[j][v].y * dr[j][v].y);
               acc[j] += (ure.x * dr[j][v].x + uim.x * di[j][v].x) + (ure.y * dr[j][v].y + uim.y * di[j][v].y);
-              *reinterpret_cast<float2*>(qd + k) = ure; *reinterpret_cast<float2*>(qd + h + k) = uim;
-              *reinterpret_cast<float2*>(qs + k) = wre; *reinterpret_cast<float2*>(qs + h + k) = wim;
+              if (qi.base) {
+                sp_store2(id_, qi.plane, k, ure); sp_store2(id_, qi.plane, h + k, uim);
+                sp_store2(is_, qi.plane, k, wre); sp_store2(is_, qi.plane, h + k, wim);
+              } else {
+                *reinterpret_cast<float2*>(qd + k) = ure; *reinterpret_cast<float2*>(qd + h + k) = uim;
+                *reinterpret_cast<float2*>(qs + k) = wre; *reinterpret_cast<float2*>(qs + h + k) = wim;
+              }
             }
           }
         }
@@ -113,6 +127,14 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
         if (e0 + j < a.n) {
           float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e0 + j) * dk;
           float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e0 + j) * dk;
+          char* id_ = nullptr; char* is_ = nullptr;
+          if (qi.base) {
+            const int ch = (e0 + j) / a.S, er = (e0 + j) % a.S;
+            id_ = sp_row(qi, 2 * ch + MAR_SIDE_DST, er); is_ = sp_row(qi, 2 * ch + MAR_SIDE_SRC, er);
+            for (int k = dim + 4 * l; k < qi.dkp; k += 4 * GL) {
+              sp_store4(id_, qi.plane, k, make_float4(0.f, 0.f, 0.f, 0.f)); sp_store4(is_, qi.plane, k, make_float4(0.f, 0.f, 0.f, 0.f));
+            }
+          }
 #pragma unroll
           for (int v = 0; v < NV; ++v) {
             const int k = 4 * (l + GL * v);
@@ -134,7 +156,8 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
                 nd[j] += (u.x * u.x + u.y * u.y) + (u.z * u.z + u.w * u.w);
                 ns[j] += (w.x * w.x + w.y * w.y) + (w.z * w.z + w.w * w.w);
               }
-              *reinterpret_cast<float4*>(qd + k) = u; *reinterpret_cast<float4*>(qs + k) = w;
+              if (qi.base) { sp_store4(id_, qi.plane, k, u); sp_store4(is_, qi.plane, k, w); }
+              else { *reinterpret_cast<float4*>(qd + k) = u; *reinterpret_cast<float4*>(qs + k) = w; }
             }
           }
         }
@@ -144,6 +167,12 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
         if (e0 + j >= a.n) break;
         float* qd = Q + ((size_t)MAR_SIDE_DST * a.B + e0 + j) * dk;
         float* qs = Q + ((size_t)MAR_SIDE_SRC * a.B + e0 + j) * dk;
+        char* id_ = nullptr; char* is_ = nullptr;
+        if (qi.base) {
+          const int ch = (e0 + j) / a.S, er = (e0 + j) % a.S;
+          id_ = sp_row(qi, 2 * ch + MAR_SIDE_DST, er); is_ = sp_row(qi, 2 * ch + MAR_SIDE_SRC, er);
+          for (int k = dim + l; k < qi.dkp; k += GL) { sp_store1(id_, qi.plane, k, 0.f); sp_store1(is_, qi.plane, k, 0.f); }
+        }
         if (MODEL == MAR_MODEL_COMPLEX) {
           const int h = dim >> 1;
           for (int k = l; k < h; k += GL) {
@@ -151,7 +180,10 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
             const float ure = sr * rr - si * ri, uim = sr * ri + si * rr;
             const float wre = rr * dr + ri * di, wim = rr * di - ri * dr;
             acc[j] += ure * dr + uim * di;
-            qd[k] = ure; qd[h + k] = uim; qs[k] = wre; qs[h + k] = wim;
+            if (qi.base) {
+              sp_store1(id_, qi.plane, k, ure); sp_store1(id_, qi.plane, h + k, uim);
+              sp_store1(is_, qi.plane, k, wre); sp_store1(is_, qi.plane, h + k, wim);
+            } else { qd[k] = ure; qd[h + k] = uim; qs[k] = wre; qs[h + k] = wim; }
           }
         } else {
           for (int k = l; k < dim; k += GL) {
@@ -160,10 +192,11 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
             if (MODEL == MAR_MODEL_DISTMULT) { u = s * r; w = r * d; acc[j] += u * d; }
             else if (MODEL == MAR_MODEL_DOT) { u = s; w = d; acc[j] += s * d; }
             else { u = s + r; w = d - r; const float df = u - d; acc[j] += df * df; nd[j] += u * u; ns[j] += w * w; }
-            qd[k] = u; qs[k] = w;
+            if (qi.base) { sp_store1(id_, qi.plane, k, u); sp_store1(is_, qi.plane, k, w); }
+            else { qd[k] = u; qs[k] = w; }
           }
         }
-        for (int k = dim + l; k < dk; k += GL) { qd[k] = 0.f; qs[k] = 0.f; }
+        if (!qi.base) { for (int k = dim + l; k < dk; k += GL) { qd[k] = 0.f; qs[k] = 0.f; } }
       }
     }
 #pragma unroll
@@ -184,6 +217,7 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
     if (rr0 >= 2 * a.cn) return;
     const float* row[PREP_NEGS];
     size_t krow[PREP_NEGS];
+    char* irow[PREP_NEGS];                                       // split precision: the rows' places in the images
 #pragma unroll
     for (int j = 0; j < PREP_NEGS; ++j) {
       const int rr = min(rr0 + j, 2 * a.cn - 1);
@@ -192,6 +226,7 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
       const int32_t id = side == MAR_SIDE_DST ? a.neg_dst[cj] : a.neg_src[cj];
       row[j] = a.node_emb + (size_t)id * dim;
       krow[j] = (size_t)side * a.C * a.N + cj;
+      irow[j] = ki.base ? sp_row(ki, 2 * (cj / a.N) + side, cj % a.N) : nullptr;
     }
     if (VEC) {
       float4 v4[PREP_NEGS][NV];
@@ -207,13 +242,17 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
       for (int j = 0; j < PREP_NEGS; ++j) {
         float nn = 0.f;
         if (rr0 + j < 2 * a.cn) {
+          if (ki.base) {
+            for (int k = dim + 4 * l; k < ki.dkp; k += 4 * GL) sp_store4(irow[j], ki.plane, k, make_float4(0.f, 0.f, 0.f, 0.f));
+          }
 #pragma unroll
           for (int v = 0; v < NV; ++v) {
             const int k = 4 * (l + GL * v);
             if (k < dim) {
               const float4 x = v4[j][v];
               nn += (x.x * x.x + x.y * x.y) + (x.z * x.z + x.w * x.w);
-              *reinterpret_cast<float4*>(Km + krow[j] * dk + k) = x;
+              if (ki.base) sp_store4(irow[j], ki.plane, k, x);
+              else *reinterpret_cast<float4*>(Km + krow[j] * dk + k) = x;
             }
           }
         }
@@ -226,10 +265,11 @@ k_prep(RowArgs a, int nbB, float* __restrict__ Q, float* __restrict__ Km, float*
       for (int j = 0; j < PREP_NEGS; ++j) {
         float nn = 0.f;
         if (rr0 + j < 2 * a.cn) {
-          for (int k = l; k < dk; k += GL) {
+          for (int k = l; k < (ki.base ? ki.dkp : dk); k += GL) {
             const float x = k < dim ? row[j][k] : 0.f;
             nn += x * x;
-            Km[krow[j] * dk + k] = x;
+            if (ki.base) sp_store1(irow[j], ki.plane, k, x);
+            else Km[krow[j] * dk + k] = x;
           }
         }
         if (MODEL == MAR_MODEL_TRANSE) {
@@ -948,14 +988,15 @@ static RowArgs row_args(const mar_ctx* c, const MarBatch& b) {
   return a;
 }
 
-hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, hipStream_t st) {
+hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, int images, hipStream_t st) {
   const MarLayout& L = c->L;
   RowArgs a = row_args(c, b);
+  const SplitImages qi = sp_images(images ? L.Qimg : nullptr, a.dk, c->dm.S), ki = sp_images(images ? L.Kimg : nullptr, a.dk, c->dm.N);
   const int GL = mar_lane_group(a.dk), gpb = 256 / GL;
   const int nbB = (b.n + gpb * PREP_EDGES - 1) / (gpb * PREP_EDGES);
   const int nbC = (2 * b.cn + gpb * PREP_NEGS - 1) / (gpb * PREP_NEGS);
   const dim3 grid(nbB + nbC), blk(256);
-#define PREP3(GLV, NVV, V, M) hipLaunchKernelGGL((k_prep<GLV, NVV, V, M>), grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out)
+#define PREP3(GLV, NVV, V, M) hipLaunchKernelGGL((k_prep<GLV, NVV, V, M>), grid, blk, 0, st, a, nbB, L.Q, L.Km, L.qq, L.kk, L.pos, pos_out, qi, ki)
 #define PREP(GLV, NVV, V) do { switch (a.model) { \
     case MAR_MODEL_DISTMULT: PREP3(GLV, NVV, V, MAR_MODEL_DISTMULT); break; \
     case MAR_MODEL_COMPLEX: PREP3(GLV, NVV, V, MAR_MODEL_COMPLEX); break; \
@@ -969,9 +1010,7 @@ hipError_t mar_launch_prep(const mar_ctx* c, const MarBatch& b, float* pos_out, 
   }
 #undef PREP
 #undef PREP3
-  hipError_t e = hipGetLastError();
-  if (e == hipSuccess && c->dm.split) e = mar_launch_split_images(c, b, st);
-  return e;
+  return hipGetLastError();
 }
 
 hipError_t mar_launch_filter(const mar_ctx* c, const MarBatch& b, const int64_t* dst_off, const int32_t* dst_ids,

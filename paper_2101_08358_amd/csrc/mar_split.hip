@@ -30,6 +30,7 @@
 
 #include "mar_common.h"
 #include "mar_flash.h"
+#include "mar_split.h"
 
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
@@ -49,20 +50,6 @@ __device__ __forceinline__ void split8(const float (&v)[8], v8bf& hi, v8bf& lo) 
   }
 }
 
-// Row pitch in bytes of a plane whose rows hold `rowb` bytes: the pitch in 4-byte banks, mod 64, must be one of
-// 12, 28, 36, 52 -- then the 16 rows of a 16-byte fragment read fall into 16 different groups of 4 banks, and the 4
-// rows of a transpose read into 4 different groups of 8 banks.
-constexpr int sp_pitch(int rowb) {
-  for (int pad = 16; pad <= 256; pad += 16) {
-    const int p = ((rowb + pad) / 4) % 64;
-    if (p == 12 || p == 28 || p == 36 || p == 52) return rowb + pad;
-  }
-  return rowb + 16;
-}
-constexpr int SP_TY = 32;                                  // rows per image
-constexpr int sp_plane(int ns) { return SP_TY * sp_pitch(64 * ns); }
-constexpr int sp_image(int ns) { return (2 * sp_plane(ns) + 1023) / 1024 * 1024; }
-
 template <int NS>
 struct SplitGeom {
   static constexpr int PA = sp_pitch(64 * NS);
@@ -72,10 +59,6 @@ struct SplitGeom {
   static constexpr int NCW = (NCH + 3) / 4;                // pieces per wave
   static constexpr size_t LDS_BYTES = 2 * (size_t)IMG;
 };
-
-// Contraction steps of 32 columns and 16-column output blocks that serve dk, and the instantiation's x-blocks per wave.
-static inline int sp_ns(int dk) { return dk <= 64 ? 2 : (dk <= 128 ? 4 : (dk <= 256 ? 8 : 13)); }
-static inline int sp_ncb(int dk) { return dk <= 64 ? 4 : (dk <= 112 ? 7 : (dk <= 128 ? 8 : (dk <= 208 ? 13 : (dk <= 256 ? 16 : 25)))); }
 
 __device__ __forceinline__ unsigned lds_address_b(const char* p) {
   return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
@@ -116,41 +99,6 @@ __device__ __forceinline__ void second_product(const char* hi, const char* lo, i
   }
 }
 
-// ------------------------------------------------------------------ operand images -----
-// One workgroup per (chunk-side, tile): splits 32 rows of an fp32 matrix into the hi and lo planes of an image.
-// Rows at or beyond the chunk-side's valid rows, and columns at or beyond dk, are written as zeros.
-struct ImageArgs {
-  const float* src;     // rows of dk floats; chunk-side cs starts at row (cs & 1) * side_rows + (cs >> 1) * cs_rows
-  char* img;            // [2 * nchunks][tiles][IMG]
-  int32_t dk, ns, tiles, cs_rows, last_rows, nchunks;
-  int64_t side_rows;
-};
-__global__ void __launch_bounds__(256) k_split_images(ImageArgs a) {
-  const int cs = blockIdx.x / a.tiles, t = blockIdx.x % a.tiles;
-  const int side = cs & 1, c = cs >> 1;
-  const int valid = c == a.nchunks - 1 ? a.last_rows : a.cs_rows;
-  const int pa = sp_pitch(64 * a.ns), plane = SP_TY * pa;
-  char* img = a.img + ((size_t)cs * a.tiles + t) * sp_image(a.ns);
-  const float* src = a.src + ((size_t)side * a.side_rows + (size_t)c * a.cs_rows) * a.dk;
-  const int groups = 4 * a.ns;                             // 8-column groups per row
-  for (int u = threadIdx.x; u < SP_TY * groups; u += 256) {
-    const int r = u / groups, q = u % groups;
-    const int row = t * SP_TY + r, col = 8 * q;
-    float v[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = 0.f;
-    if (row < valid) {
-      const float* p = src + (size_t)row * a.dk + col;
-      if (col < a.dk) { const float4 f = *reinterpret_cast<const float4*>(p); v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w; }
-      if (col + 4 < a.dk) { const float4 f = *reinterpret_cast<const float4*>(p + 4); v[4] = f.x; v[5] = f.y; v[6] = f.z; v[7] = f.w; }
-    }
-    v8bf hi, lo;
-    split8(v, hi, lo);
-    *reinterpret_cast<v8bf*>(img + r * pa + col * 2) = hi;
-    *reinterpret_cast<v8bf*>(img + plane + r * pa + col * 2) = lo;
-  }
-}
-
 // ------------------------------------------------------------------- the two passes -----
 // PASS 1: scores, online softmax and gQ = P K for 64 XB edges of one chunk-side against the chunk's negatives; the
 // unit numbering, the split of the last round's stripes and the lazily updated softmax reference are k_flash's, and
@@ -167,6 +115,7 @@ k_split(FlashArgs a) {
   constexpr int PA = SG::PA, PLANE = SG::PLANE, IMG = SG::IMG;
   constexpr int TY = SP_TY;
   constexpr int SR = 64 * XB;
+  constexpr float LOG2E = 1.44269504088896341f;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   float* const aux_all = reinterpret_cast<float*>(smem + 2 * IMG);   // PASS 2: [2][TY] log-sum-exp of the tile's edges
 
@@ -199,27 +148,22 @@ k_split(FlashArgs a) {
   const size_t x_base = PASS == 1 ? q_base : k_base;
   const int dk = a.dk;
 
-  // ---- stationary fragments: slots of step s = columns 32 s + 8g .. +7 of row x
+  // ---- stationary fragments from the rows' own images: slots of step s = columns 32 s + 8g .. +7 of row x
   int x[XB]; bool xv[XB];
   v8bf xh[XB][NS], xl[XB][NS];
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
     x[b] = stripe * SR + (wave * XB + b) * 16 + m;
     xv[b] = x[b] < n_x;
-    const float* xrow = a.X + (x_base + (xv[b] ? x[b] : 0)) * dk;
+    const char* xrow = a.ximg + ((size_t)cs * a.ximg_tiles + x[b] / TY) * IMG + (x[b] % TY) * PA + 16 * g;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const int col = 32 * s + 8 * g;
-      float v[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = 0.f;
-      if (xv[b] && col < dk) { const float4 f = *reinterpret_cast<const float4*>(xrow + col); v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w; }
-      if (xv[b] && col + 4 < dk) { const float4 f = *reinterpret_cast<const float4*>(xrow + col + 4); v[4] = f.x; v[5] = f.y; v[6] = f.z; v[7] = f.w; }
-      // the stationary rows carry the factor log2(e): the scores come out in units of ln 2 and the weights are
-      // plain powers of two of score differences
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] *= 1.44269504088896341f;
-      split8(v, xh[b][s], xl[b][s]);
+      xh[b][s] = (v8bf){0, 0, 0, 0, 0, 0, 0, 0};
+      xl[b][s] = (v8bf){0, 0, 0, 0, 0, 0, 0, 0};
+      if (xv[b]) {
+        xh[b][s] = *reinterpret_cast<const v8bf*>(xrow + 64 * s);
+        xl[b][s] = *reinterpret_cast<const v8bf*>(xrow + PLANE + 64 * s);
+      }
     }
   }
 
@@ -271,8 +215,8 @@ k_split(FlashArgs a) {
         for (int p = 1; p < a.sy_ml; ++p) { const float2 v = mlp[p * ml_stride]; ll += v.y * __expf(v.x - mm); }
       }
       // rows beyond the chunk: +inf, so that their weights are exp(-inf) = 0
-      // (in units of ln 2, like the scores; threads that share a row write the same value)
-      aux_all[buf * TY + f_row] = yr < n_y ? (mm + logf(ll)) * 1.44269504088896341f : __builtin_inff();
+      // (times log2(e): the weights are formed as 2^(score log2(e) - this); threads that share a row write the same value)
+      aux_all[buf * TY + f_row] = yr < n_y ? (mm + logf(ll)) * LOG2E : __builtin_inff();
     } else {
       asm volatile("" : : "v"(fence));
     }
@@ -348,23 +292,24 @@ k_split(FlashArgs a) {
       }
       if (PASS == 1) {
         const float mloc = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-        if (__any(mloc > mrun[b] + 23.f)) {               // 2^23 < e^16
+        if (__any(mloc > mrun[b] + 16.f)) {
           float mall = fmaxf(mloc, __shfl_xor(mloc, 16));
           mall = fmaxf(mall, __shfl_xor(mall, 32));
           const float mnew = fmaxf(mrun[b], mall);
-          float alpha = __builtin_amdgcn_exp2f(mrun[b] - mnew);
+          float alpha = __expf(mrun[b] - mnew);
           asm volatile("" : "+v"(alpha));                  // a real branch: keeps the rescale from being executed speculatively
           lrun[b] *= alpha;
 #pragma unroll
           for (int cb = 0; cb < NCB; ++cb) oacc[b][cb] *= alpha;
           mrun[b] = mnew;
         }
+        const float nm2 = -LOG2E * mrun[b];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) w[k] = __builtin_amdgcn_exp2f(sc[k] - mrun[b]);
+        for (int k = 0; k < 8; ++k) w[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[k], LOG2E, nm2));
         lrun[b] += ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
       } else {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) w[k] = __builtin_amdgcn_exp2f(sc[k] - lse8[k]);
+        for (int k = 0; k < 8; ++k) w[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[k], LOG2E, -lse8[k]));
       }
       split8(w, wh[b], wl[b]);
     }
@@ -393,7 +338,7 @@ k_split(FlashArgs a) {
       float ltot = lrun[b] + __shfl_xor(lrun[b], 16);
       ltot += __shfl_xor(ltot, 32);
       if (!xv[b]) continue;
-      if (g == 0) *reinterpret_cast<float2*>(ml_out + (size_t)x[b] * 2) = make_float2(mrun[b] * 0.693147180559945309f, ltot);
+      if (g == 0) *reinterpret_cast<float2*>(ml_out + (size_t)x[b] * 2) = make_float2(mrun[b], ltot);
       float* orow = o_out + (size_t)x[b] * dk;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
@@ -455,21 +400,4 @@ hipError_t mar_split_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t
   if (ns == 4) return ncb == 7 ? sp_launch<4, 7, 2>(a, pass, grid, st) : sp_launch<4, 8, 2>(a, pass, grid, st);
   if (ns == 8) return ncb == 13 ? sp_launch<8, 13, 1>(a, pass, grid, st) : sp_launch<8, 16, 1>(a, pass, grid, st);
   return sp_launch<13, 25, 1>(a, pass, grid, st);
-}
-
-// Images of the gathered operands of one batch: the negatives' rows (streamed by pass 1) and the edge-side operands
-// (streamed by pass 2).
-hipError_t mar_launch_split_images(const mar_ctx* c, const MarBatch& b, hipStream_t st) {
-  const MarDims& d = c->dm;
-  if (b.n == 0) return hipSuccess;
-  ImageArgs k;
-  k.dk = d.dk; k.ns = sp_ns(d.dk); k.nchunks = b.nchunks;
-  k.src = c->L.Km; k.img = c->L.Kimg; k.tiles = (d.N + SP_TY - 1) / SP_TY; k.cs_rows = d.N; k.last_rows = d.N;
-  k.side_rows = (int64_t)d.C * d.N;
-  hipLaunchKernelGGL(k_split_images, dim3((unsigned)(2 * b.nchunks * k.tiles)), dim3(256), 0, st, k);
-  ImageArgs q = k;
-  q.src = c->L.Q; q.img = c->L.Qimg; q.tiles = (d.S + SP_TY - 1) / SP_TY; q.cs_rows = d.S;
-  q.last_rows = b.n - (b.nchunks - 1) * d.S; q.side_rows = d.B;
-  hipLaunchKernelGGL(k_split_images, dim3((unsigned)(2 * b.nchunks * q.tiles)), dim3(256), 0, st, q);
-  return hipGetLastError();
 }
