@@ -81,6 +81,23 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   // workgroups share a stripe, each streaming a slice of the other matrix, until a pass has at least
   // MAR_FLASH_TARGET_WGS workgroups (measured best for a 10,000-edge batch; the 50,000-edge shapes have
   // enough stripes and are not split).
+  // Split precision: into how many parts to cut the (chunk-side, stripe) units beyond the last whole round.  The
+  // units are fewer and longer than the fp32 passes', and the remainder often exceeds half a round, so the parts may
+  // take several rounds of their own; every part beyond the first costs a write and a read of the stripes' output
+  // rows.  Estimated in microseconds from the rates these passes reach (about 600 TFLOP/s of bf16 work over all
+  // workgroup slots, 4.5 TB/s of memory traffic): the time of the last rounds plus the merge.
+  auto split_parts = [&](long rem_units, long slots, long ntiles, int sr, int n_y, long rows_per_cs) -> long {
+    const double unit_us = 12.0 * sr * (double)n_y * d->dk * (double)slots / 6.0e8;
+    const double rows = (double)rem_units / (double)((rows_per_cs + sr - 1) / sr) * (double)rows_per_cs;
+    long k = 1;
+    double best = 1e30;
+    for (long kk = 1; kk <= MAR_MAX_PARTS && kk <= ntiles; ++kk) {
+      const double cost = (double)((rem_units * kk + slots - 1) / slots) / (double)kk * unit_us
+                        + (double)(kk - 1) * rows * d->dk * 8.0 / 4.5e6;
+      if (cost < best) { best = cost; k = kk; }
+    }
+    return k;
+  };
   auto split = [&](int pass, int n_x, int n_y, int32_t* sy, int32_t* tps) {
     const long target = pass == 1 ? MAR_FLASH_TARGET_WGS1 : MAR_FLASH_TARGET_WGS2;
     const int sr = stripe_rows(pass);
@@ -114,20 +131,31 @@ static int check_config(const mar_config* cfg, MarDims* d) {
       long k = slots / rem_units;
       if (k > MAR_MAX_PARTS) k = MAR_MAX_PARTS;
       if (k > ntiles) k = ntiles;
-      if (sp) {
-        // the split-precision units are fewer and longer, and the remainder often exceeds half a round: take the
-        // number of parts whose last, partly filled round of parts is shortest
-        double best = 1e30;
-        for (long kk = 1; kk <= MAR_MAX_PARTS && kk <= ntiles; ++kk) {
-          const double cost = (double)((rem_units * kk + slots - 1) / slots) / (double)kk + 0.02 * (double)(kk - 1);
-          if (cost < best) { best = cost; k = kk; }
-        }
-      }
+      if (sp) k = split_parts(rem_units, slots, ntiles, sr1, d->N, nstripes * sr1);
       if (k >= 2) {
         d->rem_cs0 = (int32_t)(8 * whole_groups);
         d->rem_tps = (int32_t)((ntiles + k - 1) / k);
         d->rem_k = (int32_t)((ntiles + d->rem_tps - 1) / d->rem_tps);
         d->rem_rows = (int64_t)(2 * d->C - d->rem_cs0) * ((d->S + 63) & ~63);
+      }
+    }
+  }
+  d->rem2_cs0 = 2 * d->C; d->rem2_k = 1; d->rem2_tps = 0; d->rem2_rows = 0;
+  if (sp && d->sy2 == 1) {                                 // the same for pass 2 (split precision only)
+    const long slots = 256L * wgs_per_cu(2);
+    const int sr2 = stripe_rows(2);
+    const long nstripes = (d->N + sr2 - 1) / sr2, groups = (2L * d->C + 7) / 8, per_group = 8 * nstripes;
+    const long ntiles = (d->S + tile_rows(2) - 1) / tile_rows(2);
+    const long full_rounds = groups * per_group / slots;
+    const long whole_groups = full_rounds * slots / per_group;
+    if (full_rounds >= 1 && whole_groups < groups) {
+      const long rem_units = (2L * d->C - 8 * whole_groups) * nstripes;
+      const long k = split_parts(rem_units, slots, ntiles, sr2, d->S, nstripes * sr2);
+      if (k >= 2) {
+        d->rem2_cs0 = (int32_t)(8 * whole_groups);
+        d->rem2_tps = (int32_t)((ntiles + k - 1) / k);
+        d->rem2_k = (int32_t)((ntiles + d->rem2_tps - 1) / d->rem2_tps);
+        d->rem2_rows = (int64_t)(2 * d->C - d->rem2_cs0) * (nstripes * sr2);
       }
     }
   }
@@ -186,6 +214,7 @@ static size_t carve(const MarDims& d, char* base, MarLayout* L) {
   l.R = (float*)take(d.split ? 0 : 2 * (size_t)d.C * (size_t)((d.S + 63) & ~63) * (size_t)(((d.N + 127) & ~127) / 16) * 4);
   l.Kimg = (char*)take(d.split ? 2 * (size_t)d.C * (size_t)((d.N + 31) / 32) * mar_split_image_bytes(d.dk) : 0);
   l.Qimg = (char*)take(d.split ? 2 * (size_t)d.C * (size_t)((d.S + 31) / 32) * mar_split_image_bytes(d.dk) : 0);
+  l.Gx = (float*)take((size_t)(d.rem2_k - 1) * (size_t)d.rem2_rows * dk * 4);
   l.G = (float*)take(n_pos * dk * 4);
   l.carry = (float*)take(blocks * 2 * dk * 4);
   l.loss_part = (float*)take((B / 4 + 2) * 4);

@@ -41,6 +41,7 @@ struct MarLayout {
   float*    R;            // [2*chunks][N rounded up to 128, / 16][S rounded up to 64] the reference each 16-negative block of T was written with
   char*     Kimg;         // split precision: [2*chunks][N / 32 rounded up][image] bf16 hi/lo planes of Km's rows
   char*     Qimg;         // split precision: [2*chunks][S / 32 rounded up][image] the same of Q's rows
+  float*    Gx;           // [rem2_k - 1][rem2_rows][dk] parts 1.. of pass 2's split stripes (split precision)
   float*    G;            // [roles*n + 2*cn*sy2][dk] gradient rows: edge-side occurrence k < roles*n at row k, part i
                           // of negative occurrence k at row roles*n + (k - roles*n)*sy2 + i
   float*    carry;        // [reduce blocks][2][dk] partial sums of segments that cross workgroup borders
@@ -61,6 +62,10 @@ struct MarDims {
   // chunk-sides from rem_cs0 on -- are each split into rem_k parts of rem_tps tiles, which a small kernel merges.
   int32_t rem_cs0, rem_k, rem_tps;
   int64_t rem_rows;                // (2C - rem_cs0) * (S rounded up to 64)
+  // The same for pass 2 in split precision (chunk-sides counted in that pass's launch order): parts 1.. of a split
+  // stripe write their gradient rows to Gx, and a small kernel adds them to the regular rows.
+  int32_t rem2_cs0, rem2_k, rem2_tps;
+  int64_t rem2_rows;               // (2C - rem2_cs0) * (N rounded up to whole stripes)
   int64_t u_max;                   // min(num_nodes + num_rels, n_occ_max)
   int64_t nwords;                  // words of the touched-id map
   int32_t ipw_log2;                // ids per word: 5 = one bit per id (atomic marks), 2 = one byte per id (plain stores)

@@ -958,6 +958,13 @@ hipError_t mar_launch_flash(const mar_ctx* c, const MarBatch& b, int pass, int32
     const int rem_wgs = (ncs - d.rem_cs0) * a.nstripes * d.rem_k;
     grid = dim3((unsigned)(8 * (a.whole_slots + (rem_wgs + 7) / 8)));
   }
+  if (split && pass == 2 && d.rem2_k > 1 && b.n == d.B) {   // full batch: split the stripes beyond the last whole round
+    a.whole_slots = d.rem2_cs0 / 8 * a.nstripes;
+    a.rem_cs0 = d.rem2_cs0; a.rem_k = d.rem2_k; a.rem_tps = d.rem2_tps; a.rem_rows = d.rem2_rows;
+    a.outx = L.Gx;
+    const int rem_wgs = (ncs - d.rem2_cs0) * a.nstripes * d.rem2_k;
+    grid = dim3((unsigned)(8 * (a.whole_slots + (rem_wgs + 7) / 8)));
+  }
   if (split) return mar_split_launch(a, pass, grid, st);
   const int l2 = c->cfg.model == MAR_MODEL_TRANSE;
   const int nk = d.dk / 4;

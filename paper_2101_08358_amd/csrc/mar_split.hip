@@ -136,6 +136,7 @@ k_split(FlashArgs a) {
     stripe = unit % a.nstripes;
     tps = a.rem_tps;
   }
+  const int csl = cs;                                      // chunk-side in launch order
   if (PASS == 2) cs = 2 * a.nchunks - 1 - cs;              // reverse of pass 1's order (see k_flash_bwd)
   if (cs < 0 || cs >= 2 * a.nchunks) return;
   const int side = cs & 1, c = cs >> 1;
@@ -350,13 +351,37 @@ k_split(FlashArgs a) {
 #pragma unroll
     for (int b = 0; b < XB; ++b) {
       if (!xv[b]) continue;
-      float* orow = a.out + (a.roles * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x[b]) * a.sy + part) * dk;
+      float* orow = a.out + (a.roles * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x[b]) * a.sy +
+                             (slot >= a.whole_slots ? 0 : part)) * dk;
+      if (slot >= a.whole_slots && part > 0)               // parts 1.. of a split stripe: added to the regular row afterwards
+        orow = a.outx + ((size_t)(part - 1) * a.rem_rows + (size_t)(csl - a.rem_cs0) * (a.nstripes * SR) + x[b]) * dk;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
         const int col = 16 * cb + 4 * g;
         if (col < dk) *reinterpret_cast<float4*>(orow + col) = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
       }
     }
+  }
+}
+
+// Adds parts 1.. of pass 2's split stripes to the gradient rows that part 0 wrote, in the parts' order.  One group of
+// 32 lanes per row.
+__global__ void __launch_bounds__(256) k_split_merge2(FlashArgs a, int stripe_rows) {
+  const int grp = threadIdx.x >> 5, l = threadIdx.x & 31;
+  const long rrow = (long)blockIdx.x * 8 + grp;
+  if (rrow >= a.rem_rows) return;
+  const int pitch = a.nstripes * stripe_rows;
+  const int cs = 2 * a.nchunks - 1 - (a.rem_cs0 + (int)(rrow / pitch)), x = (int)(rrow % pitch);
+  if (cs < 0 || x >= a.N) return;
+  const int side = cs & 1, c = cs >> 1;
+  float* o0 = a.out + (a.roles * (size_t)a.n + ((side == MAR_SIDE_DST ? 0 : (size_t)a.cn) + (size_t)c * a.N + x)) * a.dk;
+  for (int k = 4 * l; k < a.dk; k += 128) {
+    float4 o = *reinterpret_cast<const float4*>(o0 + k);
+    for (int p = 1; p < a.rem_k; ++p) {
+      const float4 q = *reinterpret_cast<const float4*>(a.outx + ((size_t)(p - 1) * a.rem_rows + rrow) * a.dk + k);
+      o.x += q.x; o.y += q.y; o.z += q.z; o.w += q.w;
+    }
+    *reinterpret_cast<float4*>(o0 + k) = o;
   }
 }
 
@@ -394,7 +419,18 @@ static hipError_t sp_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t
 }
 
 // `a` is filled by mar_launch_flash (units, parts, buffers); this picks the instantiation for a.dk.
+static hipError_t sp_launch_sized(const FlashArgs& a, int pass, dim3 grid, hipStream_t st);
+
 hipError_t mar_split_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
+  hipError_t e = sp_launch_sized(a, pass, grid, st);
+  if (e == hipSuccess && pass == 2 && a.rem_k > 1) {
+    hipLaunchKernelGGL(k_split_merge2, dim3((unsigned)((a.rem_rows + 7) / 8)), dim3(256), 0, st, a, mar_split_stripe_rows(a.dk, 2));
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+static hipError_t sp_launch_sized(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
   const int ns = sp_ns(a.dk), ncb = sp_ncb(a.dk);
   if (ns == 2) return sp_launch<2, 4, 2>(a, pass, grid, st);
   if (ns == 4) return ncb == 7 ? sp_launch<4, 7, 2>(a, pass, grid, st) : sp_launch<4, 8, 2>(a, pass, grid, st);

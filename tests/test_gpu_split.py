@@ -48,6 +48,13 @@ def test_one_step_when_pass_one_splits_its_last_round():
     print(check_step(out), flush=True)
 
 
+def test_one_step_when_pass_two_splits_its_last_round():
+    """80 chunk-sides x 8 stripes of 128 negatives = 640 units of the second pass on 512 workgroup slots: the stripes of
+    the last 16 chunk-sides are split into parts over the edges' tiles, and the parts' gradient rows added up."""
+    out = run_step_both(COMPLEX, 50000, 3, 64, 40000, 40, 1024, 40000, seed=13, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
 def test_evaluation_in_a_split_precision_context_is_the_fp32_one():
     """Ranks are always computed in fp32: a context created for split-precision training ranks like any other."""
     rng = np.random.default_rng(9)
