@@ -35,6 +35,30 @@ def test_one_step_other_widths(model, dim):
     print(check_step(out), flush=True)
 
 
+@pytest.mark.parametrize("n", (1, 33))
+def test_short_batches(n):
+    """One edge, and one edge more than a tile of 32."""
+    out = run_step_both(DISTMULT, 800, 3, 52, 256, 4, 96, n, seed=21 + n, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
+def test_empty_batch_is_a_no_op():
+    tr = mar.Trainer(100, 2, 16, DISTMULT, 64, 2, 8, seed=3, precision=SPLIT)
+    torch.cuda.synchronize()
+    before = tr.node_emb.clone()
+    e = torch.zeros(0, dtype=torch.int32, device=tr.device)
+    tr.loss.fill_(5.0)
+    tr.train_batch(e, e, e)
+    torch.cuda.synchronize()
+    assert tr.loss.item() == 0.0 and torch.equal(before, tr.node_emb)
+    tr.close()
+
+
+def test_narrowest_rows():
+    out = run_step_both(DOT, 600, 1, 4, 256, 2, 64, 256, seed=2, std=0.3, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
 def test_one_step_with_trained_scale_embeddings():
     """Rows of the size a trained table has (std 0.3): scores of order 10, softmax far from uniform."""
     out = run_step_both(DISTMULT, 3000, 5, 100, 1024, 4, 500, 1024, seed=3, std=0.3, precision=SPLIT)
