@@ -40,7 +40,7 @@ def note(msg):
 
 def measured_traffic(workload):
     """HBM bytes per launch of each kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary committed as
-    profiles/traffic_<workload>.md (table rows `| `kernel` | fetch MB | write MB | total MB |`).  Returns
+    profiles/traffic_<workload>.md (`<workload>_split`: the same workload with the split-precision contraction) (table rows `| `kernel` | fetch MB | write MB | total MB |`).  Returns
     {kernel name without template arguments: bytes} or {} if there is no summary for this workload."""
     path = os.path.join(ROOT, "profiles", "traffic_%s.md" % workload)
     out = {}
@@ -206,7 +206,7 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
     scatter_bytes = (roles * n + 2 * cn) * dk * 4 + U * w.dim * 16                   # gradient rows read + theta/state r+w
     chain_bytes = n * (2 * dk + 2 * roles * w.dim) * 4                               # operand gradients + s/r/d read, gradient rows written
     phases = {nm: round(per_step(ms) * 1e3, 2) for nm, ms in zip(mar.binding.PHASE_NAMES, phase_ms)}
-    traffic = measured_traffic(w.name) if not nodes else {}          # per-launch bytes do not depend on the edge list
+    traffic = measured_traffic(w.name + ("_split" if precision else "")) if not nodes else {}   # per-launch bytes do not depend on the edge list
     if not precision:
         roof["traffic"] = (traffic.get("k_flash", 0.0) + traffic.get("k_flash_bwd", 0.0)) or None
     else:
