@@ -70,29 +70,31 @@ __device__ __forceinline__ v8bf join8(v4s a, v4s b) {
   return __builtin_bit_cast(v8bf, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// O^T[c][x] += sum over the tile's 32 rows of Y[y][c] W[y][x], all NCB 16-column blocks; W is given split.  Blocks
-// are taken a few at a time so that consecutive matrix instructions write different accumulators.
+// O^T[c][x] += sum over the tile's 32 rows of Y[y][c] W[y][x] for the 16-column blocks cb0 .. cb0 + ncb - 1 (ncb <= NCB,
+// uniform over the wave); W is given split.  Blocks are taken a few at a time so that consecutive matrix instructions
+// write different accumulators.
 template <int NCB, int XB, int PA>
-__device__ __forceinline__ void second_product(const char* hi, const char* lo, int trofs, const v8bf (&wh)[XB],
+__device__ __forceinline__ void second_product(const char* hi, const char* lo, int trofs, int cb0, int ncb, const v8bf (&wh)[XB],
                                                const v8bf (&wl)[XB], v4f (&oacc)[XB][NCB]) {
   constexpr int CG = XB >= 2 ? 2 : 4;
+  hi += trofs + 32 * cb0; lo += trofs + 32 * cb0;
 #pragma unroll
-  for (int cb0 = 0; cb0 < NCB; cb0 += CG) {
+  for (int c0 = 0; c0 < NCB; c0 += CG) {
     v8bf ah[CG], al[CG];
 #pragma unroll
     for (int j = 0; j < CG; ++j) {
-      if (cb0 + j < NCB) {
-        ah[j] = join8(lds_read_tr(hi + trofs + 32 * (cb0 + j)), lds_read_tr(hi + trofs + 16 * PA + 32 * (cb0 + j)));
-        al[j] = join8(lds_read_tr(lo + trofs + 32 * (cb0 + j)), lds_read_tr(lo + trofs + 16 * PA + 32 * (cb0 + j)));
+      if (c0 + j < NCB && (c0 + j < NCB - 1 || c0 + j < ncb)) {   // only the last block may be absent
+        ah[j] = join8(lds_read_tr(hi + 32 * (c0 + j)), lds_read_tr(hi + 16 * PA + 32 * (c0 + j)));
+        al[j] = join8(lds_read_tr(lo + 32 * (c0 + j)), lds_read_tr(lo + 16 * PA + 32 * (c0 + j)));
       }
     }
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
 #pragma unroll
       for (int j = 0; j < CG; ++j) {
-        if (cb0 + j < NCB) {
+        if (c0 + j < NCB && (c0 + j < NCB - 1 || c0 + j < ncb)) {
 #pragma unroll
-          for (int b = 0; b < XB; ++b) oacc[b][cb0 + j] = mfma_bf(k == 1 ? al[j] : ah[j], k == 2 ? wl[b] : wh[b], oacc[b][cb0 + j]);
+          for (int b = 0; b < XB; ++b) oacc[b][c0 + j] = mfma_bf(k == 1 ? al[j] : ah[j], k == 2 ? wl[b] : wh[b], oacc[b][c0 + j]);
         }
       }
     }
@@ -108,18 +110,31 @@ __device__ __forceinline__ void second_product(const char* hi, const char* lo, i
 // and reading them back costs 8 bytes of memory traffic per pair, computing a score again 6 d bf16 flops: at this
 // matrix rate the second is several times cheaper (the fp32 passes, whose matrix rate is 16 times lower, store them).
 // The unit numbering and the gradient rows written are k_flash_bwd's.
-template <int NS, int NCB, int XB, int PASS>
-__global__ void __launch_bounds__(256) MAR_WAVES_PER_SIMD((NS <= 8 ? 2 : 1))
+// CSP = 2 (widest rows): two waves share each 16-row block, each taking half of the columns -- half of the
+// contraction steps of the score product (the partial scores are exchanged through LDS and added, so both waves go
+// on with the same scores, weights and softmax statistics) and half of the second product's output blocks.  A wave
+// then holds half of the stationary fragments and half of the accumulators, and a workgroup of eight waves puts two
+// waves on every SIMD where the four-wave form has registers for one.
+template <int NS, int NCB, int XB, int PASS, int CSP>
+__global__ void __launch_bounds__(256 * CSP) MAR_WAVES_PER_SIMD((CSP == 2 || NS <= 8 ? 2 : 1))
 k_split(FlashArgs a) {
   typedef SplitGeom<NS> SG;
   constexpr int PA = SG::PA, PLANE = SG::PLANE, IMG = SG::IMG;
   constexpr int TY = SP_TY;
   constexpr int SR = 64 * XB;
+  constexpr int NW = 4 * CSP;                              // waves
+  constexpr int NSA = (NS + CSP - 1) / CSP, NCBA = (NCB + CSP - 1) / CSP;   // steps and output blocks per wave
+  constexpr int NCW = (SG::NCH + NW - 1) / NW;             // 1 KB pieces of an image per wave
   constexpr float LOG2E = 1.44269504088896341f;
+  static_assert(CSP == 1 || XB == 1, "the exchange of partial scores is written for one row block per wave");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   float* const aux_all = reinterpret_cast<float*>(smem + 2 * IMG);   // PASS 2: [2][TY] log-sum-exp of the tile's edges
+  float* const xch = aux_all + 2 * TY;                     // CSP = 2: [NW][8][64] partial scores
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave_all = threadIdx.x >> 6;
+  const int wave = wave_all / CSP, half = wave_all % CSP;  // row block of the workgroup, half of the columns
+  const int s0 = half * NSA, ns = min(NSA, NS - s0);       // this wave's contraction steps s0 .. s0 + ns - 1
+  const int cb0 = half * NCBA, ncb = min(NCBA, NCB - cb0); // and output blocks
   const int g = lane >> 4, m = lane & 15;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   int part, cs, stripe, tps = a.tps;
@@ -151,29 +166,29 @@ k_split(FlashArgs a) {
 
   // ---- stationary fragments from the rows' own images: slots of step s = columns 32 s + 8g .. +7 of row x
   int x[XB]; bool xv[XB];
-  v8bf xh[XB][NS], xl[XB][NS];
+  v8bf xh[XB][NSA], xl[XB][NSA];
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
     x[b] = stripe * SR + (wave * XB + b) * 16 + m;
     xv[b] = x[b] < n_x;
-    const char* xrow = a.ximg + ((size_t)cs * a.ximg_tiles + x[b] / TY) * IMG + (x[b] % TY) * PA + 16 * g;
+    const char* xrow = a.ximg + ((size_t)cs * a.ximg_tiles + x[b] / TY) * IMG + (x[b] % TY) * PA + 16 * g + 64 * s0;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
+    for (int s = 0; s < NSA; ++s) {
       xh[b][s] = (v8bf){0, 0, 0, 0, 0, 0, 0, 0};
       xl[b][s] = (v8bf){0, 0, 0, 0, 0, 0, 0, 0};
-      if (xv[b]) {
+      if (xv[b] && s < ns) {
         xh[b][s] = *reinterpret_cast<const v8bf*>(xrow + 64 * s);
         xl[b][s] = *reinterpret_cast<const v8bf*>(xrow + PLANE + 64 * s);
       }
     }
   }
 
-  v4f oacc[XB][NCB];
+  v4f oacc[XB][NCBA];
   float mrun[XB], lrun[XB];
 #pragma unroll
   for (int b = 0; b < XB; ++b) {
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < NCBA; ++cb) oacc[b][cb] = (v4f){0.f, 0.f, 0.f, 0.f};
     mrun[b] = -3.0e38f; lrun[b] = 0.f;
   }
 
@@ -189,7 +204,7 @@ k_split(FlashArgs a) {
   const v4i ywords = buf_words(ybase, ybytes);
   const BufRsrc ysrc = buf_rsrc(ybase, ybytes);
   const BufRsrc mlsrc = buf_rsrc(a.ml + q_base * 2, PASS == 2 ? (uint32_t)ne * 8 : 0u);
-  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave_all);
   const int f_row = threadIdx.x % TY;
   const size_t ml_stride = (size_t)2 * a.B;               // rows per part of pass 1's statistics
   float fence = 0.f;
@@ -198,8 +213,8 @@ k_split(FlashArgs a) {
   auto dma_tile = [&](int t, int buf) {
     const int tofs = t * IMG;
 #pragma unroll
-    for (int q = 0; q < SG::NCW; ++q) {
-      const int pc = 4 * q + wave_s;
+    for (int q = 0; q < NCW; ++q) {
+      const int pc = NW * q + wave_s;
       if (pc < SG::NCH) buf_load4_to_lds(ywords, lds_address_b(smem) + buf * IMG + pc * 1024, lane * 16, tofs + pc * 1024, token);
     }
     if (PASS == 2) st_ml = buf_load2(mlsrc, f_row * 8 + token, t * TY * 8);
@@ -247,8 +262,8 @@ k_split(FlashArgs a) {
       for (int b = 0; b < XB; ++b) sacc[yb][b] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
     {
-      constexpr int NG = 2 * NS, PD = 4;
-      const int fofs = m * PA + 16 * g;
+      constexpr int NG = 2 * NSA, PD = NG < 4 ? NG : 4;
+      const int fofs = m * PA + 16 * g + 64 * s0;
       v8bf fh[PD], fl[PD];
 #pragma unroll
       for (int q = 0; q < PD; ++q) {                       // group q: step q / 2, block q % 2
@@ -258,6 +273,7 @@ k_split(FlashArgs a) {
 #pragma unroll
       for (int q = 0; q < NG; ++q) {
         const int s = q / 2, yb = q % 2;
+        if (CSP > 1 && s == NSA - 1 && s >= ns) break;       // the second half may have one step less (uniform over the wave)
         const v8bf ah = fh[q % PD], al = fl[q % PD];
         if (q + PD < NG) {
           fh[q % PD] = *reinterpret_cast<const v8bf*>(hi + fofs + ((q + PD) % 2) * 16 * PA + ((q + PD) / 2) * 64);
@@ -270,6 +286,21 @@ k_split(FlashArgs a) {
 #pragma unroll
         for (int b = 0; b < XB; ++b) sacc[yb][b] = mfma_bf(ah, xl[b][s], sacc[yb][b]);
         __builtin_amdgcn_sched_barrier(0);                 // keeps the reads PD groups ahead of their use
+      }
+    }
+    if (CSP == 2) {                                        // add the other half's partial scores
+      float* mine = xch + (wave_all * 8) * 64 + lane;
+#pragma unroll
+      for (int yb = 0; yb < 2; ++yb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mine[(4 * yb + r) * 64] = sacc[yb][0][r];
+      }
+      __syncthreads();
+      const float* other = xch + ((wave_all ^ 1) * 8) * 64 + lane;
+#pragma unroll
+      for (int yb = 0; yb < 2; ++yb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sacc[yb][0][r] += other[(4 * yb + r) * 64];
       }
     }
     // -- weights of the lane's 8 pairs per x-block: slot kk <-> y = y0 + (kk < 4 ? 4g + kk : 16 + 4g + kk - 4)
@@ -301,7 +332,7 @@ k_split(FlashArgs a) {
           asm volatile("" : "+v"(alpha));                  // a real branch: keeps the rescale from being executed speculatively
           lrun[b] *= alpha;
 #pragma unroll
-          for (int cb = 0; cb < NCB; ++cb) oacc[b][cb] *= alpha;
+          for (int cb = 0; cb < NCBA; ++cb) oacc[b][cb] *= alpha;
           mrun[b] = mnew;
         }
         const float nm2 = -LOG2E * mrun[b];
@@ -315,7 +346,7 @@ k_split(FlashArgs a) {
       split8(w, wh[b], wl[b]);
     }
     // -- O^T[c][x] += sum_y Y[y][c] W[y][x]
-    second_product<NCB, XB, PA>(hi, lo, trofs, wh, wl, oacc);
+    second_product<NCBA, XB, PA>(hi, lo, trofs, cb0, ncb, wh, wl, oacc);
     if (has_next) {
       dma_land(t + 1, buf ^ 1);
       __syncthreads();                                     // tile t + 1 is in LDS; every wave is done with tile t
@@ -339,12 +370,12 @@ k_split(FlashArgs a) {
       float ltot = lrun[b] + __shfl_xor(lrun[b], 16);
       ltot += __shfl_xor(ltot, 32);
       if (!xv[b]) continue;
-      if (g == 0) *reinterpret_cast<float2*>(ml_out + (size_t)x[b] * 2) = make_float2(mrun[b], ltot);
+      if (g == 0 && half == 0) *reinterpret_cast<float2*>(ml_out + (size_t)x[b] * 2) = make_float2(mrun[b], ltot);
       float* orow = o_out + (size_t)x[b] * dk;
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        const int col = 16 * cb + 4 * g;
-        if (col < dk) *reinterpret_cast<float4*>(orow + col) = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
+      for (int cb = 0; cb < NCBA; ++cb) {
+        const int col = 16 * (cb0 + cb) + 4 * g;
+        if (cb < ncb && col < dk) *reinterpret_cast<float4*>(orow + col) = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
       }
     }
   } else {                                                 // gradient row of part `part` of each negative's occurrence
@@ -356,9 +387,9 @@ k_split(FlashArgs a) {
       if (slot >= a.whole_slots && part > 0)               // parts 1.. of a split stripe: added to the regular row afterwards
         orow = a.outx + ((size_t)(part - 1) * a.rem_rows + (size_t)(csl - a.rem_cs0) * (a.nstripes * SR) + x[b]) * dk;
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        const int col = 16 * cb + 4 * g;
-        if (col < dk) *reinterpret_cast<float4*>(orow + col) = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
+      for (int cb = 0; cb < NCBA; ++cb) {
+        const int col = 16 * (cb0 + cb) + 4 * g;
+        if (cb < ncb && col < dk) *reinterpret_cast<float4*>(orow + col) = make_float4(oacc[b][cb][0], oacc[b][cb][1], oacc[b][cb][2], oacc[b][cb][3]);
       }
     }
   }
@@ -392,29 +423,33 @@ int mar_split_tile_rows() { return SP_TY; }
 int mar_split_wgs_per_cu(int dk, int pass) { (void)pass; return sp_ns(dk) <= 8 ? 2 : 1; }
 size_t mar_split_image_bytes(int dk) { return (size_t)sp_image(sp_ns(dk)); }
 
-template <int NS, int NCB, int XB>
+// LDS of a launch: two image buffers, the log-sum-exp of a tile's edges (pass 2), the exchange area (CSP = 2)
+template <int NS, int CSP>
+constexpr size_t sp_lds() { return SplitGeom<NS>::LDS_BYTES + 2 * SP_TY * 4 + (CSP == 2 ? 8 * 8 * 64 * 4 : 0); }
+
+template <int NS, int NCB, int XB, int CSP>
 static hipError_t sp_prepare() {
-  constexpr size_t lds = SplitGeom<NS>::LDS_BYTES + 2 * SP_TY * 4;
+  constexpr size_t lds = sp_lds<NS, CSP>();
   hipError_t e = hipSuccess;
   if (lds > 64 * 1024) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 1, CSP>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 2, CSP>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   }
   return e;
 }
 hipError_t mar_split_prepare() {
-  hipError_t e = sp_prepare<8, 13, 1>();
-  if (e == hipSuccess) e = sp_prepare<8, 16, 1>();
-  if (e == hipSuccess) e = sp_prepare<13, 25, 1>();
+  hipError_t e = sp_prepare<8, 13, 1, 1>();
+  if (e == hipSuccess) e = sp_prepare<8, 16, 1, 1>();
+  if (e == hipSuccess) e = sp_prepare<13, 25, 1, 2>();
   return e;
 }
 
-template <int NS, int NCB, int XB>
+template <int NS, int NCB, int XB, int CSP>
 static hipError_t sp_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
-  constexpr size_t lds = SplitGeom<NS>::LDS_BYTES + 2 * SP_TY * 4;
-  if (pass == 1) hipLaunchKernelGGL((k_split<NS, NCB, XB, 1>), grid, dim3(256), lds, st, a);
-  else hipLaunchKernelGGL((k_split<NS, NCB, XB, 2>), grid, dim3(256), lds, st, a);
+  constexpr size_t lds = sp_lds<NS, CSP>();
+  if (pass == 1) hipLaunchKernelGGL((k_split<NS, NCB, XB, 1, CSP>), grid, dim3(256 * CSP), lds, st, a);
+  else hipLaunchKernelGGL((k_split<NS, NCB, XB, 2, CSP>), grid, dim3(256 * CSP), lds, st, a);
   return hipGetLastError();
 }
 
@@ -432,8 +467,8 @@ hipError_t mar_split_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t
 
 static hipError_t sp_launch_sized(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
   const int ns = sp_ns(a.dk), ncb = sp_ncb(a.dk);
-  if (ns == 2) return sp_launch<2, 4, 2>(a, pass, grid, st);
-  if (ns == 4) return ncb == 7 ? sp_launch<4, 7, 2>(a, pass, grid, st) : sp_launch<4, 8, 2>(a, pass, grid, st);
-  if (ns == 8) return ncb == 13 ? sp_launch<8, 13, 1>(a, pass, grid, st) : sp_launch<8, 16, 1>(a, pass, grid, st);
-  return sp_launch<13, 25, 1>(a, pass, grid, st);
+  if (ns == 2) return sp_launch<2, 4, 2, 1>(a, pass, grid, st);
+  if (ns == 4) return ncb == 7 ? sp_launch<4, 7, 2, 1>(a, pass, grid, st) : sp_launch<4, 8, 2, 1>(a, pass, grid, st);
+  if (ns == 8) return ncb == 13 ? sp_launch<8, 13, 1, 1>(a, pass, grid, st) : sp_launch<8, 16, 1, 1>(a, pass, grid, st);
+  return sp_launch<13, 25, 1, 2>(a, pass, grid, st);
 }
