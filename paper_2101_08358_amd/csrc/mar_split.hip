@@ -40,13 +40,18 @@ __device__ __forceinline__ v4f mfma_bf(v8bf a, v8bf b, v4f c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// v = hi + lo, both bf16 (round to nearest even)
+// v = hi + lo, both bf16 (round to nearest even); converted two at a time (one packed conversion per pair)
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void split8(const float (&v)[8], v8bf& hi, v8bf& lo) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const __bf16 h = (__bf16)v[i];
-    hi[i] = h;
-    lo[i] = (__bf16)(v[i] - (float)h);
+  for (int i = 0; i < 8; i += 2) {
+    const v2f p = {v[i], v[i + 1]};
+    const v2bf h = __builtin_convertvector(p, v2bf);
+    const v2f r = p - __builtin_convertvector(h, v2f);
+    const v2bf l = __builtin_convertvector(r, v2bf);
+    hi[i] = h[0]; hi[i + 1] = h[1];
+    lo[i] = l[0]; lo[i + 1] = l[1];
   }
 }
 
@@ -317,9 +322,15 @@ k_split(FlashArgs a) {
 #pragma unroll
       for (int yb = 0; yb < 2; ++yb) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          sc[4 * yb + r] = sacc[yb][b][r];
-          if (masked && y0 + 16 * yb + 4 * g + r >= n_y) sc[4 * yb + r] = -__builtin_inff();
+        for (int r = 0; r < 4; ++r) sc[4 * yb + r] = sacc[yb][b][r];
+      }
+      if (masked) {                                        // the chunk's last, partial tile (uniform): rows beyond it weigh nothing
+#pragma unroll
+        for (int yb = 0; yb < 2; ++yb) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (y0 + 16 * yb + 4 * g + r >= n_y) sc[4 * yb + r] = -__builtin_inff();
+          }
         }
       }
       if (PASS == 1) {
