@@ -5,14 +5,17 @@
 //     a_hi b_hi + a_lo b_hi + a_hi b_lo
 // on the bf16 matrix pipe (v_mfma_f32_16x16x32_bf16, fp32 accumulation), which runs at 16 times the fp32 matrix
 // rate.  The dropped term a_lo b_lo and the rounding of the lo parts are of relative size 2^-16 .. 2^-17 per
-// product, far inside the 1e-4 bars of the step.  The passes compute what k_flash / k_flash_bwd compute, in the
-// same formats (softmax statistics, weights T, references R, gradient rows), so everything around them is shared.
+// product, far inside the 1e-4 bars of the step.  The passes write what k_flash / k_flash_bwd write (softmax
+// statistics, unnormalised operand gradients, gradient rows of the negatives), so everything around them is shared;
+// they keep no weights between them (pass 2 computes the scores again, see k_split).
 //
-// Operand images.  The streamed matrix of a pass (pass 1: the chunk's negatives, pass 2: the chunk's edge-side
-// operands) is prepared once per step as "images": per chunk-side and tile of 32 rows a hi plane and a lo plane,
-// [32][PA bytes] each, row = 32 NS bf16 values (the row padded with zeros to a multiple of 32 columns) at a pitch
-// PA chosen so that both kinds of LDS read below are free of bank conflicts.  An image is one contiguous block
-// and is copied into LDS by buffer loads that write LDS directly, one tile ahead, in two alternating buffers.
+// Operand images (mar_split.h).  The gather writes both operand matrices (the chunk's negatives, the chunk's
+// edge-side operands) as "images": per chunk-side and tile of 32 rows a hi plane and a lo plane, [32][PA bytes] each,
+// row = 32 NS bf16 values (the row padded with zeros to a multiple of 32 columns) at a pitch PA chosen so that both
+// kinds of LDS read below are free of bank conflicts.  An image is one contiguous block; the images of the matrix a
+// pass streams (pass 1: the negatives, pass 2: the edge-side operands) are copied into LDS by buffer loads that
+// write LDS directly, one tile ahead, in two alternating buffers; the stationary rows' fragments are read from
+// their own images once.
 //
 // Lane layouts (lane = 16 g + m):
 //   v_mfma_f32_16x16x32_bf16: A lane holds row m, contraction slots 8g .. 8g+7; B lane holds column m, the same

@@ -28,7 +28,8 @@ def test_one_step_matches_oracle(model, shape):
     print(check_step(out), flush=True)
 
 
-@pytest.mark.parametrize("model,dim", ((DISTMULT, 400), (COMPLEX, 200), (DISTMULT, 36), (DISTMULT, 17), (COMPLEX, 128), (DOT, 100), (DISTMULT, 256)))
+@pytest.mark.parametrize("model,dim", ((DISTMULT, 400), (COMPLEX, 200), (DISTMULT, 36), (DISTMULT, 17), (COMPLEX, 128), (DOT, 100), (DISTMULT, 256),
+                                       (DISTMULT, 144), (COMPLEX, 300), (DOT, 268)))
 def test_one_step_other_widths(model, dim):
     print("case", model, dim, flush=True)
     out = run_step_both(model, 4000, 11, dim, 512, 4, 200, 512, seed=7 + dim, precision=SPLIT)
@@ -56,6 +57,12 @@ def test_empty_batch_is_a_no_op():
 
 def test_narrowest_rows():
     out = run_step_both(DOT, 600, 1, 4, 256, 2, 64, 256, seed=2, std=0.3, precision=SPLIT)
+    print(check_step(out), flush=True)
+
+
+def test_ragged_chunks_at_the_widest_rows():
+    """Short last chunk, chunk size and negatives not multiples of the tile, with two waves sharing each row block."""
+    out = run_step_both(DISTMULT, 3000, 5, 400, 600, 3, 130, 470, seed=31, precision=SPLIT)
     print(check_step(out), flush=True)
 
 
