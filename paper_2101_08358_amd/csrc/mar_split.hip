@@ -123,21 +123,20 @@ __device__ __forceinline__ void second_product(const char* hi, const char* lo, i
 // on with the same scores, weights and softmax statistics) and half of the second product's output blocks.  A wave
 // then holds half of the stationary fragments and half of the accumulators, and a workgroup of eight waves puts two
 // waves on every SIMD where the four-wave form has registers for one.
-template <int NS, int NCB, int XB, int PASS, int CSP>
-__global__ void __launch_bounds__(256 * CSP) MAR_WAVES_PER_SIMD((CSP == 2 || NS <= 8 ? 2 : 1))
+template <int NS, int NCB, int XB, int PASS, int CSP, int NW>
+__global__ void __launch_bounds__(64 * NW) MAR_WAVES_PER_SIMD((NW == 8 || NS <= 8 ? 2 : 1))
 k_split(FlashArgs a) {
   typedef SplitGeom<NS> SG;
   constexpr int PA = SG::PA, PLANE = SG::PLANE, IMG = SG::IMG;
   constexpr int TY = SP_TY;
-  constexpr int SR = 64 * XB;
-  constexpr int NW = 4 * CSP;                              // waves
+  constexpr int SR = (NW / CSP) * XB * 16;                 // stationary rows per workgroup
   constexpr int NSA = (NS + CSP - 1) / CSP, NCBA = (NCB + CSP - 1) / CSP;   // steps and output blocks per wave
   constexpr int NCW = (SG::NCH + NW - 1) / NW;             // 1 KB pieces of an image per wave
   constexpr float LOG2E = 1.44269504088896341f;
-  static_assert(CSP == 1 || XB == 1, "the exchange of partial scores is written for one row block per wave");
+  static_assert(SR == 64 * (NS <= 4 ? 2 : 1), "stripe rows the launch planning assumes");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   float* const aux_all = reinterpret_cast<float*>(smem + 2 * IMG);   // PASS 2: [2][TY] log-sum-exp of the tile's edges
-  float* const xch = aux_all + 2 * TY;                     // CSP = 2: [NW][8][64] partial scores
+  float* const xch = aux_all + 2 * TY;                     // CSP = 2: [NW][8 XB][64] partial scores
 
   const int lane = threadIdx.x & 63, wave_all = threadIdx.x >> 6;
   const int wave = wave_all / CSP, half = wave_all % CSP;  // row block of the workgroup, half of the columns
@@ -297,18 +296,24 @@ k_split(FlashArgs a) {
       }
     }
     if (CSP == 2) {                                        // add the other half's partial scores
-      float* mine = xch + (wave_all * 8) * 64 + lane;
+      float* mine = xch + (wave_all * 8 * XB) * 64 + lane;
 #pragma unroll
-      for (int yb = 0; yb < 2; ++yb) {
+      for (int b = 0; b < XB; ++b) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mine[(4 * yb + r) * 64] = sacc[yb][0][r];
+        for (int yb = 0; yb < 2; ++yb) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) mine[(8 * b + 4 * yb + r) * 64] = sacc[yb][b][r];
+        }
       }
       __syncthreads();
-      const float* other = xch + ((wave_all ^ 1) * 8) * 64 + lane;
+      const float* other = xch + ((wave_all ^ 1) * 8 * XB) * 64 + lane;
 #pragma unroll
-      for (int yb = 0; yb < 2; ++yb) {
+      for (int b = 0; b < XB; ++b) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sacc[yb][0][r] += other[(4 * yb + r) * 64];
+        for (int yb = 0; yb < 2; ++yb) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) sacc[yb][b][r] += other[(8 * b + 4 * yb + r) * 64];
+        }
       }
     }
     // -- weights of the lane's 8 pairs per x-block: slot kk <-> y = y0 + (kk < 4 ? 4g + kk : 16 + 4g + kk - 4)
@@ -431,6 +436,13 @@ __global__ void __launch_bounds__(256) k_split_merge2(FlashArgs a, int stripe_ro
 }
 
 // ------------------------------------------------------------------- launchers -----
+// Form of the widest instantiation (d > 256): row blocks per wave and waves per workgroup (two waves share a block).
+#ifndef SP_WIDE_XB
+#define SP_WIDE_XB 1
+#endif
+#ifndef SP_WIDE_NW
+#define SP_WIDE_NW 8
+#endif
 int mar_split_supported(int dk) { return dk >= 4 && dk <= 400; }
 int mar_split_stripe_rows(int dk, int pass) { (void)pass; return sp_ns(dk) <= 4 ? 128 : 64; }
 int mar_split_tile_rows() { return SP_TY; }
@@ -438,32 +450,32 @@ int mar_split_wgs_per_cu(int dk, int pass) { (void)pass; return sp_ns(dk) <= 8 ?
 size_t mar_split_image_bytes(int dk) { return (size_t)sp_image(sp_ns(dk)); }
 
 // LDS of a launch: two image buffers, the log-sum-exp of a tile's edges (pass 2), the exchange area (CSP = 2)
-template <int NS, int CSP>
-constexpr size_t sp_lds() { return SplitGeom<NS>::LDS_BYTES + 2 * SP_TY * 4 + (CSP == 2 ? 8 * 8 * 64 * 4 : 0); }
+template <int NS, int XB, int CSP, int NW>
+constexpr size_t sp_lds() { return SplitGeom<NS>::LDS_BYTES + 2 * SP_TY * 4 + (CSP == 2 ? NW * 8 * XB * 64 * 4 : 0); }
 
-template <int NS, int NCB, int XB, int CSP>
+template <int NS, int NCB, int XB, int CSP, int NW>
 static hipError_t sp_prepare() {
-  constexpr size_t lds = sp_lds<NS, CSP>();
+  constexpr size_t lds = sp_lds<NS, XB, CSP, NW>();
   hipError_t e = hipSuccess;
   if (lds > 64 * 1024) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 1, CSP>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 1, CSP, NW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 2, CSP>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_split<NS, NCB, XB, 2, CSP, NW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   }
   return e;
 }
 hipError_t mar_split_prepare() {
-  hipError_t e = sp_prepare<8, 13, 1, 1>();
-  if (e == hipSuccess) e = sp_prepare<8, 16, 1, 1>();
-  if (e == hipSuccess) e = sp_prepare<13, 25, 1, 2>();
+  hipError_t e = sp_prepare<8, 13, 1, 1, 4>();
+  if (e == hipSuccess) e = sp_prepare<8, 16, 1, 1, 4>();
+  if (e == hipSuccess) e = sp_prepare<13, 25, SP_WIDE_XB, 2, SP_WIDE_NW>();
   return e;
 }
 
-template <int NS, int NCB, int XB, int CSP>
+template <int NS, int NCB, int XB, int CSP, int NW>
 static hipError_t sp_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
-  constexpr size_t lds = sp_lds<NS, CSP>();
-  if (pass == 1) hipLaunchKernelGGL((k_split<NS, NCB, XB, 1, CSP>), grid, dim3(256 * CSP), lds, st, a);
-  else hipLaunchKernelGGL((k_split<NS, NCB, XB, 2, CSP>), grid, dim3(256 * CSP), lds, st, a);
+  constexpr size_t lds = sp_lds<NS, XB, CSP, NW>();
+  if (pass == 1) hipLaunchKernelGGL((k_split<NS, NCB, XB, 1, CSP, NW>), grid, dim3(64 * NW), lds, st, a);
+  else hipLaunchKernelGGL((k_split<NS, NCB, XB, 2, CSP, NW>), grid, dim3(64 * NW), lds, st, a);
   return hipGetLastError();
 }
 
@@ -481,8 +493,8 @@ hipError_t mar_split_launch(const FlashArgs& a, int pass, dim3 grid, hipStream_t
 
 static hipError_t sp_launch_sized(const FlashArgs& a, int pass, dim3 grid, hipStream_t st) {
   const int ns = sp_ns(a.dk), ncb = sp_ncb(a.dk);
-  if (ns == 2) return sp_launch<2, 4, 2, 1>(a, pass, grid, st);
-  if (ns == 4) return ncb == 7 ? sp_launch<4, 7, 2, 1>(a, pass, grid, st) : sp_launch<4, 8, 2, 1>(a, pass, grid, st);
-  if (ns == 8) return ncb == 13 ? sp_launch<8, 13, 1, 1>(a, pass, grid, st) : sp_launch<8, 16, 1, 1>(a, pass, grid, st);
-  return sp_launch<13, 25, 1, 2>(a, pass, grid, st);
+  if (ns == 2) return sp_launch<2, 4, 2, 1, 4>(a, pass, grid, st);
+  if (ns == 4) return ncb == 7 ? sp_launch<4, 7, 2, 1, 4>(a, pass, grid, st) : sp_launch<4, 8, 2, 1, 4>(a, pass, grid, st);
+  if (ns == 8) return ncb == 13 ? sp_launch<8, 13, 1, 1, 4>(a, pass, grid, st) : sp_launch<8, 16, 1, 1, 4>(a, pass, grid, st);
+  return sp_launch<13, 25, SP_WIDE_XB, 2, SP_WIDE_NW>(a, pass, grid, st);
 }
