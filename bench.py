@@ -270,8 +270,11 @@ def run_workload(name, steps, warmup, edges=0, nodes=0, phase_events=True, cpu_b
         torch.cuda.synchronize()
         pm2, pst2 = mar.mar_profile_read(tr2.ctx)
         mar.mar_profile_enable(tr2.ctx, 0, 0)
+        roof2 = contraction_roofline(fp2, ps2, pe2, True)
+        if not nodes:
+            roof2["traffic"] = measured_traffic(w.name + "_split").get("k_split") or None
         rec["split_bf16"] = {"value": done2 / el2, "unit": "edges/s", "steps": steps, "ms_per_step": el2 / steps * 1e3,
-                             "dtype": SPLIT_DTYPE, "roofline": contraction_roofline(fp2, ps2, pe2, True),
+                             "dtype": SPLIT_DTYPE, "roofline": roof2,
                              "phases_us_per_step": {nm: round(ms / max(pst2, 1) * 1e3, 2) for nm, ms in zip(mar.binding.PHASE_NAMES, pm2)},
                              "final_loss_per_edge": float(tr2.loss.item()) / last_batch_edges,
                              "speedup_over_f32": (done2 / el2) / (edges_done / elapsed)}
