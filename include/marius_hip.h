@@ -66,6 +66,8 @@ typedef struct mar_config {
   int32_t  num_chunks;          /* the batch is cut into this many contiguous chunks;                */
                                 /* batch_size must be a multiple of num_chunks                       */
   int32_t  negs_per_chunk;      /* n_t: negatives per chunk and corrupted side, shared by the chunk  */
+                                /* (one chunk's rows x dim x 4 bytes, and chunk edges x n_t x 4 bytes,   */
+                                /* must stay below 2^31: MAR_ERANGE otherwise)                           */
   int32_t  deg_negs_per_chunk;  /* round(alpha_nt * n_t): how many of them are drawn by degree       */
   float    lr;                  /* Adagrad learning rate                                             */
   float    eps;                 /* Adagrad epsilon, added outside the square root                    */

@@ -73,6 +73,16 @@ static int check_config(const mar_config* cfg, MarDims* d) {
   if (!mar_flash_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the contraction kernels", d->dk);
   d->split = cfg->precision == MAR_PRECISION_SPLIT_BF16;
   if (d->split && !mar_split_supported(d->dk)) return fail(MAR_ERANGE, "row width %d not supported by the split-precision kernels", d->dk);
+  // The contraction kernels address one chunk-side's rows of either operand, and its block of weights, with 32-bit
+  // byte offsets.
+  {
+    const int64_t rows = d->S > d->N ? d->S : d->N;
+    const int64_t tp = (d->N + 127) & ~(int64_t)127, tr_ = (d->S + 63) & ~(int64_t)63;
+    if (rows * d->dk * 4 >= ((int64_t)1 << 31) || tp * tr_ * 4 >= ((int64_t)1 << 31))
+      return fail(MAR_ERANGE, "chunk too large: rows x row bytes of a chunk's edges or negatives, and chunk edges x negatives x 4, must be below 2^31");
+    if (d->split && ((rows + 31) / 32) * (int64_t)mar_split_image_bytes(d->dk) >= ((int64_t)1 << 31))
+      return fail(MAR_ERANGE, "chunk too large for the split-precision operand images (2^31 bytes per chunk and side)");
+  }
   const int sp = d->split;
   auto stripe_rows = [&](int pass) { return sp ? mar_split_stripe_rows(d->dk, pass) : mar_flash_stripe_rows(d->dk, pass); };
   auto tile_rows = [&](int pass) { return sp ? mar_split_tile_rows() : mar_flash_tile_rows(d->dk, pass); };

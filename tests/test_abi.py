@@ -57,7 +57,9 @@ def test_workspace_bytes_scales_and_validates(lib):
                       (dict(batch_size=101), -2), (dict(num_chunks=0), -1), (dict(deg_negs_per_chunk=21), -1),
                       (dict(num_nodes=(1 << 31) - 2), -2), (dict(lr=0.0), -1), (dict(num_rels=0), -1),
                       (dict(precision=2), -1), (dict(precision=-1), -1), (dict(precision=1, model=2), -1),
-                      (dict(reserved=1), -1)):
+                      (dict(reserved=1), -1),
+                      (dict(batch_size=40_000_000, num_chunks=1, negs_per_chunk=100, dim=400), -2),     # 64 GB of rows in one chunk
+                      (dict(batch_size=30_000, num_chunks=1, negs_per_chunk=30_000, dim=8), -2)):        # 3.6 GB of pair weights in one chunk
         with pytest.raises(mar.MarError) as e:
             mar.mar_workspace_bytes(_cfg(**bad))
         assert e.value.code == code, bad
