@@ -163,7 +163,7 @@ def check_step(out, rel=REL, max_flip_frac=1e-4, row_rel=None):
     return rep
 
 
-def run_step_device_tables(model, num_nodes, num_rels, dim, B, C, N, ids, seed=0, lr=0.1, eps=1e-10, std=0.001):
+def run_step_device_tables(model, num_nodes, num_rels, dim, B, C, N, ids, seed=0, lr=0.1, eps=1e-10, std=0.001, precision=0):
     """One step on tables that are too large to build on the host: the seeded input generator builds them
     on the device, the touched rows are copied out, and the oracle runs on a compact copy with remapped
     ids (the step only depends on touched rows).  Returns the same dict as run_step_both, with tables
@@ -172,7 +172,7 @@ def run_step_device_tables(model, num_nodes, num_rels, dim, B, C, N, ids, seed=0
     src, rel, dst, neg_src, neg_dst = ids
     n = src.shape[0]
     d_ne, d_re = synth.make_tables(num_nodes, num_rels, dim, std, seed=seed, device="cuda:0")
-    tr = mar.Trainer(num_nodes, num_rels, dim, model, B, C, N, 0, lr, eps, std, seed, node_emb=d_ne, rel_emb=d_re)
+    tr = mar.Trainer(num_nodes, num_rels, dim, model, B, C, N, 0, lr, eps, std, seed, node_emb=d_ne, rel_emb=d_re, precision=precision)
     dev = tr.device
     nch = (n + B // C - 1) // (B // C)
     uniq_n = np.unique(np.concatenate([src, dst, neg_src[:nch].ravel(), neg_dst[:nch].ravel()]))

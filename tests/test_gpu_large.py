@@ -54,14 +54,15 @@ def test_large_id_space_bitmap_index_and_hot_rows():
     print(check_step(out, max_flip_frac=1e-3), flush=True)
 
 
-@pytest.mark.parametrize("model", (0, 1))
-def test_social_shape_batch_on_a_41m_row_table(model):
+@pytest.mark.parametrize("model,precision", ((0, 0), (1, 0), (0, 1), (1, 1)))
+def test_social_shape_batch_on_a_41m_row_table(model, precision):
     """Batch geometry of the social / large-KG workloads (50,000 edges, 50 chunks x 1,000 negatives, d = 100)
-    on a 41.6 M-row table (16.6 GB per table, row offsets beyond 2^31 bytes)."""
+    on a 41.6 M-row table (16.6 GB per table, row offsets beyond 2^31 bytes); precision 1: the split-precision
+    contraction in the launch configuration bench.py times (both passes split their last round)."""
     rng = np.random.default_rng(11 + model)
     V, R, dim, B, C, N = 41_600_000, (1 if model == 0 else 1000), 100, 50_000, 50, 1_000
     ids = _hot_ids(rng, V, R, B, C, N, 0.3)
-    out = run_step_device_tables(model, V, R, dim, B, C, N, ids, seed=5)
+    out = run_step_device_tables(model, V, R, dim, B, C, N, ids, seed=5, precision=precision)
     assert out["gpu"]["untouched_ok"]
     print(check_step(out, max_flip_frac=1e-3), flush=True)
 
@@ -93,12 +94,14 @@ def test_large_kg_shape_with_degree_negatives_on_86m_rows():
     print(check_step(out, max_flip_frac=1e-3), flush=True)
 
 
-def test_wide_workload_full_size_160gb():
+@pytest.mark.parametrize("precision", (0, 1))
+def test_wide_workload_full_size_160gb(precision):
     """The wide-embedding workload at full size: 50 M nodes x 400 floats (80 GB of embeddings + 80 GB of
-    accumulators), 100,000 edges, 100 chunks x 1,000 negatives."""
+    accumulators), 100,000 edges, 100 chunks x 1,000 negatives; in fp32 and in split precision."""
     w = synth.get_workload("wide")
     rng = np.random.default_rng(21)
     ids = _hot_ids(rng, w.num_nodes, w.num_rels, w.batch_size, w.num_chunks, w.negs_per_chunk, 0.1)
-    out = run_step_device_tables(w.model, w.num_nodes, w.num_rels, w.dim, w.batch_size, w.num_chunks, w.negs_per_chunk, ids, seed=4)
+    out = run_step_device_tables(w.model, w.num_nodes, w.num_rels, w.dim, w.batch_size, w.num_chunks, w.negs_per_chunk, ids, seed=4,
+                                 precision=precision)
     assert out["gpu"]["untouched_ok"]
     print(check_step(out, max_flip_frac=1e-3), flush=True)
