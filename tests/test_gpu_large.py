@@ -67,7 +67,8 @@ def test_social_shape_batch_on_a_41m_row_table(model, precision):
     print(check_step(out, max_flip_frac=1e-3), flush=True)
 
 
-def test_large_kg_shape_with_degree_negatives_on_86m_rows():
+@pytest.mark.parametrize("precision", (0, 1))
+def test_large_kg_shape_with_degree_negatives_on_86m_rows(precision):
     """Geometry of the large-KG workload: 86.1 M nodes, 14,824 relations, ComplEx d = 100 (69 GB of tables and
     accumulators), 50,000 edges, 50 chunks x 1,000 negatives of which 500 are drawn by degree through the
     library's sampler from a power-law edge list (bit-exact against the oracle's sampler), then one step."""
@@ -89,7 +90,7 @@ def test_large_kg_shape_with_degree_negatives_on_86m_rows():
     assert np.array_equal(ns, ons) and np.array_equal(nd, ond)
     b = w.batch_size
     out = run_step_device_tables(w.model, w.num_nodes, w.num_rels, w.dim, b, w.num_chunks, w.negs_per_chunk,
-                                 (es[:b].copy(), er[:b].copy(), ed[:b].copy(), ons, ond), seed=2)
+                                 (es[:b].copy(), er[:b].copy(), ed[:b].copy(), ons, ond), seed=2, precision=precision)
     assert out["gpu"]["untouched_ok"]
     print(check_step(out, max_flip_frac=1e-3), flush=True)
 
