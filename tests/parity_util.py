@@ -103,7 +103,7 @@ def check_step(out, rel=REL, max_flip_frac=1e-4, row_rel=None):
     # TransE at distance 0) are left to the tensor-wide bar above.
     rep["G_row"] = 0.0
     for g_gpu, g_or in ((gpu["G"][:un], res.G_nodes), (gpu["G"][un:], res.G_rels)):
-        if g_or.size == 0:
+        if g_or.size == 0 or not np.any(g_or):            # nothing to compare row by row (e.g. Dot: no relation gradient)
             continue
         rowmax = np.max(np.abs(g_or), axis=1)
         keep = rowmax >= ROW_FLOOR * rowmax.max()
