@@ -98,6 +98,28 @@ def test_degenerate_cases():
     check_step(out)
 
 
+def test_many_contexts_created_and_destroyed():
+    """Every context owns a stream and a few events: creating and destroying many in a row, in both precisions and with
+    a step in between, must leave nothing behind and keep giving the same step."""
+    import paper_2101_08358_amd as mar
+    rng = np.random.default_rng(0)
+    ne = (rng.standard_normal((300, 32)) * 0.1).astype(np.float32)
+    re_ = (rng.standard_normal((2, 32)) * 0.1).astype(np.float32)
+    ids = [torch.from_numpy(rng.integers(0, hi, 64).astype(np.int32)).cuda() for hi in (300, 2, 300)]
+    want = {}
+    for i in range(120):
+        precision = i % 2
+        tr = mar.Trainer(300, 2, 32, DISTMULT, 64, 2, 16, seed=1, node_emb=ne, rel_emb=re_, precision=precision)
+        tr.sample_negatives(0)
+        tr.train_batch(*ids)
+        torch.cuda.synchronize()
+        got = (tr.node_emb.clone(), float(tr.loss.item()))
+        tr.close()
+        if precision not in want:
+            want[precision] = got
+        assert got[1] == want[precision][1] and torch.equal(got[0], want[precision][0])
+
+
 def test_empty_batch_is_a_no_op():
     import paper_2101_08358_amd as mar
     tr = mar.Trainer(100, 2, 16, DISTMULT, 64, 2, 8, seed=3)
